@@ -1,0 +1,195 @@
+"""CPU oracle for the local kernels of PCCL's hierarchical collectives.
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the
+benchmark's CPU-baseline leg.  The product path (the HIP library and its
+Python binding) never imports this package, and this package never imports
+the product.
+
+All arithmetic lives in pccl_oracle.c; this module only marshals numpy arrays.
+bf16 data is carried as numpy uint16 bit patterns, fp32 data as numpy float32.
+"""
+import ctypes
+import os
+
+import numpy as np
+
+from . import build as _build
+
+F32 = 0
+BF16 = 1
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        L = ctypes.CDLL(_build.build())
+        vp, i, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+        L.pccl_oracle_f32_to_bf16.restype = ctypes.c_uint16
+        L.pccl_oracle_f32_to_bf16.argtypes = [ctypes.c_uint32]
+        L.pccl_oracle_f32_to_bf16_array.restype = None
+        L.pccl_oracle_f32_to_bf16_array.argtypes = [vp, vp, sz]
+        L.pccl_oracle_flat_reduce.argtypes = [vp, vp, i, sz, i, i, i]
+        L.pccl_oracle_two_level_reduce.argtypes = [vp, vp, vp, i, i, sz, i, i, i]
+        L.pccl_oracle_rs_phase1.argtypes = [vp, vp, i, i, sz, i, i]
+        L.pccl_oracle_rs_phase2.argtypes = [vp, vp, i, sz, i, i, i]
+        L.pccl_oracle_hier_pack.argtypes = [vp, vp, i, i, sz]
+        L.pccl_oracle_hier_unpack.argtypes = [vp, vp, i, i, sz]
+        L.pccl_oracle_allgather_reassemble.argtypes = [vp, vp, i, i, sz]
+        _lib = L
+    return _lib
+
+
+def _dt(a):
+    if a.dtype == np.float32:
+        return F32
+    if a.dtype == np.uint16:
+        return BF16
+    raise TypeError("oracle takes float32 (fp32) or uint16 (bf16 bits) arrays, got %s" % a.dtype)
+
+
+def _np_dtype(code):
+    return np.float32 if code == F32 else np.uint16
+
+
+def _flat(a):
+    a = np.ascontiguousarray(a)
+    return a.reshape(-1)
+
+
+def _ptr_array(arrs):
+    arr = (ctypes.c_void_p * len(arrs))()
+    for k, a in enumerate(arrs):
+        arr[k] = a.ctypes.data
+    return arr
+
+
+def _check(rc, what):
+    if rc != 0:
+        raise ValueError("oracle %s: bad argument (rc=%d)" % (what, rc))
+
+
+def f32_to_bf16(x):
+    """Round float32 values to bf16 bit patterns (round to nearest, ties to even)."""
+    x = _flat(np.asarray(x, dtype=np.float32))
+    out = np.empty(x.shape, dtype=np.uint16)
+    lib().pccl_oracle_f32_to_bf16_array(out.ctypes.data, x.ctypes.data, x.size)
+    return out
+
+
+def bf16_to_f32(bits):
+    """Widen bf16 bit patterns to float32 (exact)."""
+    bits = np.asarray(bits, dtype=np.uint16)
+    return (bits.astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+def flat_reduce(srcs, out_dt=None, nthreads=1):
+    """out[e] = ((x0[e] + x1[e]) + ...) in fp32, sources in the order given."""
+    srcs = [_flat(s) for s in srcs]
+    in_dt = _dt(srcs[0])
+    out_dt = in_dt if out_dt is None else out_dt
+    count = srcs[0].size
+    assert all(s.size == count and _dt(s) == in_dt for s in srcs)
+    out = np.empty(count, dtype=_np_dtype(out_dt))
+    rc = lib().pccl_oracle_flat_reduce(out.ctypes.data, _ptr_array(srcs), len(srcs), count,
+                                       in_dt, out_dt, nthreads)
+    _check(rc, "flat_reduce")
+    return out
+
+
+def two_level_reduce(srcs, nodes, gpus, out_dt=None, want_partials=False, nthreads=1):
+    """Two-level sum of nodes*gpus sources given node-major (srcs[n*gpus+g])."""
+    srcs = [_flat(s) for s in srcs]
+    assert len(srcs) == nodes * gpus
+    in_dt = _dt(srcs[0])
+    out_dt = in_dt if out_dt is None else out_dt
+    count = srcs[0].size
+    assert all(s.size == count and _dt(s) == in_dt for s in srcs)
+    out = np.empty(count, dtype=_np_dtype(out_dt))
+    partials = np.empty((nodes, count), dtype=_np_dtype(in_dt)) if want_partials else None
+    rc = lib().pccl_oracle_two_level_reduce(
+        out.ctypes.data, partials.ctypes.data if want_partials else None, _ptr_array(srcs),
+        nodes, gpus, count, in_dt, out_dt, nthreads)
+    _check(rc, "two_level_reduce")
+    return (out, partials) if want_partials else out
+
+
+def rs_phase1(pieces, nodes, chunk, nthreads=1):
+    """partial[n][e] = round_io(sum over g of pieces[g][n][e]); pieces[g] is [nodes][chunk]."""
+    pieces = [_flat(p) for p in pieces]
+    io_dt = _dt(pieces[0])
+    assert all(p.size == nodes * chunk and _dt(p) == io_dt for p in pieces)
+    partial = np.empty((nodes, chunk), dtype=_np_dtype(io_dt))
+    rc = lib().pccl_oracle_rs_phase1(partial.ctypes.data, _ptr_array(pieces), nodes, len(pieces),
+                                     chunk, io_dt, nthreads)
+    _check(rc, "rs_phase1")
+    return partial
+
+
+def rs_phase2(inter, out_dt=None, nthreads=1):
+    """shard[e] = round_out(sum over n of inter[n][e])."""
+    inter = [_flat(c) for c in inter]
+    io_dt = _dt(inter[0])
+    out_dt = io_dt if out_dt is None else out_dt
+    chunk = inter[0].size
+    shard = np.empty(chunk, dtype=_np_dtype(out_dt))
+    rc = lib().pccl_oracle_rs_phase2(shard.ctypes.data, _ptr_array(inter), len(inter), chunk,
+                                     io_dt, out_dt, nthreads)
+    _check(rc, "rs_phase2")
+    return shard
+
+
+def reduce_scatter_local(x, my_node=0, inter=None, out_dt=None, nthreads=1):
+    """One GPU's share of a two-level reduce-scatter.
+
+    x: array [gpus][nodes][chunk] (piece g = what node-mate g sent).
+    inter: None -> the partial's own rows stand in for what every node sent;
+           else a list of `nodes` chunks, entry my_node is ignored and
+           partial[my_node] is used in its place.
+    Returns (shard, partial)."""
+    gpus, nodes, chunk = x.shape
+    partial = rs_phase1([x[g] for g in range(gpus)], nodes, chunk, nthreads)
+    if inter is None:
+        rows = [partial[n] for n in range(nodes)]
+    else:
+        rows = [partial[n] if n == my_node else inter[n] for n in range(nodes)]
+    shard = rs_phase2(rows, out_dt, nthreads)
+    return shard, partial
+
+
+def _bytes_view(a):
+    a = np.ascontiguousarray(a)
+    return a.reshape(-1).view(np.uint8)
+
+
+def hier_pack(src, nodes, gpus):
+    """[node][gpu][chunk] -> [gpu][node][chunk]; src is any contiguous array."""
+    s = _bytes_view(src)
+    assert s.size % (nodes * gpus) == 0
+    d = np.empty_like(s)
+    _check(lib().pccl_oracle_hier_pack(d.ctypes.data, s.ctypes.data, nodes, gpus,
+                                       s.size // (nodes * gpus)), "hier_pack")
+    return d.view(src.dtype).reshape(src.shape)
+
+
+def hier_unpack(src, nodes, gpus):
+    """[gpu][node][chunk] -> [node][gpu][chunk]."""
+    s = _bytes_view(src)
+    assert s.size % (nodes * gpus) == 0
+    d = np.empty_like(s)
+    _check(lib().pccl_oracle_hier_unpack(d.ctypes.data, s.ctypes.data, nodes, gpus,
+                                         s.size // (nodes * gpus)), "hier_unpack")
+    return d.view(src.dtype).reshape(src.shape)
+
+
+def allgather_reassemble(slots, nodes, gpus):
+    """slots[g*nodes+n] (one array per hierarchical slot) -> rank-order concatenation."""
+    assert len(slots) == nodes * gpus
+    views = [_bytes_view(s) for s in slots]
+    cb = views[0].size
+    assert all(v.size == cb for v in views)
+    d = np.empty(cb * len(views), dtype=np.uint8)
+    _check(lib().pccl_oracle_allgather_reassemble(d.ctypes.data, _ptr_array(views), nodes, gpus, cb),
+           "allgather_reassemble")
+    return d.view(slots[0].dtype)
