@@ -1,0 +1,171 @@
+/*
+ * pccl_local.h -- C ABI of libpccl_local.so: the on-GPU work one rank does inside the
+ * two-level (hierarchical) reduce-scatter, all-gather and all-reduce of PCCL
+ * ("The Big Send-off: Scalable and Performant Collectives for Deep Learning").
+ *
+ * The library covers the paper's two device-local kernels:
+ *   - the GPU vector-reduction kernel that sums received buffers into the owned shard
+ *     (Section III-B; Section IV-B, PCCL_ring / PCCL_rec), generalised to many sources;
+ *   - the device-local shuffle (a chunk transpose) between the two-level layout and
+ *     rank order (Section IV-A, step 3 of the hierarchical all-gather, and its inverse
+ *     for the reduce-scatter).
+ * Transport (MPI / RCCL messages) is not part of it: every buffer a rank would have
+ * received is simply a region of this GPU's memory.
+ *
+ * Vocabulary (Section IV-A): N = nodes, M = gpus_per_node, P = N*M ranks,
+ * rank r = n*M + g for node n and local id g.  A message of m bytes per rank is P chunks;
+ * "rank order" is [node][gpu][chunk], "hierarchical order" is [gpu][node][chunk].
+ *
+ * Common rules for every entry point
+ *   Pointers   All data pointers are DEVICE pointers (hipMalloc'ed memory of the current
+ *              device) unless a parameter is explicitly called "host".  Arrays of pointers
+ *              (d_srcs, d_inter, d_slots) and descriptor tables (d_buckets) are themselves
+ *              device-resident.
+ *   Ownership  The caller owns every buffer, scratch included.  The library allocates
+ *              nothing, frees nothing and keeps no pointer after the call returns.
+ *   Stream     Work is only enqueued on `stream` (a hipStream_t; NULL = the default
+ *              stream).  No call synchronises the device; results are valid once the
+ *              caller has synchronised the stream.
+ *   Errors     A status code is returned; nothing throws or aborts.  All argument checks
+ *              run on the host before the first HIP call, so a rejected call has no side
+ *              effect.  A failed launch is reported as PCCL_ERR_HIP.
+ *   Empty      count == 0 / chunk_bytes == 0 / chunk_count == 0 / nbuckets == 0 succeed
+ *              and launch nothing.
+ *   Alignment  Any element-aligned pointer is accepted.  Pointers, strides and chunk sizes
+ *              that are multiples of 16 bytes take the 128-bit path; others take a slower
+ *              element-wise path with identical results.
+ *   Aliasing   Outputs must not overlap inputs.  Where both ranges are visible to the
+ *              host (strided forms) an overlap is rejected with PCCL_ERR_OVERLAP; for
+ *              pointer-array forms it is undefined behaviour.
+ *   Arithmetic Every sum is accumulated in IEEE binary32 with round-to-nearest-even adds,
+ *              no FMA, no reassociation, subnormals kept; the accumulator starts from the
+ *              first source.  bf16 -> fp32 widening is exact; fp32 -> bf16 rounds to
+ *              nearest even (a NaN stays a quiet NaN of the same sign; its payload is
+ *              unspecified).  Results are therefore bit-reproducible.
+ */
+#ifndef PCCL_LOCAL_H
+#define PCCL_LOCAL_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  PCCL_OK = 0,
+  PCCL_ERR_NULL = 1,        /* a required pointer is NULL */
+  PCCL_ERR_INVALID = 2,     /* a count, stride, index or size is out of range or overflows */
+  PCCL_ERR_UNSUPPORTED = 3, /* unknown dtype / op */
+  PCCL_ERR_OVERLAP = 4,     /* an output range overlaps an input range */
+  PCCL_ERR_HIP = 5          /* the HIP runtime refused a launch */
+} pccl_status_t;
+
+typedef enum { PCCL_F32 = 0, PCCL_BF16 = 1 } pccl_dtype_t;
+typedef enum { PCCL_SUM = 0 } pccl_op_t; /* the paper's collectives are sums */
+typedef void* pccl_stream_t;             /* a hipStream_t */
+
+/* One bucket of a batched two-level reduce-scatter share (see
+ * pccl_reduce_scatter_local_batched).  All pointers are device pointers. */
+typedef struct {
+  void* shard;               /* out: [chunk_count] elements of io_dt                    */
+  void* partial;             /* out: [nodes][chunk_count] elements of io_dt             */
+  const void* intra_base;    /* in : piece g' at intra_base + g'*intra_stride_bytes,    */
+  size_t intra_stride_bytes; /*      each piece [nodes][chunk_count] elements of io_dt  */
+  size_t chunk_count;        /* elements per rank-chunk                                 */
+} pccl_bucket_t;
+
+/* Flat local reduce -- the GPU vector-reduction kernel of Sections III-B / IV-B applied to
+ * nsrc received buffers at once:
+ *     dst[e] = ((x_0[e] + x_1[e]) + x_2[e]) + ... + x_{nsrc-1}[e],   e in [0, count)
+ * with x_s = (const char*)src_base + s*src_stride_bytes holding `count` elements of in_dt,
+ * dst holding `count` elements of out_dt.  nsrc == 1 is a (converting) copy.
+ * src_stride_bytes must be >= count*sizeof(in_dt) when nsrc > 1 and a multiple of the
+ * element size.  Errors: NULL dst/src_base; nsrc < 1; size overflow; dst overlapping the
+ * source span. */
+pccl_status_t pccl_local_reduce(void* dst, const void* src_base, size_t src_stride_bytes,
+                                int nsrc, size_t count, pccl_dtype_t in_dt,
+                                pccl_dtype_t out_dt, pccl_op_t op, pccl_stream_t stream);
+
+/* The same flat sum with the sources given by a device array of nsrc device pointers
+ * (d_srcs[s] -> `count` elements of in_dt), summed in array order. */
+pccl_status_t pccl_local_reduce_ptrs(void* dst, const void* const* d_srcs, int nsrc,
+                                     size_t count, pccl_dtype_t in_dt, pccl_dtype_t out_dt,
+                                     pccl_op_t op, pccl_stream_t stream);
+
+/* Two-level sum over a node-major device pointer array, d_srcs[n*gpus_per_node + g] = the
+ * chunk contributed by rank (n, g) -- the whole local reduction of one shard of a two-level
+ * reduce-scatter / all-reduce (Section IV-A: intra-node phase, then inter-node phase):
+ *     t_n    = x[n][0] + x[n][1] + ... + x[n][M-1]        (left to right)
+ *     p_n    = t_n rounded through in_dt (identity for fp32 messages)
+ *     dst[e] = (p_0 + p_1) + ... + p_{N-1}                  (left to right), stored as out_dt
+ * Built for many small chunks (2048 ranks x 64 KB): the per-node sums run in parallel and
+ * are staged in LDS, the node order is kept. */
+pccl_status_t pccl_local_reduce_ptrs_two_level(void* dst, const void* const* d_srcs, int nodes,
+                                               int gpus_per_node, size_t count,
+                                               pccl_dtype_t in_dt, pccl_dtype_t out_dt,
+                                               pccl_op_t op, pccl_stream_t stream);
+
+/* Pre-shuffle of a reduce-scatter message (inverse of the all-gather shuffle of Section
+ * IV-A): rank order [node][gpu][chunk] -> hierarchical order [gpu][node][chunk],
+ *     dst chunk (g*N + n) = src chunk (n*M + g),  chunk_bytes bytes each.
+ * dst and src hold N*M*chunk_bytes bytes and must not overlap.  Pure byte movement. */
+pccl_status_t pccl_hier_pack(void* dst, const void* src, int nodes, int gpus_per_node,
+                             size_t chunk_bytes, pccl_stream_t stream);
+
+/* Step 3 of the hierarchical all-gather (Section IV-A, the device-local shuffle):
+ * hierarchical order [gpu][node][chunk] -> rank order [node][gpu][chunk],
+ *     dst chunk (n*M + g) = src chunk (g*N + n). */
+pccl_status_t pccl_hier_unpack(void* dst, const void* src, int nodes, int gpus_per_node,
+                               size_t chunk_bytes, pccl_stream_t stream);
+
+/* One GPU's share of a two-level reduce-scatter (Section IV-A: the mirror image of the
+ * two-level all-gather, intra-node phase first; reductions on the GPU, Section IV-B).
+ *   Phase 1: partial[n][e] = round_io( sum over g' = 0..M-1, in order, of piece_g'[n][e] )
+ *            piece_g' = intra_base + g'*intra_stride_bytes, [nodes][chunk_count] of io_dt:
+ *            what node-mate g' sent, i.e. its chunks bound for this local id on every node.
+ *   Phase 2: shard[e] = round_io( sum over n' = 0..N-1, in order, of inter_n'[e] )
+ *            inter_n' = what node n' sent for this node.
+ *            d_inter == NULL: inter_n' = partial[n'] (one GPU standing in for all nodes);
+ *            else d_inter is a device array of `nodes` device pointers to chunk_count
+ *            elements each; slot my_node is ignored and partial[my_node] is used.
+ * partial is caller-provided scratch/output: [nodes][chunk_count] of io_dt (it is the
+ * buffer that would go on the wire between the phases).  Two kernels are enqueued.
+ * Errors: NULLs; nodes/gpus < 1; my_node outside [0, nodes); stride < nodes*chunk bytes;
+ * shard or partial overlapping the intra span or each other. */
+pccl_status_t pccl_reduce_scatter_local(void* shard, void* partial, const void* intra_base,
+                                        size_t intra_stride_bytes, const void* const* d_inter,
+                                        int nodes, int gpus_per_node, int my_node,
+                                        size_t chunk_count, pccl_dtype_t io_dt, pccl_op_t op,
+                                        pccl_stream_t stream);
+
+/* The all-gather shuffle with the gathered chunks either contiguous in hierarchical order
+ * (d_slots == NULL, `src` used; identical to pccl_hier_unpack) or each in its own buffer
+ * (d_slots = device array of P device pointers indexed by hierarchical slot g*N + n, `src`
+ * ignored):  dst chunk (n*M + g) = slot (g*N + n). */
+pccl_status_t pccl_allgather_reassemble(void* dst, const void* src, const void* const* d_slots,
+                                        int nodes, int gpus_per_node, size_t chunk_bytes,
+                                        pccl_stream_t stream);
+
+/* nbuckets independent two-level reduce-scatter shares (pccl_reduce_scatter_local with
+ * d_inter == NULL) in one launch per phase -- the shape of the many reduce-scatters a
+ * ZeRO-3 / FSDP step issues (Section II-A, message-size figure).
+ * d_buckets: device array of nbuckets descriptors read by the kernels.
+ * h_buckets: HOST copy of the same descriptors, used only for argument checks and to size
+ * the launch; must be identical to d_buckets.  nodes, gpus_per_node and io_dt are common
+ * to the batch.  nbuckets <= PCCL_MAX_BUCKETS.  A bucket with chunk_count == 0 is skipped. */
+#define PCCL_MAX_BUCKETS 512
+pccl_status_t pccl_reduce_scatter_local_batched(const pccl_bucket_t* d_buckets,
+                                                const pccl_bucket_t* h_buckets, int nbuckets,
+                                                int nodes, int gpus_per_node,
+                                                pccl_dtype_t io_dt, pccl_op_t op,
+                                                pccl_stream_t stream);
+
+/* Static, human-readable name of a status code (never NULL). */
+const char* pccl_status_string(pccl_status_t status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PCCL_LOCAL_H */

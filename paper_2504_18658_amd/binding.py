@@ -1,0 +1,231 @@
+"""ctypes binding of libpccl_local.so: same entry points as include/pccl_local.h.
+
+Argument marshalling only -- tensors become device pointers, dtypes become enum codes, the
+current torch stream becomes the hipStream_t.  Every step of the path runs in the library's
+kernels; there is no fallback: if the library cannot be loaded or built, calls raise.
+"""
+import ctypes
+import os
+
+import torch
+
+from . import build as _build
+
+PCCL_OK, PCCL_ERR_NULL, PCCL_ERR_INVALID, PCCL_ERR_UNSUPPORTED, PCCL_ERR_OVERLAP, PCCL_ERR_HIP = range(6)
+PCCL_F32, PCCL_BF16 = 0, 1
+PCCL_SUM = 0
+PCCL_MAX_BUCKETS = 512
+
+EXPORTS = (
+    "pccl_local_reduce", "pccl_local_reduce_ptrs", "pccl_local_reduce_ptrs_two_level",
+    "pccl_hier_pack", "pccl_hier_unpack", "pccl_reduce_scatter_local",
+    "pccl_allgather_reassemble", "pccl_reduce_scatter_local_batched", "pccl_status_string",
+)
+
+
+class pccl_bucket_t(ctypes.Structure):
+    _fields_ = [("shard", ctypes.c_void_p), ("partial", ctypes.c_void_p),
+                ("intra_base", ctypes.c_void_p), ("intra_stride_bytes", ctypes.c_size_t),
+                ("chunk_count", ctypes.c_size_t)]
+
+
+class PcclError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = int(status)
+        super().__init__("%s: %s" % (where, status_string(status)))
+
+
+_lib = None
+
+
+def lib():
+    """The loaded shared library (built in-tree with hipcc if it is not there yet)."""
+    global _lib
+    if _lib is None:
+        path = _build.LIB
+        if not os.path.exists(path):
+            path = _build.build(force=True)
+        L = ctypes.CDLL(path)
+        vp, i, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+        L.pccl_local_reduce.argtypes = [vp, vp, sz, i, sz, i, i, i, vp]
+        L.pccl_local_reduce_ptrs.argtypes = [vp, vp, i, sz, i, i, i, vp]
+        L.pccl_local_reduce_ptrs_two_level.argtypes = [vp, vp, i, i, sz, i, i, i, vp]
+        L.pccl_hier_pack.argtypes = [vp, vp, i, i, sz, vp]
+        L.pccl_hier_unpack.argtypes = [vp, vp, i, i, sz, vp]
+        L.pccl_reduce_scatter_local.argtypes = [vp, vp, vp, sz, vp, i, i, i, sz, i, i, vp]
+        L.pccl_allgather_reassemble.argtypes = [vp, vp, vp, i, i, sz, vp]
+        L.pccl_reduce_scatter_local_batched.argtypes = [vp, vp, i, i, i, i, i, vp]
+        for name in EXPORTS[:-1]:
+            getattr(L, name).restype = i
+        L.pccl_status_string.argtypes = [i]
+        L.pccl_status_string.restype = ctypes.c_char_p
+        _lib = L
+    return _lib
+
+
+def status_string(status):
+    return lib().pccl_status_string(int(status)).decode()
+
+
+def _check(status, where):
+    if status != PCCL_OK:
+        raise PcclError(status, where)
+
+
+def dtype_code(dt):
+    if dt == torch.float32:
+        return PCCL_F32
+    if dt == torch.bfloat16:
+        return PCCL_BF16
+    raise TypeError("pccl: dtype must be torch.float32 or torch.bfloat16, got %s" % dt)
+
+
+def _stream(stream):
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def _dev(t, what):
+    if not t.is_cuda:
+        raise ValueError("pccl: %s must live in GPU memory" % what)
+    return t.data_ptr()
+
+
+def _rows(t, what):
+    """(base pointer, row stride in bytes, rows, row elements) of a tensor whose rows are contiguous."""
+    if t.dim() < 2:
+        raise ValueError("pccl: %s must have a leading source dimension" % what)
+    inner = t[0]
+    if not inner.is_contiguous():
+        raise ValueError("pccl: every source of %s must be contiguous" % what)
+    return _dev(t, what), t.stride(0) * t.element_size(), t.shape[0], inner.numel()
+
+
+def device_pointer_array(tensors, device=None):
+    """A device-resident array of the tensors' device pointers (int64 tensor)."""
+    ptrs = [_dev(t, "pointer-array entry") for t in tensors]
+    device = tensors[0].device if device is None else device
+    return torch.tensor(ptrs, dtype=torch.int64).to(device)
+
+
+# ------------------------------------------------------------------------------- entry points
+def pccl_local_reduce(dst, src, stream=None):
+    """dst[e] = sum over rows s of src[s][e], rows in order; src is [nsrc, ...] with contiguous rows."""
+    base, stride, nsrc, count = _rows(src, "src")
+    if dst.numel() != count or not dst.is_contiguous():
+        raise ValueError("pccl_local_reduce: dst must be contiguous with one source's element count")
+    _check(lib().pccl_local_reduce(_dev(dst, "dst"), base, stride, nsrc, count, dtype_code(src.dtype),
+                                   dtype_code(dst.dtype), PCCL_SUM, _stream(stream)),
+           "pccl_local_reduce")
+    return dst
+
+
+def pccl_local_reduce_ptrs(dst, d_srcs, count, in_dtype, stream=None):
+    """Flat sum over a device pointer array (int64 tensor) of sources holding `count` elements."""
+    _check(lib().pccl_local_reduce_ptrs(_dev(dst, "dst"), _dev(d_srcs, "d_srcs"), d_srcs.numel(), count,
+                                        dtype_code(in_dtype), dtype_code(dst.dtype), PCCL_SUM,
+                                        _stream(stream)), "pccl_local_reduce_ptrs")
+    return dst
+
+
+def pccl_local_reduce_ptrs_two_level(dst, d_srcs, nodes, gpus_per_node, count, in_dtype, stream=None):
+    """Two-level sum over a node-major device pointer array: d_srcs[n*gpus_per_node + g]."""
+    if d_srcs.numel() != nodes * gpus_per_node:
+        raise ValueError("pccl_local_reduce_ptrs_two_level: need nodes*gpus_per_node pointers")
+    _check(lib().pccl_local_reduce_ptrs_two_level(
+        _dev(dst, "dst"), _dev(d_srcs, "d_srcs"), nodes, gpus_per_node, count, dtype_code(in_dtype),
+        dtype_code(dst.dtype), PCCL_SUM, _stream(stream)), "pccl_local_reduce_ptrs_two_level")
+    return dst
+
+
+def _chunk_bytes(t, nodes, gpus, where):
+    total = t.numel() * t.element_size()
+    if not t.is_contiguous() or total % (nodes * gpus) != 0:
+        raise ValueError("%s: buffer must be contiguous and hold nodes*gpus equal chunks" % where)
+    return total // (nodes * gpus)
+
+
+def pccl_hier_pack(dst, src, nodes, gpus_per_node, stream=None):
+    """Rank order [node][gpu][chunk] -> hierarchical order [gpu][node][chunk]."""
+    cb = _chunk_bytes(src, nodes, gpus_per_node, "pccl_hier_pack")
+    if _chunk_bytes(dst, nodes, gpus_per_node, "pccl_hier_pack") != cb:
+        raise ValueError("pccl_hier_pack: dst and src sizes differ")
+    _check(lib().pccl_hier_pack(_dev(dst, "dst"), _dev(src, "src"), nodes, gpus_per_node, cb,
+                                _stream(stream)), "pccl_hier_pack")
+    return dst
+
+
+def pccl_hier_unpack(dst, src, nodes, gpus_per_node, stream=None):
+    """Hierarchical order [gpu][node][chunk] -> rank order [node][gpu][chunk]."""
+    cb = _chunk_bytes(src, nodes, gpus_per_node, "pccl_hier_unpack")
+    if _chunk_bytes(dst, nodes, gpus_per_node, "pccl_hier_unpack") != cb:
+        raise ValueError("pccl_hier_unpack: dst and src sizes differ")
+    _check(lib().pccl_hier_unpack(_dev(dst, "dst"), _dev(src, "src"), nodes, gpus_per_node, cb,
+                                  _stream(stream)), "pccl_hier_unpack")
+    return dst
+
+
+def pccl_reduce_scatter_local(shard, partial, intra, d_inter=None, my_node=0, stream=None):
+    """One GPU's share of a two-level reduce-scatter.
+
+    intra: [gpus][nodes][chunk] (piece g' = intra[g'], rows may be strided apart);
+    partial: [nodes][chunk] scratch/output; shard: [chunk]; d_inter: optional int64 device
+    tensor of `nodes` pointers to the chunks received from the other nodes."""
+    if intra.dim() != 3:
+        raise ValueError("pccl_reduce_scatter_local: intra must be [gpus][nodes][chunk]")
+    base, stride, gpus, _ = _rows(intra, "intra")
+    nodes, chunk = intra.shape[1], intra.shape[2]
+    if partial.numel() != nodes * chunk or shard.numel() != chunk or \
+            partial.dtype != intra.dtype or shard.dtype != intra.dtype or \
+            not partial.is_contiguous() or not shard.is_contiguous():
+        raise ValueError("pccl_reduce_scatter_local: partial is [nodes][chunk], shard is [chunk], "
+                         "both contiguous and of the message dtype")
+    _check(lib().pccl_reduce_scatter_local(
+        _dev(shard, "shard"), _dev(partial, "partial"), base, stride,
+        None if d_inter is None else _dev(d_inter, "d_inter"), nodes, gpus, my_node, chunk,
+        dtype_code(intra.dtype), PCCL_SUM, _stream(stream)), "pccl_reduce_scatter_local")
+    return shard
+
+
+def pccl_allgather_reassemble(dst, src=None, d_slots=None, nodes=1, gpus_per_node=1, stream=None):
+    """Hierarchical slots (contiguous src, or int64 device pointer tensor d_slots) -> rank order."""
+    cb = _chunk_bytes(dst, nodes, gpus_per_node, "pccl_allgather_reassemble")
+    _check(lib().pccl_allgather_reassemble(
+        _dev(dst, "dst"), None if src is None else _dev(src, "src"),
+        None if d_slots is None else _dev(d_slots, "d_slots"), nodes, gpus_per_node, cb,
+        _stream(stream)), "pccl_allgather_reassemble")
+    return dst
+
+
+class BucketTable:
+    """Descriptor table of a batch: a host array and its device copy, built once and reused."""
+
+    def __init__(self, buckets):
+        """buckets: list of (shard, partial, intra) tensors shaped as for pccl_reduce_scatter_local."""
+        n = len(buckets)
+        self.host = (pccl_bucket_t * max(n, 1))()
+        self.nbuckets = n
+        self.nodes = self.gpus = None
+        self.dtype = None
+        for k, (shard, partial, intra) in enumerate(buckets):
+            base, stride, gpus, _ = _rows(intra, "intra")
+            nodes, chunk = intra.shape[1], intra.shape[2]
+            if self.nodes is None:
+                self.nodes, self.gpus, self.dtype = nodes, gpus, intra.dtype
+            if (nodes, gpus, intra.dtype) != (self.nodes, self.gpus, self.dtype):
+                raise ValueError("BucketTable: nodes, gpus and dtype are common to a batch")
+            self.host[k] = pccl_bucket_t(_dev(shard, "shard"), _dev(partial, "partial"), base, stride, chunk)
+        raw = bytes(self.host)[: n * ctypes.sizeof(pccl_bucket_t)]
+        dev = buckets[0][0].device if n else "cuda"
+        self.device = torch.frombuffer(bytearray(raw), dtype=torch.uint8).to(dev) if n else None
+        self._keep = buckets  # the table holds raw pointers: keep the tensors alive
+
+
+def pccl_reduce_scatter_local_batched(table, stream=None):
+    """All buckets of a BucketTable: phase 1 in one launch, phase 2 in one launch."""
+    if table.nbuckets == 0:
+        return
+    _check(lib().pccl_reduce_scatter_local_batched(
+        table.device.data_ptr(), ctypes.addressof(table.host), table.nbuckets, table.nodes, table.gpus,
+        dtype_code(table.dtype), PCCL_SUM, _stream(stream)), "pccl_reduce_scatter_local_batched")

@@ -1,0 +1,67 @@
+// Host-side view of the gfx950 kernels: parameter blocks and launchers.
+// The C ABI (pccl_api.hip) validates arguments and calls these; nothing here allocates.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/pccl_local.h"
+
+namespace pccl {
+
+// One two-level (or flat) reduction problem.  Source (n, g), n < nodes, g < gpus, is
+//   ptrs != nullptr : ptrs[n*gpus + g]   (slot override_index reads override_ptr instead)
+//   else            : base + n*stride_n + g*stride_g
+// and holds `count` elements.  For every element e:
+//   t_n = x[n][0][e] + ... + x[n][gpus-1][e];  p_n = round_partial ? through in_dt : t_n
+//   partial[n*count + e] = p_n (if partial != nullptr, in in_dt);  dst[e] = p_0 + ... + p_{nodes-1}
+struct ReduceProblem {
+  void* dst;
+  void* partial;
+  const char* base;
+  const void* const* ptrs;
+  const void* override_ptr;
+  size_t stride_n;
+  size_t stride_g;
+  size_t count;
+  int nodes;
+  int gpus;
+  int override_index;  // -1: none
+  int round_partial;
+};
+
+// Chunk-granular transpose: dst chunk (c*rows + r) = src chunk (r*cols + c); src chunk k is
+// slots[k] when slots != nullptr, else src + k*chunk_bytes.
+struct PermuteProblem {
+  char* dst;
+  const char* src;
+  const void* const* slots;
+  size_t chunk_bytes;
+  int rows;
+  int cols;
+};
+
+constexpr int kMaxBuckets = PCCL_MAX_BUCKETS;
+
+// Prefix of tiles over the buckets of a batch, passed by value to the batched kernels.
+struct BatchTiles {
+  uint32_t first_tile[kMaxBuckets + 1];
+};
+
+hipError_t launch_reduce(const ReduceProblem& p, bool in_bf16, bool out_bf16, hipStream_t st);
+hipError_t launch_reduce_two_level_lds(const ReduceProblem& p, bool in_bf16, bool out_bf16,
+                                       hipStream_t st);
+// True when the LDS-staged kernel is the better choice for this shape.
+bool prefer_lds_two_level(const ReduceProblem& p, bool in_bf16);
+
+hipError_t launch_permute(const PermuteProblem& p, hipStream_t st);
+
+// Batched two-level reduce-scatter share; h_buckets is the host copy used to size the grid.
+hipError_t launch_rs_batched(const pccl_bucket_t* d_buckets, const pccl_bucket_t* h_buckets,
+                             int nbuckets, int nodes, int gpus, bool bf16, hipStream_t st);
+
+// Vectors (16 bytes of input per source) per tile of the streaming reduce, as a function of
+// the inner unroll chosen for `gpus` sources.
+size_t reduce_tile_elems(int gpus, bool in_bf16);
+
+}  // namespace pccl

@@ -1,0 +1,310 @@
+// C ABI of libpccl_local.so: argument checks on the host, then kernel launches on the
+// caller's stream.  Every check runs before the first HIP call, so a rejected call has no
+// side effect and the error paths can be exercised on a machine without a GPU.
+#include <cstdlib>
+
+#include "../../include/pccl_local.h"
+#include "kernels.h"
+
+namespace {
+
+using pccl::PermuteProblem;
+using pccl::ReduceProblem;
+
+inline bool dtype_ok(pccl_dtype_t d) { return d == PCCL_F32 || d == PCCL_BF16; }
+inline size_t esize(pccl_dtype_t d) { return d == PCCL_BF16 ? 2 : 4; }
+
+inline bool mul_ok(size_t a, size_t b, size_t* out) { return !__builtin_mul_overflow(a, b, out); }
+inline bool add_ok(size_t a, size_t b, size_t* out) { return !__builtin_add_overflow(a, b, out); }
+
+inline bool elem_aligned(const void* p, size_t es) {
+  return (reinterpret_cast<uintptr_t>(p) & (es - 1)) == 0;
+}
+
+// [a, a+la) and [b, b+lb) share a byte
+inline bool overlaps(const void* a, size_t la, const void* b, size_t lb) {
+  if (la == 0 || lb == 0) return false;
+  const uintptr_t x = reinterpret_cast<uintptr_t>(a), y = reinterpret_cast<uintptr_t>(b);
+  return x < y + lb && y < x + la;
+}
+
+inline pccl_status_t from_hip(hipError_t e) { return e == hipSuccess ? PCCL_OK : PCCL_ERR_HIP; }
+
+ReduceProblem blank_problem() {
+  ReduceProblem p;
+  p.dst = nullptr;
+  p.partial = nullptr;
+  p.base = nullptr;
+  p.ptrs = nullptr;
+  p.override_ptr = nullptr;
+  p.stride_n = 0;
+  p.stride_g = 0;
+  p.count = 0;
+  p.nodes = 1;
+  p.gpus = 1;
+  p.override_index = -1;
+  p.round_partial = 0;
+  return p;
+}
+
+// PCCL_FORCE_TWO_LEVEL_KERNEL=stream|lds pins the kernel behind
+// pccl_local_reduce_ptrs_two_level (for A/B runs under the profiler).
+int forced_two_level_kernel() {
+  const char* v = std::getenv("PCCL_FORCE_TWO_LEVEL_KERNEL");
+  if (v == nullptr) return 0;
+  if (v[0] == 's') return 1;
+  if (v[0] == 'l') return 2;
+  return 0;
+}
+
+pccl_status_t check_common(pccl_dtype_t in_dt, pccl_dtype_t out_dt, pccl_op_t op) {
+  if (!dtype_ok(in_dt) || !dtype_ok(out_dt)) return PCCL_ERR_UNSUPPORTED;
+  if (op != PCCL_SUM) return PCCL_ERR_UNSUPPORTED;
+  return PCCL_OK;
+}
+
+pccl_status_t permute_common(void* dst, const void* src, const void* const* slots, int rows,
+                             int cols, size_t chunk_bytes, pccl_stream_t stream) {
+  if (dst == nullptr || (src == nullptr && slots == nullptr)) return PCCL_ERR_NULL;
+  if (rows < 1 || cols < 1) return PCCL_ERR_INVALID;
+  size_t chunks, total;
+  if (!mul_ok((size_t)rows, (size_t)cols, &chunks) || chunks > 0x7FFFFFFFull)
+    return PCCL_ERR_INVALID;
+  if (!mul_ok(chunks, chunk_bytes, &total)) return PCCL_ERR_INVALID;
+  if (slots == nullptr && overlaps(dst, total, src, total)) return PCCL_ERR_OVERLAP;
+  if (chunk_bytes == 0) return PCCL_OK;
+  PermuteProblem p;
+  p.dst = reinterpret_cast<char*>(dst);
+  p.src = reinterpret_cast<const char*>(src);
+  p.slots = slots;
+  p.chunk_bytes = chunk_bytes;
+  p.rows = rows;
+  p.cols = cols;
+  const hipError_t e = pccl::launch_permute(p, reinterpret_cast<hipStream_t>(stream));
+  return e == hipErrorInvalidValue ? PCCL_ERR_INVALID : from_hip(e);
+}
+
+}  // namespace
+
+extern "C" {
+
+pccl_status_t pccl_local_reduce(void* dst, const void* src_base, size_t src_stride_bytes,
+                                int nsrc, size_t count, pccl_dtype_t in_dt,
+                                pccl_dtype_t out_dt, pccl_op_t op, pccl_stream_t stream) {
+  if (dst == nullptr || src_base == nullptr) return PCCL_ERR_NULL;
+  if (pccl_status_t s = check_common(in_dt, out_dt, op)) return s;
+  if (nsrc < 1) return PCCL_ERR_INVALID;
+  const size_t ei = esize(in_dt), eo = esize(out_dt);
+  size_t in_bytes, out_bytes, span;
+  if (!mul_ok(count, ei, &in_bytes) || !mul_ok(count, eo, &out_bytes)) return PCCL_ERR_INVALID;
+  if (!elem_aligned(dst, eo) || !elem_aligned(src_base, ei)) return PCCL_ERR_INVALID;
+  if (nsrc > 1 && (src_stride_bytes < in_bytes || src_stride_bytes % ei != 0))
+    return PCCL_ERR_INVALID;
+  if (!mul_ok((size_t)(nsrc - 1), nsrc > 1 ? src_stride_bytes : 0, &span) ||
+      !add_ok(span, in_bytes, &span))
+    return PCCL_ERR_INVALID;
+  if (overlaps(dst, out_bytes, src_base, span)) return PCCL_ERR_OVERLAP;
+  if (count == 0) return PCCL_OK;
+  ReduceProblem p = blank_problem();
+  p.dst = dst;
+  p.base = reinterpret_cast<const char*>(src_base);
+  p.stride_g = nsrc > 1 ? src_stride_bytes : 0;
+  p.count = count;
+  p.gpus = nsrc;
+  const hipError_t e = pccl::launch_reduce(p, in_dt == PCCL_BF16, out_dt == PCCL_BF16,
+                                           reinterpret_cast<hipStream_t>(stream));
+  return e == hipErrorInvalidValue ? PCCL_ERR_INVALID : from_hip(e);
+}
+
+pccl_status_t pccl_local_reduce_ptrs(void* dst, const void* const* d_srcs, int nsrc,
+                                     size_t count, pccl_dtype_t in_dt, pccl_dtype_t out_dt,
+                                     pccl_op_t op, pccl_stream_t stream) {
+  if (dst == nullptr || d_srcs == nullptr) return PCCL_ERR_NULL;
+  if (pccl_status_t s = check_common(in_dt, out_dt, op)) return s;
+  if (nsrc < 1) return PCCL_ERR_INVALID;
+  size_t bytes;
+  if (!mul_ok(count, esize(in_dt), &bytes) || !mul_ok(count, esize(out_dt), &bytes))
+    return PCCL_ERR_INVALID;
+  if (!elem_aligned(dst, esize(out_dt))) return PCCL_ERR_INVALID;
+  if (count == 0) return PCCL_OK;
+  ReduceProblem p = blank_problem();
+  p.dst = dst;
+  p.ptrs = d_srcs;
+  p.count = count;
+  p.gpus = nsrc;
+  const bool ib = in_dt == PCCL_BF16, ob = out_dt == PCCL_BF16;
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  // A long flat chain over short buffers: stage the sources through LDS (a flat sum is the
+  // two-level sum with one GPU per node) so that the loads of many sources overlap.
+  ReduceProblem q = p;
+  q.nodes = nsrc;
+  q.gpus = 1;
+  const hipError_t e = pccl::prefer_lds_two_level(q, ib)
+                           ? pccl::launch_reduce_two_level_lds(q, ib, ob, st)
+                           : pccl::launch_reduce(p, ib, ob, st);
+  return e == hipErrorInvalidValue ? PCCL_ERR_INVALID : from_hip(e);
+}
+
+pccl_status_t pccl_local_reduce_ptrs_two_level(void* dst, const void* const* d_srcs, int nodes,
+                                               int gpus_per_node, size_t count,
+                                               pccl_dtype_t in_dt, pccl_dtype_t out_dt,
+                                               pccl_op_t op, pccl_stream_t stream) {
+  if (dst == nullptr || d_srcs == nullptr) return PCCL_ERR_NULL;
+  if (pccl_status_t s = check_common(in_dt, out_dt, op)) return s;
+  if (nodes < 1 || gpus_per_node < 1) return PCCL_ERR_INVALID;
+  size_t ranks, bytes;
+  if (!mul_ok((size_t)nodes, (size_t)gpus_per_node, &ranks) || ranks > 0x7FFFFFFFull)
+    return PCCL_ERR_INVALID;
+  if (!mul_ok(count, esize(in_dt), &bytes) || !mul_ok(count, esize(out_dt), &bytes))
+    return PCCL_ERR_INVALID;
+  if (!elem_aligned(dst, esize(out_dt))) return PCCL_ERR_INVALID;
+  if (count == 0) return PCCL_OK;
+  ReduceProblem p = blank_problem();
+  p.dst = dst;
+  p.ptrs = d_srcs;
+  p.count = count;
+  p.nodes = nodes;
+  p.gpus = gpus_per_node;
+  p.round_partial = 1;
+  const bool ib = in_dt == PCCL_BF16, ob = out_dt == PCCL_BF16;
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  const int forced = forced_two_level_kernel();
+  const bool lds = forced == 2 || (forced == 0 && pccl::prefer_lds_two_level(p, ib));
+  const hipError_t e = lds ? pccl::launch_reduce_two_level_lds(p, ib, ob, st)
+                           : pccl::launch_reduce(p, ib, ob, st);
+  return e == hipErrorInvalidValue ? PCCL_ERR_INVALID : from_hip(e);
+}
+
+pccl_status_t pccl_hier_pack(void* dst, const void* src, int nodes, int gpus_per_node,
+                             size_t chunk_bytes, pccl_stream_t stream) {
+  if (src == nullptr) return PCCL_ERR_NULL;
+  // src is [node][gpu]: rows = nodes, cols = gpus; dst chunk (g*N + n) = src chunk (n*M + g)
+  return permute_common(dst, src, nullptr, nodes, gpus_per_node, chunk_bytes, stream);
+}
+
+pccl_status_t pccl_hier_unpack(void* dst, const void* src, int nodes, int gpus_per_node,
+                               size_t chunk_bytes, pccl_stream_t stream) {
+  if (src == nullptr) return PCCL_ERR_NULL;
+  // src is [gpu][node]: rows = gpus, cols = nodes; dst chunk (n*M + g) = src chunk (g*N + n)
+  return permute_common(dst, src, nullptr, gpus_per_node, nodes, chunk_bytes, stream);
+}
+
+pccl_status_t pccl_allgather_reassemble(void* dst, const void* src, const void* const* d_slots,
+                                        int nodes, int gpus_per_node, size_t chunk_bytes,
+                                        pccl_stream_t stream) {
+  return permute_common(dst, d_slots != nullptr ? nullptr : src, d_slots, gpus_per_node, nodes,
+                        chunk_bytes, stream);
+}
+
+pccl_status_t pccl_reduce_scatter_local(void* shard, void* partial, const void* intra_base,
+                                        size_t intra_stride_bytes, const void* const* d_inter,
+                                        int nodes, int gpus_per_node, int my_node,
+                                        size_t chunk_count, pccl_dtype_t io_dt, pccl_op_t op,
+                                        pccl_stream_t stream) {
+  if (shard == nullptr || partial == nullptr || intra_base == nullptr) return PCCL_ERR_NULL;
+  if (pccl_status_t s = check_common(io_dt, io_dt, op)) return s;
+  if (nodes < 1 || gpus_per_node < 1 || my_node < 0 || my_node >= nodes) return PCCL_ERR_INVALID;
+  const size_t es = esize(io_dt);
+  size_t piece_count, piece_bytes, chunk_bytes, span;
+  if (!mul_ok((size_t)nodes, chunk_count, &piece_count) || !mul_ok(piece_count, es, &piece_bytes))
+    return PCCL_ERR_INVALID;
+  chunk_bytes = chunk_count * es;
+  if (!elem_aligned(shard, es) || !elem_aligned(partial, es) || !elem_aligned(intra_base, es))
+    return PCCL_ERR_INVALID;
+  if (gpus_per_node > 1 && (intra_stride_bytes < piece_bytes || intra_stride_bytes % es != 0))
+    return PCCL_ERR_INVALID;
+  if (!mul_ok((size_t)(gpus_per_node - 1), gpus_per_node > 1 ? intra_stride_bytes : 0, &span) ||
+      !add_ok(span, piece_bytes, &span))
+    return PCCL_ERR_INVALID;
+  if (overlaps(partial, piece_bytes, intra_base, span) ||
+      overlaps(shard, chunk_bytes, intra_base, span) ||
+      overlaps(shard, chunk_bytes, partial, piece_bytes))
+    return PCCL_ERR_OVERLAP;
+  if (chunk_count == 0) return PCCL_OK;
+  const bool bf = io_dt == PCCL_BF16;
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+
+  // phase 1 (intra-node): partial[n][e] = sum over g' of piece_g'[n][e], an M-source flat
+  // sum over the nodes*chunk_count elements of a piece
+  ReduceProblem p1 = blank_problem();
+  p1.dst = partial;
+  p1.base = reinterpret_cast<const char*>(intra_base);
+  p1.stride_g = gpus_per_node > 1 ? intra_stride_bytes : 0;
+  p1.count = piece_count;
+  p1.gpus = gpus_per_node;
+  hipError_t e = pccl::launch_reduce(p1, bf, bf, st);
+  if (e != hipSuccess) return e == hipErrorInvalidValue ? PCCL_ERR_INVALID : PCCL_ERR_HIP;
+
+  // phase 2 (inter-node): shard[e] = sum over n' of inter_n'[e], an N-source flat sum
+  ReduceProblem p2 = blank_problem();
+  p2.dst = shard;
+  p2.count = chunk_count;
+  p2.gpus = nodes;
+  if (d_inter == nullptr) {
+    p2.base = reinterpret_cast<const char*>(partial);
+    p2.stride_g = chunk_bytes;
+  } else {
+    p2.ptrs = d_inter;
+    p2.override_index = my_node;
+    p2.override_ptr = reinterpret_cast<const char*>(partial) + (size_t)my_node * chunk_bytes;
+  }
+  e = pccl::launch_reduce(p2, bf, bf, st);
+  return e == hipErrorInvalidValue ? PCCL_ERR_INVALID : from_hip(e);
+}
+
+pccl_status_t pccl_reduce_scatter_local_batched(const pccl_bucket_t* d_buckets,
+                                                const pccl_bucket_t* h_buckets, int nbuckets,
+                                                int nodes, int gpus_per_node,
+                                                pccl_dtype_t io_dt, pccl_op_t op,
+                                                pccl_stream_t stream) {
+  if (nbuckets < 0 || nbuckets > PCCL_MAX_BUCKETS) return PCCL_ERR_INVALID;
+  if (nbuckets > 0 && (d_buckets == nullptr || h_buckets == nullptr)) return PCCL_ERR_NULL;
+  if (pccl_status_t s = check_common(io_dt, io_dt, op)) return s;
+  if (nodes < 1 || gpus_per_node < 1) return PCCL_ERR_INVALID;
+  const size_t es = esize(io_dt);
+  bool any = false;
+  for (int b = 0; b < nbuckets; ++b) {
+    const pccl_bucket_t& k = h_buckets[b];
+    if (k.chunk_count == 0) continue;  // an empty bucket is skipped whatever its pointers are
+    if (k.shard == nullptr || k.partial == nullptr || k.intra_base == nullptr)
+      return PCCL_ERR_NULL;
+    size_t piece_count, piece_bytes, span;
+    if (!mul_ok((size_t)nodes, k.chunk_count, &piece_count) ||
+        !mul_ok(piece_count, es, &piece_bytes))
+      return PCCL_ERR_INVALID;
+    if (!elem_aligned(k.shard, es) || !elem_aligned(k.partial, es) ||
+        !elem_aligned(k.intra_base, es))
+      return PCCL_ERR_INVALID;
+    if (gpus_per_node > 1 && (k.intra_stride_bytes < piece_bytes || k.intra_stride_bytes % es != 0))
+      return PCCL_ERR_INVALID;
+    if (!mul_ok((size_t)(gpus_per_node - 1), gpus_per_node > 1 ? k.intra_stride_bytes : 0,
+                &span) ||
+        !add_ok(span, piece_bytes, &span))
+      return PCCL_ERR_INVALID;
+    const size_t chunk_bytes = k.chunk_count * es;
+    if (overlaps(k.partial, piece_bytes, k.intra_base, span) ||
+        overlaps(k.shard, chunk_bytes, k.intra_base, span) ||
+        overlaps(k.shard, chunk_bytes, k.partial, piece_bytes))
+      return PCCL_ERR_OVERLAP;
+    any = true;
+  }
+  if (!any) return PCCL_OK;
+  const hipError_t e =
+      pccl::launch_rs_batched(d_buckets, h_buckets, nbuckets, nodes, gpus_per_node,
+                              io_dt == PCCL_BF16, reinterpret_cast<hipStream_t>(stream));
+  return e == hipErrorInvalidValue ? PCCL_ERR_INVALID : from_hip(e);
+}
+
+const char* pccl_status_string(pccl_status_t status) {
+  switch (status) {
+    case PCCL_OK: return "PCCL_OK";
+    case PCCL_ERR_NULL: return "PCCL_ERR_NULL: a required pointer is NULL";
+    case PCCL_ERR_INVALID: return "PCCL_ERR_INVALID: a count, stride, index or size is out of range";
+    case PCCL_ERR_UNSUPPORTED: return "PCCL_ERR_UNSUPPORTED: unknown dtype or reduction op";
+    case PCCL_ERR_OVERLAP: return "PCCL_ERR_OVERLAP: an output range overlaps an input range";
+    case PCCL_ERR_HIP: return "PCCL_ERR_HIP: the HIP runtime refused a kernel launch";
+  }
+  return "PCCL: unknown status";
+}
+
+}  // extern "C"
