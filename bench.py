@@ -1,0 +1,280 @@
+#!/usr/bin/env python3
+"""Benchmark of the local kernels of PCCL's hierarchical collectives on one MI355X.
+
+A step is one GPU's share of a two-level all-reduce of one 256 MB bf16 message at
+16 nodes x 8 GPUs (the 256 MB workload of the configuration list):
+    pccl_hier_pack            256 MB rank-order message -> hierarchical order
+    pccl_reduce_scatter_local phase 1: 8 x 32 MB -> 32 MB partial; phase 2: 16 x 2 MB -> 2 MB
+                              (the 15 foreign chunks arrive through a device pointer array)
+    pccl_allgather_reassemble 256 MB of gathered shards -> rank order
+Inputs are seeded synthetic tensors already resident in HBM; every step works on the next of
+several disjoint buffer sets so that the last-level cache cannot serve a re-run.
+
+Prints ONE JSON line.  `value` = algorithmic bytes of a step / wall time of a step.
+`roofline` is for the dominant kernel (the chunk transpose), timed with events on the launch
+stream inside the timed region.  `cpu_baseline` times the CPU oracle on the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np  # noqa: E402
+import torch  # noqa: E402
+
+import paper_2504_18658_amd as pccl  # noqa: E402
+from paper_2504_18658_amd import workloads as W  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
+MB = 1 << 20
+
+
+def to_np(t):
+    t = t.detach().cpu().contiguous()
+    return t.view(torch.int16).numpy().view(np.uint16) if t.dtype == torch.bfloat16 else t.numpy()
+
+
+class AllReduceShare:
+    """Buffers of one step of the headline workload (one of several rotating sets)."""
+
+    def __init__(self, w, dev, k, my_node=5):
+        self.w, self.my_node = w, my_node
+        n = w.ranks * w.chunk
+        self.msg = W.draw(w, n, dev, seed_offset=10 * k + 1)          # [node][gpu][chunk]
+        self.packed = torch.empty_like(self.msg)                       # [gpu][node][chunk]
+        self.x = W.two_level_input(w, dev, seed_offset=10 * k + 2)     # [gpu'][node][chunk] received
+        self.partial = torch.empty(w.nodes * w.chunk, dtype=w.dtype, device=dev)
+        self.shard = torch.empty(w.chunk, dtype=w.dtype, device=dev)
+        self.inter = W.draw(w, w.nodes * w.chunk, dev, seed_offset=10 * k + 3).view(w.nodes, w.chunk)
+        self.d_inter = pccl.device_pointer_array([self.inter[j] for j in range(w.nodes)])
+        self.gathered = W.draw(w, n, dev, seed_offset=10 * k + 4)      # [gpu][node][chunk]
+        self.out = torch.empty_like(self.gathered)
+
+    def bytes_per_call(self):
+        w = self.w
+        e = w.esize
+        m = w.ranks * w.chunk * e
+        piece = w.nodes * w.chunk * e
+        return {
+            "pccl_hier_pack": 2 * m,
+            "pccl_reduce_scatter_local": (w.gpus + 1) * piece + (w.nodes + 1) * w.chunk * e,
+            "pccl_allgather_reassemble": 2 * m,
+        }
+
+    def run(self, events=None):
+        w = self.w
+        if events is not None:
+            events[0].record()
+        pccl.pccl_hier_pack(self.packed, self.msg, w.nodes, w.gpus)
+        if events is not None:
+            events[1].record()
+        pccl.pccl_reduce_scatter_local(self.shard, self.partial, self.x, d_inter=self.d_inter,
+                                       my_node=self.my_node)
+        if events is not None:
+            events[2].record()
+        pccl.pccl_allgather_reassemble(self.out, src=self.gathered, nodes=w.nodes, gpus_per_node=w.gpus)
+        if events is not None:
+            events[3].record()
+
+    def oracle_step(self, host, nthreads=1):
+        import oracle
+        w = self.w
+        packed = oracle.hier_pack(host["msg"], w.nodes, w.gpus)
+        inter = [host["inter"][j] for j in range(w.nodes)]
+        shard, partial = oracle.reduce_scatter_local(host["x"], my_node=self.my_node, inter=inter,
+                                                     nthreads=nthreads)
+        out = oracle.hier_unpack(host["gathered"], w.nodes, w.gpus)
+        return packed, partial, shard, out
+
+    def host_inputs(self):
+        return {"msg": to_np(self.msg), "x": to_np(self.x), "inter": to_np(self.inter),
+                "gathered": to_np(self.gathered)}
+
+
+def time_calls(fn_list, trials=10, warm=3):
+    """Mean/min milliseconds of fn_list[k % len]() over `trials` calls, events on the current stream."""
+    for k in range(warm):
+        fn_list[k % len(fn_list)]()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(trials)]
+    torch.cuda.synchronize()
+    for k in range(trials):
+        ev[k][0].record()
+        fn_list[k % len(fn_list)]()
+        ev[k][1].record()
+    torch.cuda.synchronize()
+    ms = [a.elapsed_time(b) for a, b in ev]
+    return float(np.mean(ms)), float(np.min(ms)), float(np.std(ms))
+
+
+def other_workloads(dev):
+    """The remaining configurations, each timed on its own (10 trials, rotating buffer sets)."""
+    res = {}
+
+    def entry(name, nbytes, mean_ms, min_ms, std_ms, **kw):
+        res[name] = dict(bytes=nbytes, mean_us=round(mean_ms * 1e3, 2), min_us=round(min_ms * 1e3, 2),
+                         std_us=round(std_ms * 1e3, 2), GBps=round(nbytes / (mean_ms * 1e-3) / 1e9, 1),
+                         frac_of_peak=round(nbytes / (mean_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4), **kw)
+
+    # cfg1: flat reduce of 8 x 512 KB fp32 (latency-sized)
+    w = W.cfg1()
+    sets = [(torch.empty(w.chunk, dtype=w.dtype, device=dev),
+             W.draw(w, w.gpus * w.chunk, dev, seed_offset=k).view(w.gpus, w.chunk)) for k in range(8)]
+    entry("cfg1_flat_reduce_p8_f32_512KB", (w.gpus + 1) * w.chunk * 4,
+          *time_calls([lambda s=s: pccl.pccl_local_reduce(s[0], s[1]) for s in sets]))
+    del sets
+    # cfg2: all-gather reassembly, 4 x 8, 64 MB bf16
+    w = W.cfg2()
+    n = w.ranks * w.chunk
+    sets = [(torch.empty(n, dtype=w.dtype, device=dev), W.draw(w, n, dev, seed_offset=k)) for k in range(8)]
+    entry("cfg2_hier_unpack_4x8_bf16_64MB", 2 * n * 2,
+          *time_calls([lambda s=s: pccl.pccl_hier_unpack(s[0], s[1], w.nodes, w.gpus) for s in sets]))
+    del sets
+    # cfg4: 2048 x 64 KB fp32 through a shuffled pointer array, then reassembly of 128 MB
+    w = W.cfg4()
+    sets = []
+    for k in range(4):
+        arena = W.draw(w, w.ranks * w.chunk, dev, seed_offset=k).view(w.ranks, w.chunk)
+        order = W.shuffled_slot_order(w.ranks, w.seed + k)
+        ptrs = pccl.device_pointer_array([arena[order[s]] for s in range(w.ranks)])
+        sets.append((torch.empty(w.chunk, dtype=w.dtype, device=dev), ptrs, arena,
+                     torch.empty(w.ranks * w.chunk, dtype=w.dtype, device=dev)))
+    entry("cfg4_reduce_ptrs_two_level_256x8_f32_128MB", (w.ranks + 1) * w.chunk * 4,
+          *time_calls([lambda s=s: pccl.pccl_local_reduce_ptrs_two_level(
+              s[0], s[1], w.nodes, w.gpus, w.chunk, w.dtype) for s in sets]))
+    entry("cfg4_allgather_reassemble_256x8_f32_128MB", 2 * w.ranks * w.chunk * 4,
+          *time_calls([lambda s=s: pccl.pccl_allgather_reassemble(
+              s[3], src=s[2], nodes=w.nodes, gpus_per_node=w.gpus) for s in sets]))
+    del sets
+    # cfg5: 40 ZeRO-3-shaped buckets in one batched call
+    w = W.cfg5()
+    sizes = w.extra["bucket_bytes"]
+    buckets, nbytes = [], 0
+    for k, b in enumerate(sizes):
+        chunk = b // (w.ranks * w.esize)
+        x = W.two_level_input(w, dev, seed_offset=k + 1, chunk=chunk)
+        buckets.append((torch.empty(chunk, dtype=w.dtype, device=dev),
+                        torch.empty(w.nodes * chunk, dtype=w.dtype, device=dev), x))
+        nbytes += (w.gpus + 1) * w.nodes * chunk * 2 + (w.nodes + 1) * chunk * 2
+    table = pccl.BucketTable(buckets)
+    entry("cfg5_rs_batched_40_buckets_8x8_bf16", nbytes,
+          *time_calls([lambda: pccl.pccl_reduce_scatter_local_batched(table)], trials=5, warm=2),
+          total_bucket_MB=round(sum(sizes) / MB, 1))
+    return res
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--sets", type=int, default=4, help="disjoint buffer sets rotated over (cold cache)")
+    ap.add_argument("--no-kernel-events", action="store_true", help="do not record per-call events")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-others", action="store_true", help="skip the other four configurations")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is the single-GPU local path of the collectives; "
+              "--gpus %d is not supported (nothing here uses a second GPU)" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+    dev = "cuda:0"
+    pccl.lib()
+
+    w = W.cfg3()
+    sets = [AllReduceShare(w, dev, k) for k in range(args.sets)]
+    per_call = sets[0].bytes_per_call()
+    step_bytes = sum(per_call.values())
+
+    for k in range(args.warmup):
+        sets[k % len(sets)].run()
+    torch.cuda.synchronize()
+
+    use_ev = not args.no_kernel_events
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)] if use_ev else None
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        sets[k % len(sets)].run(events[k] if use_ev else None)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    value = step_bytes / (ms_per_step * 1e-3) / 1e9
+
+    calls = {}
+    roofline = None
+    if use_ev:
+        names = ["pccl_hier_pack", "pccl_reduce_scatter_local", "pccl_allgather_reassemble"]
+        dur = {n: [] for n in names}
+        for ev in events:
+            for j, n in enumerate(names):
+                dur[n].append(ev[j].elapsed_time(ev[j + 1]))
+        for n in names:
+            m = float(np.mean(dur[n]))
+            calls[n] = dict(bytes=per_call[n], mean_us=round(m * 1e3, 2), min_us=round(float(np.min(dur[n])) * 1e3, 2),
+                            std_us=round(float(np.std(dur[n])) * 1e3, 2),
+                            GBps=round(per_call[n] / (m * 1e-3) / 1e9, 1))
+        perm = dur["pccl_hier_pack"] + dur["pccl_allgather_reassemble"]
+        avg_ms = float(np.mean(perm))
+        achieved = per_call["pccl_hier_pack"] / (avg_ms * 1e-3) / 1e9
+        roofline = dict(kernel="k_permute (pccl_hier_pack / pccl_allgather_reassemble, 256 MB each)",
+                        bound="hbm", achieved=round(achieved, 1), peak=HBM_PEAK_GBS, unit="GB/s",
+                        frac=round(achieved / HBM_PEAK_GBS, 4), traffic=None,
+                        algorithmic_bytes_per_launch=per_call["pccl_hier_pack"],
+                        avg_launch_us=round(avg_ms * 1e3, 2), launches=len(perm))
+        red = dur["pccl_reduce_scatter_local"]
+        roofline["reduce"] = dict(
+            kernel="k_reduce phase 1 (8 x 32 MB) + phase 2 (16 x 2 MB), one call", bound="hbm",
+            achieved=round(per_call["pccl_reduce_scatter_local"] / (float(np.mean(red)) * 1e-3) / 1e9, 1),
+            peak=HBM_PEAK_GBS, unit="GB/s",
+            frac=round(per_call["pccl_reduce_scatter_local"] / (float(np.mean(red)) * 1e-3) / 1e9 / HBM_PEAK_GBS, 4))
+
+    # parity of the timed configuration + CPU baseline: the oracle on the very same buffers
+    cpu_baseline, parity = None, None
+    if not args.no_cpu_baseline:
+        s0 = sets[0]
+        s0.run()
+        torch.cuda.synchronize()
+        host = s0.host_inputs()
+        got = [to_np(s0.packed), to_np(s0.partial), to_np(s0.shard), to_np(s0.out)]
+        reps, t_cpu = 0, 0.0
+        while t_cpu < 10.0 and reps < 50:
+            c0 = time.perf_counter()
+            want = s0.oracle_step(host, nthreads=1)
+            t_cpu += time.perf_counter() - c0
+            reps += 1
+        parity = all(g.tobytes() == np.ascontiguousarray(x).tobytes() for g, x in zip(got, want))
+        cpu_baseline = dict(value=round(step_bytes * reps / t_cpu / 1e9, 3), unit="GB/s", cores=1, kind="oracle",
+                            sample="%d whole steps of the same workload (pack, two-level reduce, reassemble), "
+                                   "%.1f s, single thread of %d host cores" % (reps, t_cpu, os.cpu_count() or 0),
+                            ms_per_step=round(t_cpu / reps * 1e3, 1))
+    del sets
+    torch.cuda.empty_cache()
+
+    others = None if args.no_others else other_workloads(dev)
+
+    out = {
+        "metric": "achieved HBM GB/s, local reduce + hier permute (one GPU's share of a two-level all-reduce)",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4),
+        "config": {"workload": w.name + ": pack 256 MB + two-level reduce (8 x 32 MB, 16 x 2 MB) + reassemble 256 MB",
+                   "nodes": w.nodes, "gpus_per_node": w.gpus, "message_MB": w.ranks * w.chunk * w.esize // MB,
+                   "accumulate": "f32", "algorithmic_bytes_per_step": step_bytes, "buffer_sets": args.sets,
+                   "kernel_events_in_timed_region": use_ev},
+        "roofline": roofline, "cpu_baseline": cpu_baseline, "parity_vs_oracle": parity,
+        "calls": calls, "other_workloads": others,
+    }
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -29,74 +29,94 @@ __device__ __forceinline__ uint16_t to_bf16(float x) { return (uint16_t)(pack_bf
 __device__ __forceinline__ float round_through_bf16(float x) { return bf16_lo(pack_bf16(x, 0.0f)); }
 
 // ---- streaming global access ------------------------------------------------------------
-// `base` is wave-uniform, `byte_off` is per lane.  Data is touched once, so loads and stores
-// carry the non-temporal hint.
+// Every buffer the library touches is device global memory.  Pointers arrive inside
+// by-value parameter blocks, where the compiler would otherwise treat them as generic
+// (flat) pointers; the casts below pin them to the global / constant address spaces so that
+// global_load / global_store / s_load are emitted.  Data is touched once, so loads and
+// stores carry the non-temporal hint.
+#define PCCL_GLOBAL __attribute__((address_space(1)))
+#define PCCL_CONSTANT __attribute__((address_space(4)))
 
 template <typename T>
 __device__ __forceinline__ T ld_stream(const void* p) {
-  return __builtin_nontemporal_load(reinterpret_cast<const T*>(p));
+  return __builtin_nontemporal_load((const PCCL_GLOBAL T*)p);
 }
 template <typename T>
 __device__ __forceinline__ void st_stream(void* p, T v) {
-  __builtin_nontemporal_store(v, reinterpret_cast<T*>(p));
+  __builtin_nontemporal_store(v, (PCCL_GLOBAL T*)p);
+}
+
+// Entry `idx` of a device-resident pointer array that no kernel writes (wave-uniform idx).
+typedef const void* pccl_cvoidp;
+__device__ __forceinline__ const char* ld_pointer(const void* const* table, int idx) {
+  return reinterpret_cast<const char*>(((const PCCL_CONSTANT pccl_cvoidp*)table)[idx]);
+}
+// The same with a per-lane index.
+__device__ __forceinline__ const char* ld_pointer_lane(const void* const* table, size_t idx) {
+  return reinterpret_cast<const char*>(((const PCCL_GLOBAL pccl_cvoidp*)table)[idx]);
 }
 
 __device__ __forceinline__ bool aligned_to(const void* p, uintptr_t a) {
   return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0;
 }
 
-// 16 bytes from base+byte_off; ES = element size the buffer is guaranteed aligned to (2 or 4).
-template <int ES>
-__device__ __forceinline__ u32x4 ld16(const char* base, size_t byte_off) {
+// W consecutive 32-bit words from base+byte_off (W = 1, 2 or 4).  The vector instruction
+// needs base aligned to 4*W bytes (byte_off is always a multiple of that); otherwise the
+// words are gathered with dword or halfword loads.  ES = element size the buffer is
+// guaranteed aligned to (2 or 4).  ALIGNED = the caller has checked 16-byte alignment.
+template <int W>
+struct Words;
+template <>
+struct Words<1> { typedef uint32_t T; };
+template <>
+struct Words<2> { typedef u32x2 T; };
+template <>
+struct Words<4> { typedef u32x4 T; };
+
+template <int W, int ES, bool ALIGNED = false>
+__device__ __forceinline__ void ld_words(const char* base, size_t byte_off, uint32_t* w) {
   const char* p = base + byte_off;
-  if (aligned_to(base, 16)) return ld_stream<u32x4>(p);
-  u32x4 v;
-  if (ES == 4 || aligned_to(base, 4)) {
+  if (ALIGNED || aligned_to(base, 4 * W)) {
+    if constexpr (W == 1) {
+      w[0] = ld_stream<uint32_t>(p);
+    } else {
+      const typename Words<W>::T v = ld_stream<typename Words<W>::T>(p);
 #pragma unroll
-    for (int k = 0; k < 4; ++k) v[k] = ld_stream<uint32_t>(p + 4 * k);
-  } else {
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      uint32_t lo = ld_stream<uint16_t>(p + 4 * k);
-      uint32_t hi = ld_stream<uint16_t>(p + 4 * k + 2);
-      v[k] = lo | (hi << 16);
+      for (int k = 0; k < W; ++k) w[k] = v[k];
     }
-  }
-  return v;
-}
-
-template <int ES>
-__device__ __forceinline__ void st16(char* base, size_t byte_off, u32x4 v) {
-  char* p = base + byte_off;
-  if (aligned_to(base, 16)) {
-    st_stream<u32x4>(p, v);
-    return;
-  }
-  if (ES == 4 || aligned_to(base, 4)) {
+  } else if (ES == 4 || aligned_to(base, 4)) {
 #pragma unroll
-    for (int k = 0; k < 4; ++k) st_stream<uint32_t>(p + 4 * k, v[k]);
+    for (int k = 0; k < W; ++k) w[k] = ld_stream<uint32_t>(p + 4 * k);
   } else {
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      st_stream<uint16_t>(p + 4 * k, (uint16_t)(v[k] & 0xFFFFu));
-      st_stream<uint16_t>(p + 4 * k + 2, (uint16_t)(v[k] >> 16));
+    for (int k = 0; k < W; ++k) {
+      const uint32_t lo = ld_stream<uint16_t>(p + 4 * k);
+      const uint32_t hi = ld_stream<uint16_t>(p + 4 * k + 2);
+      w[k] = lo | (hi << 16);
     }
   }
 }
 
-// 8 bytes (two words) of bf16 output from an fp32-input vector.
-__device__ __forceinline__ void st8_bf16(char* base, size_t byte_off, u32x2 v) {
+template <int W, int ES, bool ALIGNED = false>
+__device__ __forceinline__ void st_words(char* base, size_t byte_off, const uint32_t* w) {
   char* p = base + byte_off;
-  if (aligned_to(base, 8)) {
-    st_stream<u32x2>(p, v);
-  } else if (aligned_to(base, 4)) {
-    st_stream<uint32_t>(p, v[0]);
-    st_stream<uint32_t>(p + 4, v[1]);
+  if (ALIGNED || aligned_to(base, 4 * W)) {
+    if constexpr (W == 1) {
+      st_stream<uint32_t>(p, w[0]);
+    } else {
+      typename Words<W>::T v;
+#pragma unroll
+      for (int k = 0; k < W; ++k) v[k] = w[k];
+      st_stream<typename Words<W>::T>(p, v);
+    }
+  } else if (ES == 4 || aligned_to(base, 4)) {
+#pragma unroll
+    for (int k = 0; k < W; ++k) st_stream<uint32_t>(p + 4 * k, w[k]);
   } else {
 #pragma unroll
-    for (int k = 0; k < 2; ++k) {
-      st_stream<uint16_t>(p + 4 * k, (uint16_t)(v[k] & 0xFFFFu));
-      st_stream<uint16_t>(p + 4 * k + 2, (uint16_t)(v[k] >> 16));
+    for (int k = 0; k < W; ++k) {
+      st_stream<uint16_t>(p + 4 * k, (uint16_t)(w[k] & 0xFFFFu));
+      st_stream<uint16_t>(p + 4 * k + 2, (uint16_t)(w[k] >> 16));
     }
   }
 }

@@ -60,8 +60,4 @@ hipError_t launch_permute(const PermuteProblem& p, hipStream_t st);
 hipError_t launch_rs_batched(const pccl_bucket_t* d_buckets, const pccl_bucket_t* h_buckets,
                              int nbuckets, int nodes, int gpus, bool bf16, hipStream_t st);
 
-// Vectors (16 bytes of input per source) per tile of the streaming reduce, as a function of
-// the inner unroll chosen for `gpus` sources.
-size_t reduce_tile_elems(int gpus, bool in_bf16);
-
 }  // namespace pccl

@@ -3,8 +3,9 @@
 // all-gather, and its inverse ahead of the two-level reduce-scatter).
 //
 // Every chunk is contiguous on both sides, so the transpose is P independent streaming
-// copies; nothing is staged in LDS.  A block copies one 16 KB tile of one chunk: each lane
-// issues four 128-bit loads before its four stores.  HBM-bound: 2 bytes moved per byte.
+// copies; nothing is staged in LDS.  A block copies one 4 KB tile of one chunk, one 128-bit
+// load and store per lane: measured on MI355X, more bytes in flight per lane at full
+// occupancy lowers the achieved HBM bandwidth.  HBM-bound: 2 bytes moved per byte.
 #include "device_utils.h"
 #include "kernels.h"
 
@@ -12,7 +13,7 @@ namespace pccl {
 
 namespace {
 
-constexpr int kPermU = 4;                                // 16-byte vectors per thread
+constexpr int kPermU = 1;                                // 16-byte vectors per thread
 constexpr size_t kPermTile = (size_t)kBlock * 16 * kPermU;  // bytes per block
 
 __global__ __launch_bounds__(kBlock) void k_permute(PermuteProblem p, uint32_t tiles_per_chunk) {
@@ -22,7 +23,7 @@ __global__ __launch_bounds__(kBlock) void k_permute(PermuteProblem p, uint32_t t
   const uint32_t c = chunk / (uint32_t)p.rows;  // dst chunk = c*rows + r
   const uint32_t r = chunk - c * (uint32_t)p.rows;
   const size_t sidx = (size_t)r * p.cols + c;
-  const char* sp = p.slots != nullptr ? reinterpret_cast<const char*>(p.slots[sidx])
+  const char* sp = p.slots != nullptr ? ld_pointer_lane(p.slots, sidx)
                                       : p.src + sidx * p.chunk_bytes;
   char* dp = p.dst + (size_t)chunk * p.chunk_bytes;
   const size_t off = (size_t)tile * kPermTile;
@@ -45,15 +46,16 @@ __global__ __launch_bounds__(kBlock) void k_permute(PermuteProblem p, uint32_t t
       if (i < nv) st_stream<u32x4>(dp + i * 16, v[u]);
     }
     const size_t b = nv * 16 + threadIdx.x;  // fewer than 16 bytes can be left
-    if (b < len) dp[b] = sp[b];
+    if (b < len) st_stream<uint8_t>(dp + b, ld_stream<uint8_t>(sp + b));
   } else if (aligned_to(sp, 4) && aligned_to(dp, 4)) {
     const size_t nw = len / 4;
     for (size_t i = threadIdx.x; i < nw; i += kBlock)
       st_stream<uint32_t>(dp + i * 4, ld_stream<uint32_t>(sp + i * 4));
     const size_t b = nw * 4 + threadIdx.x;
-    if (b < len) dp[b] = sp[b];
+    if (b < len) st_stream<uint8_t>(dp + b, ld_stream<uint8_t>(sp + b));
   } else {
-    for (size_t i = threadIdx.x; i < len; i += kBlock) dp[i] = sp[i];
+    for (size_t i = threadIdx.x; i < len; i += kBlock)
+      st_stream<uint8_t>(dp + i, ld_stream<uint8_t>(sp + i));
   }
 }
 

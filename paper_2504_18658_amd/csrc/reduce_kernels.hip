@@ -3,9 +3,9 @@
 // the fixed intra-node-then-inter-node order of Section IV-A).
 //
 // Two kernel families:
-//   k_reduce            streaming: one thread owns a 16-byte input vector position and
-//                       walks the sources in order; bandwidth comes from the M independent
-//                       128-bit loads per lane and from occupancy.
+//   k_reduce            streaming: one thread owns a 4..16-byte vector position and walks
+//                       the sources in order; bandwidth comes from the M independent
+//                       loads per lane and from occupancy.
 //   k_reduce2l_lds      many small chunks (2048 ranks x 64 KB): a wavefront owns a node,
 //                       the per-node sums of one element slice are staged in LDS and a
 //                       final pass adds them in node order.
@@ -19,26 +19,54 @@ namespace {
 
 // ------------------------------------------------------------------------------------------
 // source addressing (everything here is wave-uniform)
+// FAST: the host has checked that the sources are strided (no pointer array) and that every
+// base, stride and output is 16-byte aligned, so no run-time checks are compiled in.
+template <bool FAST = false>
 __device__ __forceinline__ const char* src_ptr(const ReduceProblem& p, int n, int g) {
-  if (p.ptrs != nullptr) {
+  if (!FAST && p.ptrs != nullptr) {
     const int idx = n * p.gpus + g;
     return idx == p.override_index ? reinterpret_cast<const char*>(p.override_ptr)
-                                   : reinterpret_cast<const char*>(p.ptrs[idx]);
+                                   : ld_pointer(p.ptrs, idx);
   }
   return p.base + (size_t)n * p.stride_n + (size_t)g * p.stride_g;
 }
 
-template <bool IN_BF16>
-__device__ __forceinline__ void unpack(u32x4 v, float* f) {
-  if (IN_BF16) {
+// W packed words -> fp32 values (2 per word for bf16, 1 per word for fp32)
+template <bool IN_BF16, int W>
+__device__ __forceinline__ void unpack(const uint32_t* w, float* f) {
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      f[2 * k] = bf16_lo(v[k]);
-      f[2 * k + 1] = bf16_hi(v[k]);
+  for (int k = 0; k < W; ++k) {
+    if (IN_BF16) {
+      f[2 * k] = bf16_lo(w[k]);
+      f[2 * k + 1] = bf16_hi(w[k]);
+    } else {
+      f[k] = __uint_as_float(w[k]);
+    }
+  }
+}
+
+// VE consecutive results, starting at element `e`, converted to the output dtype
+template <bool OUT_BF16, int VE, bool ALIGNED>
+__device__ __forceinline__ void store_vals(char* dst, size_t e, const float* a) {
+  if constexpr (OUT_BF16) {
+    if constexpr (VE == 1) {
+      st_elem<true>(dst, e, a[0]);
+    } else {
+      uint32_t w[VE / 2];
+#pragma unroll
+      for (int k = 0; k < VE / 2; ++k) w[k] = pack_bf16(a[2 * k], a[2 * k + 1]);
+      st_words<VE / 2, 2, ALIGNED>(dst, e * 2, w);
     }
   } else {
+    uint32_t w[VE];
 #pragma unroll
-    for (int k = 0; k < 4; ++k) f[k] = __uint_as_float(v[k]);
+    for (int k = 0; k < VE; ++k) w[k] = __float_as_uint(a[k]);
+    if constexpr (VE == 8) {
+      st_words<4, 4, ALIGNED>(dst, e * 4, w);
+      st_words<4, 4, ALIGNED>(dst, e * 4 + 16, w + 4);
+    } else {
+      st_words<VE, 4, ALIGNED>(dst, e * 4, w);
+    }
   }
 }
 
@@ -48,8 +76,8 @@ template <bool IN_BF16, bool OUT_BF16>
 __device__ void reduce_elem(const ReduceProblem& p, size_t e) {
   float acc = 0.0f;
   for (int n = 0; n < p.nodes; ++n) {
-    float t = ld_elem<IN_BF16>(src_ptr(p, n, 0), e);
-    for (int g = 1; g < p.gpus; ++g) t = t + ld_elem<IN_BF16>(src_ptr(p, n, g), e);
+    float t = ld_elem<IN_BF16>(src_ptr<>(p, n, 0), e);
+    for (int g = 1; g < p.gpus; ++g) t = t + ld_elem<IN_BF16>(src_ptr<>(p, n, g), e);
     if (IN_BF16 && p.round_partial) t = round_through_bf16(t);
     if (p.partial != nullptr)
       st_elem<IN_BF16>(reinterpret_cast<char*>(p.partial), (size_t)n * p.count + e, t);
@@ -59,194 +87,144 @@ __device__ void reduce_elem(const ReduceProblem& p, size_t e) {
 }
 
 // ------------------------------------------------------------------------------------------
-// streaming path.  A tile is kBlock*U consecutive 16-byte input vectors; thread t owns
-// vectors t, t + kBlock, ... of the tile, so every wavefront load is one contiguous 1 KB.
-// M > 0: exactly M sources per node, fully unrolled (M loads in flight per lane and vector);
+// streaming path.  A thread owns one vector of W 32-bit words per source; a tile is kBlock
+// consecutive vectors, so every wavefront load is one contiguous 256*W bytes.
+// M > 0: exactly M sources per node, fully unrolled (M loads in flight per lane);
 // M == 0: any number of sources, walked in batches of four.
-template <bool IN_BF16, bool OUT_BF16, int M, int U>
+// W is picked so that a lane keeps about 32 bytes of loads in flight (M * 4W): measured on
+// MI355X, more bytes per lane at full occupancy lowers the achieved HBM bandwidth.
+template <bool IN_BF16, bool OUT_BF16, int M, int W, bool FAST>
 __device__ __forceinline__ void reduce_tile(const ReduceProblem& p, size_t tile) {
-  constexpr int VE = IN_BF16 ? 8 : 4;  // elements per 16-byte input vector
+  constexpr int VE = IN_BF16 ? 2 * W : W;  // elements per vector
   constexpr int ES = IN_BF16 ? 2 : 4;
+  constexpr int VB = 4 * W;  // bytes per vector
   const size_t nvec = p.count / VE;
-  const size_t ntiles_vec = (nvec + (size_t)kBlock * U - 1) / ((size_t)kBlock * U);
+  const size_t ntiles_vec = (nvec + kBlock - 1) / kBlock;
   const size_t last_tile = ntiles_vec == 0 ? 0 : ntiles_vec - 1;
+  const size_t v = tile * kBlock + threadIdx.x;
+  const size_t tile_off = tile * ((size_t)kBlock * VB);  // wave-uniform byte offset of the tile
+  const uint32_t lane_off = threadIdx.x * VB;            // this lane's offset inside the tile
 
-  size_t v[U];
-  bool live[U];
+  if (v < nvec) {
+    float acc[VE];
+    for (int n = 0; n < p.nodes; ++n) {
+      float t[VE];
+      if (M > 0) {
+        const char* sp[M > 0 ? M : 1];
 #pragma unroll
-  for (int u = 0; u < U; ++u) {
-    v[u] = tile * ((size_t)kBlock * U) + (size_t)u * kBlock + threadIdx.x;
-    live[u] = v[u] < nvec;
-  }
-
-  float acc[U][VE];
-  for (int n = 0; n < p.nodes; ++n) {
-    float t[U][VE];
-    if (M > 0) {
-      u32x4 raw[M > 0 ? M : 1][U];
+        for (int g = 0; g < M; ++g) sp[g] = src_ptr<FAST>(p, n, g) + tile_off;
+        uint32_t raw[M > 0 ? M : 1][W];
 #pragma unroll
-      for (int g = 0; g < M; ++g) {
-        const char* sp = src_ptr(p, n, g);
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-          raw[g][u] = u32x4{0u, 0u, 0u, 0u};
-          if (live[u]) raw[g][u] = ld16<ES>(sp, v[u] * 16);
-        }
-      }
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        unpack<IN_BF16>(raw[0][u], t[u]);
+        for (int g = 0; g < M; ++g) ld_words<W, ES, FAST>(sp[g], lane_off, raw[g]);
+        unpack<IN_BF16, W>(raw[0], t);
 #pragma unroll
         for (int g = 1; g < M; ++g) {
           float x[VE];
-          unpack<IN_BF16>(raw[g][u], x);
+          unpack<IN_BF16, W>(raw[g], x);
 #pragma unroll
-          for (int k = 0; k < VE; ++k) t[u][k] = t[u][k] + x[k];
+          for (int k = 0; k < VE; ++k) t[k] = t[k] + x[k];
         }
-      }
-    } else {
-      {
-        const char* sp = src_ptr(p, n, 0);
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-          u32x4 r = {0u, 0u, 0u, 0u};
-          if (live[u]) r = ld16<ES>(sp, v[u] * 16);
-          unpack<IN_BF16>(r, t[u]);
+      } else {
+        {
+          uint32_t r[W];
+          ld_words<W, ES, FAST>(src_ptr<FAST>(p, n, 0) + tile_off, lane_off, r);
+          unpack<IN_BF16, W>(r, t);
         }
-      }
-      int g = 1;
-      for (; g + 4 <= p.gpus; g += 4) {
-        u32x4 raw[4][U];
+        int g = 1;
+        for (; g + 4 <= p.gpus; g += 4) {
+          const char* sp[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const char* sp = src_ptr(p, n, g + j);
+          for (int j = 0; j < 4; ++j) sp[j] = src_ptr<FAST>(p, n, g + j) + tile_off;
+          uint32_t raw[4][W];
 #pragma unroll
-          for (int u = 0; u < U; ++u) {
-            raw[j][u] = u32x4{0u, 0u, 0u, 0u};
-            if (live[u]) raw[j][u] = ld16<ES>(sp, v[u] * 16);
-          }
-        }
+          for (int j = 0; j < 4; ++j) ld_words<W, ES, FAST>(sp[j], lane_off, raw[j]);
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-          for (int u = 0; u < U; ++u) {
+          for (int j = 0; j < 4; ++j) {
             float x[VE];
-            unpack<IN_BF16>(raw[j][u], x);
+            unpack<IN_BF16, W>(raw[j], x);
 #pragma unroll
-            for (int k = 0; k < VE; ++k) t[u][k] = t[u][k] + x[k];
+            for (int k = 0; k < VE; ++k) t[k] = t[k] + x[k];
           }
-      }
-      for (; g < p.gpus; ++g) {
-        const char* sp = src_ptr(p, n, g);
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-          u32x4 r = {0u, 0u, 0u, 0u};
-          if (live[u]) r = ld16<ES>(sp, v[u] * 16);
+        }
+        for (; g < p.gpus; ++g) {
+          uint32_t r[W];
+          ld_words<W, ES, FAST>(src_ptr<FAST>(p, n, g) + tile_off, lane_off, r);
           float x[VE];
-          unpack<IN_BF16>(r, x);
+          unpack<IN_BF16, W>(r, x);
 #pragma unroll
-          for (int k = 0; k < VE; ++k) t[u][k] = t[u][k] + x[k];
+          for (int k = 0; k < VE; ++k) t[k] = t[k] + x[k];
         }
       }
-    }
 
-    // node partial: round through the message dtype, optionally keep it
-    const bool keep = p.partial != nullptr;
-    if (IN_BF16 && (p.round_partial || keep)) {
+      // node partial: round through the message dtype, optionally keep it
+      const bool keep = p.partial != nullptr;
+      char* prow = reinterpret_cast<char*>(p.partial) + (size_t)n * p.count * ES + tile_off;
+      if (IN_BF16) {
+        if (p.round_partial || keep) {
+          uint32_t w[W];
 #pragma unroll
-      for (int u = 0; u < U; ++u) {
-        u32x4 w;
+          for (int k = 0; k < W; ++k) w[k] = pack_bf16(t[2 * k], t[2 * k + 1]);
+          if (keep) st_words<W, ES, FAST>(prow, lane_off, w);
+          if (p.round_partial) unpack<true, W>(w, t);
+        }
+      } else if (keep) {
+        uint32_t w[W];
 #pragma unroll
-        for (int k = 0; k < 4; ++k) w[k] = pack_bf16(t[u][2 * k], t[u][2 * k + 1]);
-        if (keep && live[u])
-          st16<ES>(reinterpret_cast<char*>(p.partial) + (size_t)n * p.count * ES, v[u] * 16, w);
-        if (p.round_partial) unpack<true>(w, t[u]);
+        for (int k = 0; k < W; ++k) w[k] = __float_as_uint(t[k]);
+        st_words<W, ES, FAST>(prow, lane_off, w);
       }
-    } else if (keep) {
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        u32x4 w;
-#pragma unroll
-        for (int k = 0; k < 4; ++k) w[k] = __float_as_uint(t[u][k]);
-        if (live[u])
-          st16<ES>(reinterpret_cast<char*>(p.partial) + (size_t)n * p.count * ES, v[u] * 16, w);
-      }
-    }
 
-    if (n == 0) {
 #pragma unroll
-      for (int u = 0; u < U; ++u)
-#pragma unroll
-        for (int k = 0; k < VE; ++k) acc[u][k] = t[u][k];
-    } else {
-#pragma unroll
-      for (int u = 0; u < U; ++u)
-#pragma unroll
-        for (int k = 0; k < VE; ++k) acc[u][k] = acc[u][k] + t[u][k];
+      for (int k = 0; k < VE; ++k) acc[k] = (n == 0) ? t[k] : acc[k] + t[k];
     }
+    store_vals<OUT_BF16, VE, FAST>(reinterpret_cast<char*>(p.dst), v * VE, acc);
   }
 
-  char* dst = reinterpret_cast<char*>(p.dst);
-#pragma unroll
-  for (int u = 0; u < U; ++u) {
-    if (!live[u]) continue;
-    if (IN_BF16 && OUT_BF16) {
-      u32x4 w;
-#pragma unroll
-      for (int k = 0; k < 4; ++k) w[k] = pack_bf16(acc[u][2 * k], acc[u][2 * k + 1]);
-      st16<2>(dst, v[u] * 16, w);
-    } else if (IN_BF16 && !OUT_BF16) {
-      u32x4 w0, w1;
-#pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        w0[k] = __float_as_uint(acc[u][k]);
-        w1[k] = __float_as_uint(acc[u][4 + k]);
-      }
-      st16<4>(dst, v[u] * 32, w0);
-      st16<4>(dst, v[u] * 32 + 16, w1);
-    } else if (!IN_BF16 && OUT_BF16) {
-      u32x2 w = {pack_bf16(acc[u][0], acc[u][1]), pack_bf16(acc[u][2], acc[u][3])};
-      st8_bf16(dst, v[u] * 8, w);
-    } else {
-      u32x4 w;
-#pragma unroll
-      for (int k = 0; k < 4; ++k) w[k] = __float_as_uint(acc[u][k]);
-      st16<4>(dst, v[u] * 16, w);
-    }
-  }
-
-  // ragged tail (count not a multiple of the vector width): fewer than VE elements
+  // ragged tail (count not a multiple of the vector width): fewer than VE <= 8 elements
   if (tile == last_tile) {
     const size_t e = nvec * VE + threadIdx.x;
     if (e < p.count) reduce_elem<IN_BF16, OUT_BF16>(p, e);
   }
 }
 
-template <bool IN_BF16, bool OUT_BF16, int M, int U>
-__global__ __launch_bounds__(kBlock) void k_reduce(ReduceProblem p) {
-  reduce_tile<IN_BF16, OUT_BF16, M, U>(p, blockIdx.x);
-}
-
-// inner unroll and vectors per thread chosen for a source count
-constexpr int unroll_u(int m) { return m == 0 ? 2 : (m <= 2 ? 4 : (m == 4 ? 2 : 1)); }
+// words per lane and load for a given inner unroll
+constexpr int words_for(int m) { return m == 0 ? 2 : (m <= 2 ? 4 : (m == 4 ? 2 : 1)); }
 inline int pick_m(int gpus) {
   return (gpus == 1 || gpus == 2 || gpus == 4 || gpus == 8 || gpus == 16) ? gpus : 0;
 }
 
+template <bool IN_BF16, bool OUT_BF16, int M, bool FAST>
+__global__ __launch_bounds__(kBlock) void k_reduce(ReduceProblem p) {
+  reduce_tile<IN_BF16, OUT_BF16, M, words_for(M), FAST>(p, blockIdx.x);
+}
+
 inline size_t tiles_for(size_t count, int m, bool in_bf16) {
-  const size_t ve = in_bf16 ? 8 : 4;
-  const size_t per_tile = (size_t)kBlock * unroll_u(m);
+  const size_t ve = (size_t)words_for(m) * (in_bf16 ? 2 : 1);
   const size_t nvec = count / ve;
-  const size_t t = (nvec + per_tile - 1) / per_tile;
+  const size_t t = (nvec + kBlock - 1) / kBlock;
   return t == 0 ? 1 : t;  // a lone ragged tail still needs one block
+}
+
+inline bool is16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+// strided sources with every base, stride, row and output 16-byte aligned
+inline bool fast_eligible(const ReduceProblem& p, bool in_bf16) {
+  const size_t es = in_bf16 ? 2 : 4;
+  return p.ptrs == nullptr && is16(p.base) && is16(p.dst) && p.stride_n % 16 == 0 &&
+         p.stride_g % 16 == 0 &&
+         (p.partial == nullptr || (is16(p.partial) && (p.count * es) % 16 == 0));
 }
 
 template <bool IN_BF16, bool OUT_BF16, int M>
 hipError_t launch_m(const ReduceProblem& p, hipStream_t st) {
   const size_t tiles = tiles_for(p.count, M, IN_BF16);
   if (tiles > 0x7FFFFFFFull) return hipErrorInvalidValue;
-  hipLaunchKernelGGL((k_reduce<IN_BF16, OUT_BF16, M, unroll_u(M)>), dim3((unsigned)tiles),
-                     dim3(kBlock), 0, st, p);
+  if (fast_eligible(p, IN_BF16))
+    hipLaunchKernelGGL((k_reduce<IN_BF16, OUT_BF16, M, true>), dim3((unsigned)tiles), dim3(kBlock), 0,
+                       st, p);
+  else
+    hipLaunchKernelGGL((k_reduce<IN_BF16, OUT_BF16, M, false>), dim3((unsigned)tiles), dim3(kBlock), 0,
+                       st, p);
   return hipGetLastError();
 }
 
@@ -266,14 +244,18 @@ hipError_t launch_io(const ReduceProblem& p, hipStream_t st) {
 // LDS-staged two-level reduction for many small chunks.
 //   block  = 16 wavefronts, owns E = 64 * EPL consecutive elements (EPL = elements in one
 //            32-bit word: 1 for fp32, 2 for bf16) of every source;
-//   wave w = sums the M sources of nodes w, w+16, ... of the current node tile (the M
-//            loads of a node are independent, so they are all in flight together) and
-//            parks the rounded node partial in LDS as fp32;
+//   wave w = sums the M sources of nodes w, w+16, ... of the current node tile, two nodes
+//            per trip so that 2*M independent loads are in flight per lane, and parks the
+//            rounded node partial in LDS as fp32;
 //   then E threads add the parked partials in ascending node order.
 // Which wave computed which partial never changes the value: the association is fixed by
-// the node-major order, not by the schedule.
+// the node-major order, not by the schedule.  When the sources come as a pointer array the
+// block first copies the array into LDS, so that no data load waits on a pointer load.
 constexpr int kLdsBlock = 1024;
 constexpr int kLdsWaves = kLdsBlock / 64;
+constexpr int kLdsNodesPerTrip = 2;
+constexpr size_t kLdsStageBytes = 32 * 1024;  // parked partials
+constexpr size_t kLdsTableBytes = 32 * 1024;  // pointer table (up to 4096 sources)
 
 template <bool IN_BF16, int EPL>
 __device__ __forceinline__ void ld_word(const char* sp, size_t le, size_t count, float* x) {
@@ -292,45 +274,84 @@ __device__ __forceinline__ void ld_word(const char* sp, size_t le, size_t count,
 }
 
 template <bool IN_BF16, bool OUT_BF16, int M>
-__global__ __launch_bounds__(kLdsBlock) void k_reduce2l_lds(ReduceProblem p, int node_tile) {
-  extern __shared__ float parked[];  // [node_tile][E]
+__global__ __launch_bounds__(kLdsBlock) void k_reduce2l_lds(ReduceProblem p, int node_tile,
+                                                            int table_in_lds) {
+  extern __shared__ __align__(16) unsigned char lds_raw[];
+  float* parked = reinterpret_cast<float*>(lds_raw);  // [node_tile][E]
+  const char** table = reinterpret_cast<const char**>(lds_raw + kLdsStageBytes);
   constexpr int EPL = IN_BF16 ? 2 : 1;
   constexpr int E = 64 * EPL;
+  constexpr int MM = M > 0 ? M : 1;
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
   const size_t e0 = (size_t)blockIdx.x * E;
   const size_t le = e0 + (size_t)lane * EPL;
+  const int gpus = M > 0 ? M : p.gpus;
+
+  if (table_in_lds) {
+    const int nsrc = p.nodes * gpus;
+    for (int s = threadIdx.x; s < nsrc; s += kLdsBlock)
+      table[s] = s == p.override_index ? reinterpret_cast<const char*>(p.override_ptr)
+                                       : ld_pointer_lane(p.ptrs, (size_t)s);
+    __syncthreads();
+  }
+  auto source = [&](int n, int g) -> const char* {
+    return table_in_lds ? table[n * gpus + g] : src_ptr<>(p, n, g);
+  };
 
   float acc = 0.0f;
   for (int n0 = 0; n0 < p.nodes; n0 += node_tile) {
     const int tn = min(node_tile, p.nodes - n0);
-#pragma unroll 2
-    for (int j = wave; j < tn; j += kLdsWaves) {
-      const int n = n0 + j;
-      float t[EPL];
+    for (int j0 = wave; j0 < tn; j0 += kLdsWaves * kLdsNodesPerTrip) {
+      float t[kLdsNodesPerTrip][EPL];
       if (M > 0) {
-        float x[M > 0 ? M : 1][EPL];
+        float x[kLdsNodesPerTrip][MM][EPL];
 #pragma unroll
-        for (int g = 0; g < M; ++g) ld_word<IN_BF16, EPL>(src_ptr(p, n, g), le, p.count, x[g]);
+        for (int q = 0; q < kLdsNodesPerTrip; ++q) {
+          const int j = j0 + q * kLdsWaves;
+          if (j < tn) {
 #pragma unroll
-        for (int k = 0; k < EPL; ++k) {
-          t[k] = x[0][k];
+            for (int g = 0; g < MM; ++g) ld_word<IN_BF16, EPL>(source(n0 + j, g), le, p.count, x[q][g]);
+          }
+        }
 #pragma unroll
-          for (int g = 1; g < M; ++g) t[k] = t[k] + x[g][k];
+        for (int q = 0; q < kLdsNodesPerTrip; ++q) {
+          const int j = j0 + q * kLdsWaves;
+          if (j < tn) {
+#pragma unroll
+            for (int k = 0; k < EPL; ++k) {
+              t[q][k] = x[q][0][k];
+#pragma unroll
+              for (int g = 1; g < MM; ++g) t[q][k] = t[q][k] + x[q][g][k];
+            }
+          }
         }
       } else {
-        ld_word<IN_BF16, EPL>(src_ptr(p, n, 0), le, p.count, t);
-        for (int g = 1; g < p.gpus; ++g) {
-          float x[EPL];
-          ld_word<IN_BF16, EPL>(src_ptr(p, n, g), le, p.count, x);
 #pragma unroll
-          for (int k = 0; k < EPL; ++k) t[k] = t[k] + x[k];
+        for (int q = 0; q < kLdsNodesPerTrip; ++q) {
+          const int j = j0 + q * kLdsWaves;
+          if (j < tn) {
+            ld_word<IN_BF16, EPL>(source(n0 + j, 0), le, p.count, t[q]);
+            for (int g = 1; g < gpus; ++g) {
+              float x[EPL];
+              ld_word<IN_BF16, EPL>(source(n0 + j, g), le, p.count, x);
+#pragma unroll
+              for (int k = 0; k < EPL; ++k) t[q][k] = t[q][k] + x[k];
+            }
+          }
         }
       }
 #pragma unroll
-      for (int k = 0; k < EPL; ++k) {
-        if (IN_BF16 && p.round_partial) t[k] = round_through_bf16(t[k]);
-        parked[j * E + lane * EPL + k] = t[k];
+      for (int q = 0; q < kLdsNodesPerTrip; ++q) {
+        const int j = j0 + q * kLdsWaves;
+        if (j < tn) {
+#pragma unroll
+          for (int k = 0; k < EPL; ++k) {
+            float r = t[q][k];
+            if (IN_BF16 && p.round_partial) r = round_through_bf16(r);
+            parked[j * E + lane * EPL + k] = r;
+          }
+        }
       }
     }
     __syncthreads();
@@ -352,13 +373,15 @@ __global__ __launch_bounds__(kLdsBlock) void k_reduce2l_lds(ReduceProblem p, int
 template <bool IN_BF16, bool OUT_BF16, int M>
 hipError_t launch_lds_m(const ReduceProblem& p, hipStream_t st) {
   constexpr int E = IN_BF16 ? 128 : 64;
-  const int max_tile = (64 * 1024) / (E * 4);  // 64 KB of LDS per block
+  const int max_tile = (int)(kLdsStageBytes / (E * sizeof(float)));
   const int node_tile = p.nodes < max_tile ? p.nodes : max_tile;
   const size_t blocks = (p.count + E - 1) / E;
   if (blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
-  const size_t lds_bytes = (size_t)node_tile * E * sizeof(float);
+  const size_t nsrc = (size_t)p.nodes * (size_t)p.gpus;
+  const int table_in_lds = p.ptrs != nullptr && nsrc * sizeof(void*) <= kLdsTableBytes;
+  const size_t lds_bytes = kLdsStageBytes + (table_in_lds ? nsrc * sizeof(void*) : 0);
   hipLaunchKernelGGL((k_reduce2l_lds<IN_BF16, OUT_BF16, M>), dim3((unsigned)blocks),
-                     dim3(kLdsBlock), lds_bytes, st, p, node_tile);
+                     dim3(kLdsBlock), lds_bytes, st, p, node_tile, table_in_lds);
   return hipGetLastError();
 }
 
@@ -376,7 +399,7 @@ hipError_t launch_lds_io(const ReduceProblem& p, hipStream_t st) {
 // ------------------------------------------------------------------------------------------
 // batched two-level reduce-scatter share: a flat tile space over all buckets, one launch
 // per phase.  Each block finds its bucket by bisection in the tile prefix (kernel argument).
-template <bool BF16, int M, int PHASE>
+template <bool BF16, int M, int PHASE, bool FAST>
 __global__ __launch_bounds__(kBlock) void k_rs_batched(const pccl_bucket_t* __restrict__ buckets,
                                                        BatchTiles tiles, int nbuckets, int nodes,
                                                        int gpus) {
@@ -411,7 +434,7 @@ __global__ __launch_bounds__(kBlock) void k_rs_batched(const pccl_bucket_t* __re
     p.count = b.chunk_count;
     p.gpus = nodes;
   }
-  reduce_tile<BF16, BF16, M, unroll_u(M)>(p, blockIdx.x - tiles.first_tile[lo]);
+  reduce_tile<BF16, BF16, M, words_for(M), FAST>(p, blockIdx.x - tiles.first_tile[lo]);
 }
 
 template <bool BF16, int M, int PHASE>
@@ -428,8 +451,21 @@ hipError_t launch_batched_phase(const pccl_bucket_t* d_buckets, const pccl_bucke
   }
   for (int b = nbuckets; b <= kMaxBuckets; ++b) tiles.first_tile[b] = (uint32_t)total;
   if (total == 0) return hipSuccess;
-  hipLaunchKernelGGL((k_rs_batched<BF16, M, PHASE>), dim3((unsigned)total), dim3(kBlock), 0, st,
-                     d_buckets, tiles, nbuckets, nodes, gpus);
+  // every bucket 16-byte aligned in all its bases, strides and rows -> no run-time checks
+  bool fast = true;
+  const size_t es = BF16 ? 2 : 4;
+  for (int b = 0; b < nbuckets; ++b) {
+    const pccl_bucket_t& k = h_buckets[b];
+    if (k.chunk_count == 0) continue;
+    fast = fast && is16(k.shard) && is16(k.partial) && is16(k.intra_base) &&
+           k.intra_stride_bytes % 16 == 0 && (k.chunk_count * es) % 16 == 0;
+  }
+  if (fast)
+    hipLaunchKernelGGL((k_rs_batched<BF16, M, PHASE, true>), dim3((unsigned)total), dim3(kBlock), 0,
+                       st, d_buckets, tiles, nbuckets, nodes, gpus);
+  else
+    hipLaunchKernelGGL((k_rs_batched<BF16, M, PHASE, false>), dim3((unsigned)total), dim3(kBlock), 0,
+                       st, d_buckets, tiles, nbuckets, nodes, gpus);
   return hipGetLastError();
 }
 

@@ -392,6 +392,33 @@ def test_cfg3_two_level_reduce_scatter_full_size():
     packed.check()
 
 
+def test_cfg3_in_the_benchmarked_launch_configuration():
+    """The call sequence bench.py times, at full size: pack, reduce-scatter share with the 15
+    foreign chunks behind a device pointer array, reassemble."""
+    w = W.cfg3()
+    n = w.ranks * w.chunk
+    my = 5
+    msg = W.draw(w, n, DEV, seed_offset=1)
+    x = W.two_level_input(w, DEV, seed_offset=2)
+    inter = W.draw(w, w.nodes * w.chunk, DEV, seed_offset=3).view(w.nodes, w.chunk)
+    d_inter = pccl.device_pointer_array([inter[j] for j in range(w.nodes)])
+    gathered = W.draw(w, n, DEV, seed_offset=4)
+    packed, out = Guarded(n, BF16), Guarded(n, BF16)
+    partial, shard = Guarded(w.nodes * w.chunk, BF16), Guarded(w.chunk, BF16)
+    pccl.pccl_hier_pack(packed.view, msg, w.nodes, w.gpus)
+    pccl.pccl_reduce_scatter_local(shard.view, partial.view, x, d_inter=d_inter, my_node=my)
+    pccl.pccl_allgather_reassemble(out.view, src=gathered, nodes=w.nodes, gpus_per_node=w.gpus)
+    _sync()
+    assert same_bits(to_np(packed.view), oracle.hier_pack(to_np(msg), w.nodes, w.gpus))
+    want_shard, want_partial = oracle.reduce_scatter_local(
+        to_np(x), my_node=my, inter=[to_np(inter[j]) for j in range(w.nodes)], nthreads=16)
+    assert same_bits(to_np(partial.view), want_partial)
+    assert same_bits(to_np(shard.view), want_shard), first_diff(to_np(shard.view), want_shard)
+    assert same_bits(to_np(out.view), oracle.hier_unpack(to_np(gathered), w.nodes, w.gpus))
+    for gbuf in (packed, out, partial, shard):
+        gbuf.check()
+
+
 # ------------------------------------------------------------------------------- batched buckets
 def _make_buckets(w, sizes_bytes, device):
     buckets, hosts = [], []
