@@ -102,6 +102,9 @@ def time_calls(fn_list, trials=10, warm=3):
         fn_list[k % len(fn_list)]()
     ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(trials)]
     torch.cuda.synchronize()
+    # keep the GPU busy while the host enqueues, so that the timed calls run back to back and
+    # an event pair brackets the kernels, not the host's launch latency
+    torch.cuda._sleep(2_000_000)
     for k in range(trials):
         ev[k][0].record()
         fn_list[k % len(fn_list)]()

@@ -249,20 +249,27 @@ hipError_t launch_io(const ReduceProblem& p, hipStream_t st) {
 //            rounded node partial in LDS as fp32;
 //   then E threads add the parked partials in ascending node order.
 // Which wave computed which partial never changes the value: the association is fixed by
-// the node-major order, not by the schedule.  When the sources come as a pointer array the
-// block first copies the array into LDS, so that no data load waits on a pointer load.
+// the node-major order, not by the schedule.  The block first writes every source address
+// into an LDS table (copied from the pointer array, or computed from the strides), so that
+// no data load waits on a pointer load; a block whose slice is complete and whose sources are
+// word-aligned then runs a body without any per-load check, which lets all loads of a trip
+// issue back to back.
 constexpr int kLdsBlock = 1024;
 constexpr int kLdsWaves = kLdsBlock / 64;
 constexpr int kLdsNodesPerTrip = 2;
 constexpr size_t kLdsStageBytes = 32 * 1024;  // parked partials
-constexpr size_t kLdsTableBytes = 32 * 1024;  // pointer table (up to 4096 sources)
+constexpr size_t kLdsTableBytes = 32 * 1024;  // source address table (up to 4096 sources)
 
-template <bool IN_BF16, int EPL>
+// one 32-bit word of a source as EPL fp32 values; CHECKED adds bounds and alignment handling
+template <bool IN_BF16, int EPL, bool CHECKED>
 __device__ __forceinline__ void ld_word(const char* sp, size_t le, size_t count, float* x) {
   if (!IN_BF16) {
-    x[0] = (le < count) ? ld_stream<float>(sp + 4 * le) : 0.0f;
+    if (CHECKED)
+      x[0] = (le < count) ? ld_stream<float>(sp + 4 * le) : 0.0f;
+    else
+      x[0] = ld_stream<float>(sp + 4 * le);
   } else {
-    if (le + 1 < count && aligned_to(sp, 4)) {
+    if (!CHECKED || (le + 1 < count && aligned_to(sp, 4))) {
       const uint32_t w = ld_stream<uint32_t>(sp + 2 * le);
       x[0] = bf16_lo(w);
       x[1] = bf16_hi(w);
@@ -273,87 +280,126 @@ __device__ __forceinline__ void ld_word(const char* sp, size_t le, size_t count,
   }
 }
 
-template <bool IN_BF16, bool OUT_BF16, int M>
-__global__ __launch_bounds__(kLdsBlock) void k_reduce2l_lds(ReduceProblem p, int node_tile,
-                                                            int table_in_lds) {
+// Sum the M sources of node n (addresses from `srcs`, an LDS table row or a computed list).
+template <bool IN_BF16, int EPL, int M, bool CHECKED, typename SrcFn>
+__device__ __forceinline__ void node_loads(SrcFn src, int n, int gpus, size_t le, size_t count,
+                                           float (*x)[EPL]) {
+#pragma unroll
+  for (int g = 0; g < M; ++g) ld_word<IN_BF16, EPL, CHECKED>(src(n, g), le, count, x[g]);
+}
+
+template <bool IN_BF16, int M, bool TABLE, bool CHECKED>
+__device__ __forceinline__ void lds_fill_tile(const ReduceProblem& p, const char* const* table,
+                                              float* parked, int n0, int tn, int gpus, int wave,
+                                              int lane, size_t le) {
+  constexpr int EPL = IN_BF16 ? 2 : 1;
+  constexpr int E = 64 * EPL;
+  constexpr int MM = M > 0 ? M : 1;
+  auto src = [&](int n, int g) -> const char* {
+    return TABLE ? table[n * gpus + g] : src_ptr<>(p, n, g);
+  };
+  auto park = [&](int j, const float* t) {
+#pragma unroll
+    for (int k = 0; k < EPL; ++k) {
+      float r = t[k];
+      if (IN_BF16 && p.round_partial) r = round_through_bf16(r);
+      parked[j * E + lane * EPL + k] = r;
+    }
+  };
+  for (int j0 = wave; j0 < tn; j0 += kLdsWaves * kLdsNodesPerTrip) {
+    if (M > 0) {
+      const bool full_trip = j0 + (kLdsNodesPerTrip - 1) * kLdsWaves < tn;
+      if (full_trip) {
+        // all source addresses of the trip first (LDS reads), then all loads back to back
+        const char* sp[kLdsNodesPerTrip][MM];
+#pragma unroll
+        for (int q = 0; q < kLdsNodesPerTrip; ++q)
+#pragma unroll
+          for (int g = 0; g < MM; ++g) sp[q][g] = src(n0 + j0 + q * kLdsWaves, g);
+        float x[kLdsNodesPerTrip][MM][EPL];
+#pragma unroll
+        for (int q = 0; q < kLdsNodesPerTrip; ++q)
+#pragma unroll
+          for (int g = 0; g < MM; ++g) ld_word<IN_BF16, EPL, CHECKED>(sp[q][g], le, p.count, x[q][g]);
+#pragma unroll
+        for (int q = 0; q < kLdsNodesPerTrip; ++q) {
+          float t[EPL];
+#pragma unroll
+          for (int k = 0; k < EPL; ++k) {
+            t[k] = x[q][0][k];
+#pragma unroll
+            for (int g = 1; g < MM; ++g) t[k] = t[k] + x[q][g][k];
+          }
+          park(j0 + q * kLdsWaves, t);
+        }
+      } else {
+        for (int j = j0; j < tn; j += kLdsWaves) {
+          float x[MM][EPL];
+          node_loads<IN_BF16, EPL, MM, CHECKED>(src, n0 + j, gpus, le, p.count, x);
+          float t[EPL];
+#pragma unroll
+          for (int k = 0; k < EPL; ++k) {
+            t[k] = x[0][k];
+#pragma unroll
+            for (int g = 1; g < MM; ++g) t[k] = t[k] + x[g][k];
+          }
+          park(j, t);
+        }
+      }
+    } else {
+      for (int j = j0; j < tn && j < j0 + kLdsWaves * kLdsNodesPerTrip; j += kLdsWaves) {
+        float t[EPL];
+        ld_word<IN_BF16, EPL, CHECKED>(src(n0 + j, 0), le, p.count, t);
+        for (int g = 1; g < gpus; ++g) {
+          float x[EPL];
+          ld_word<IN_BF16, EPL, CHECKED>(src(n0 + j, g), le, p.count, x);
+#pragma unroll
+          for (int k = 0; k < EPL; ++k) t[k] = t[k] + x[k];
+        }
+        park(j, t);
+      }
+    }
+  }
+}
+
+template <bool IN_BF16, bool OUT_BF16, int M, bool TABLE>
+__global__ __launch_bounds__(kLdsBlock) void k_reduce2l_lds(ReduceProblem p, int node_tile) {
   extern __shared__ __align__(16) unsigned char lds_raw[];
   float* parked = reinterpret_cast<float*>(lds_raw);  // [node_tile][E]
   const char** table = reinterpret_cast<const char**>(lds_raw + kLdsStageBytes);
   constexpr int EPL = IN_BF16 ? 2 : 1;
   constexpr int E = 64 * EPL;
-  constexpr int MM = M > 0 ? M : 1;
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
   const size_t e0 = (size_t)blockIdx.x * E;
   const size_t le = e0 + (size_t)lane * EPL;
   const int gpus = M > 0 ? M : p.gpus;
 
-  if (table_in_lds) {
+  // source address table; a block-wide vote tells whether every source is word-aligned
+  int unaligned = 0;
+  if (TABLE) {
     const int nsrc = p.nodes * gpus;
-    for (int s = threadIdx.x; s < nsrc; s += kLdsBlock)
-      table[s] = s == p.override_index ? reinterpret_cast<const char*>(p.override_ptr)
-                                       : ld_pointer_lane(p.ptrs, (size_t)s);
-    __syncthreads();
+    for (int s = threadIdx.x; s < nsrc; s += kLdsBlock) {
+      const char* a;
+      if (p.ptrs != nullptr)
+        a = s == p.override_index ? reinterpret_cast<const char*>(p.override_ptr)
+                                  : ld_pointer_lane(p.ptrs, (size_t)s);
+      else
+        a = p.base + (size_t)(s / gpus) * p.stride_n + (size_t)(s % gpus) * p.stride_g;
+      table[s] = a;
+      unaligned |= !aligned_to(a, 4);
+    }
   }
-  auto source = [&](int n, int g) -> const char* {
-    return table_in_lds ? table[n * gpus + g] : src_ptr<>(p, n, g);
-  };
+  const bool all_aligned = TABLE && !__syncthreads_or(unaligned);
+  const bool unchecked = all_aligned && e0 + E <= p.count;  // block-uniform
 
   float acc = 0.0f;
   for (int n0 = 0; n0 < p.nodes; n0 += node_tile) {
     const int tn = min(node_tile, p.nodes - n0);
-    for (int j0 = wave; j0 < tn; j0 += kLdsWaves * kLdsNodesPerTrip) {
-      float t[kLdsNodesPerTrip][EPL];
-      if (M > 0) {
-        float x[kLdsNodesPerTrip][MM][EPL];
-#pragma unroll
-        for (int q = 0; q < kLdsNodesPerTrip; ++q) {
-          const int j = j0 + q * kLdsWaves;
-          if (j < tn) {
-#pragma unroll
-            for (int g = 0; g < MM; ++g) ld_word<IN_BF16, EPL>(source(n0 + j, g), le, p.count, x[q][g]);
-          }
-        }
-#pragma unroll
-        for (int q = 0; q < kLdsNodesPerTrip; ++q) {
-          const int j = j0 + q * kLdsWaves;
-          if (j < tn) {
-#pragma unroll
-            for (int k = 0; k < EPL; ++k) {
-              t[q][k] = x[q][0][k];
-#pragma unroll
-              for (int g = 1; g < MM; ++g) t[q][k] = t[q][k] + x[q][g][k];
-            }
-          }
-        }
-      } else {
-#pragma unroll
-        for (int q = 0; q < kLdsNodesPerTrip; ++q) {
-          const int j = j0 + q * kLdsWaves;
-          if (j < tn) {
-            ld_word<IN_BF16, EPL>(source(n0 + j, 0), le, p.count, t[q]);
-            for (int g = 1; g < gpus; ++g) {
-              float x[EPL];
-              ld_word<IN_BF16, EPL>(source(n0 + j, g), le, p.count, x);
-#pragma unroll
-              for (int k = 0; k < EPL; ++k) t[q][k] = t[q][k] + x[k];
-            }
-          }
-        }
-      }
-#pragma unroll
-      for (int q = 0; q < kLdsNodesPerTrip; ++q) {
-        const int j = j0 + q * kLdsWaves;
-        if (j < tn) {
-#pragma unroll
-          for (int k = 0; k < EPL; ++k) {
-            float r = t[q][k];
-            if (IN_BF16 && p.round_partial) r = round_through_bf16(r);
-            parked[j * E + lane * EPL + k] = r;
-          }
-        }
-      }
-    }
+    if (unchecked)
+      lds_fill_tile<IN_BF16, M, TABLE, false>(p, table, parked, n0, tn, gpus, wave, lane, le);
+    else
+      lds_fill_tile<IN_BF16, M, TABLE, true>(p, table, parked, n0, tn, gpus, wave, lane, le);
     __syncthreads();
     if (threadIdx.x < E) {
       int j = 0;
@@ -378,10 +424,12 @@ hipError_t launch_lds_m(const ReduceProblem& p, hipStream_t st) {
   const size_t blocks = (p.count + E - 1) / E;
   if (blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
   const size_t nsrc = (size_t)p.nodes * (size_t)p.gpus;
-  const int table_in_lds = p.ptrs != nullptr && nsrc * sizeof(void*) <= kLdsTableBytes;
-  const size_t lds_bytes = kLdsStageBytes + (table_in_lds ? nsrc * sizeof(void*) : 0);
-  hipLaunchKernelGGL((k_reduce2l_lds<IN_BF16, OUT_BF16, M>), dim3((unsigned)blocks),
-                     dim3(kLdsBlock), lds_bytes, st, p, node_tile, table_in_lds);
+  if (nsrc * sizeof(void*) <= kLdsTableBytes)
+    hipLaunchKernelGGL((k_reduce2l_lds<IN_BF16, OUT_BF16, M, true>), dim3((unsigned)blocks),
+                       dim3(kLdsBlock), kLdsStageBytes + nsrc * sizeof(void*), st, p, node_tile);
+  else
+    hipLaunchKernelGGL((k_reduce2l_lds<IN_BF16, OUT_BF16, M, false>), dim3((unsigned)blocks),
+                       dim3(kLdsBlock), kLdsStageBytes, st, p, node_tile);
   return hipGetLastError();
 }
 

@@ -259,7 +259,8 @@ def test_cfg4_allreduce_share_full_size():
 # ------------------------------------------------------------------------------- permutations
 @pytest.mark.parametrize("nodes,gpus,chunk_bytes", [
     (2, 3, 1), (4, 8, 2), (3, 2, 6), (4, 8, 16), (4, 8, 4096), (16, 8, 16384 + 48), (5, 3, 17),
-    (7, 2, 16384 * 2 + 3), (256, 8, 260), (1, 8, 100), (8, 1, 100), (2, 2, 100000)])
+    (7, 2, 16384 * 2 + 3), (256, 8, 260), (1, 8, 100), (8, 1, 100), (2, 2, 100000), (70000, 1, 4),
+    (2, 66000, 2), (3, 3, 1024), (3, 3, 1040), (3, 3, 1023)])
 @pytest.mark.parametrize("offset", [0, 1, 4])
 def test_pack_unpack_match_oracle(nodes, gpus, chunk_bytes, offset):
     print("case", nodes, gpus, chunk_bytes, offset, flush=True)
