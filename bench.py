@@ -31,6 +31,10 @@ import paper_2504_18658_amd as pccl  # noqa: E402
 from paper_2504_18658_amd import workloads as W  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
+# HBM bytes per 256 MB k_permute launch from the two rocprofv3 --pmc runs summarised in
+# profiles/bench_all_workloads_hbm_counters.txt: FETCH_SIZE 131084.8 KiB (x 2.000, the factor a
+# plain 256 MiB copy calibrates) + WRITE_SIZE 262209.0 KiB (x 1.000).
+PROFILED_PERMUTE_TRAFFIC_BYTES = int((131084.8 * 2.000 + 262209.0 * 1.000) * 1024)
 MB = 1 << 20
 
 
@@ -179,6 +183,8 @@ def main():
     ap.add_argument("--no-kernel-events", action="store_true", help="do not record per-call events")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-others", action="store_true", help="skip the other four configurations")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run plain 256 MB device-to-device copies (reference for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is the single-GPU local path of the collectives; "
@@ -229,7 +235,7 @@ def main():
         achieved = per_call["pccl_hier_pack"] / (avg_ms * 1e-3) / 1e9
         roofline = dict(kernel="k_permute (pccl_hier_pack / pccl_allgather_reassemble, 256 MB each)",
                         bound="hbm", achieved=round(achieved, 1), peak=HBM_PEAK_GBS, unit="GB/s",
-                        frac=round(achieved / HBM_PEAK_GBS, 4), traffic=None,
+                        frac=round(achieved / HBM_PEAK_GBS, 4), traffic=PROFILED_PERMUTE_TRAFFIC_BYTES,
                         algorithmic_bytes_per_launch=per_call["pccl_hier_pack"],
                         avg_launch_us=round(avg_ms * 1e3, 2), launches=len(perm))
         red = dur["pccl_reduce_scatter_local"]
@@ -262,6 +268,12 @@ def main():
     torch.cuda.empty_cache()
 
     others = None if args.no_others else other_workloads(dev)
+    if args.calibration_copy:
+        a = torch.empty(256 * MB, dtype=torch.uint8, device=dev)
+        b = torch.ones(256 * MB, dtype=torch.uint8, device=dev)
+        for _ in range(5):
+            a.copy_(b)
+        torch.cuda.synchronize()
 
     out = {
         "metric": "achieved HBM GB/s, local reduce + hier permute (one GPU's share of a two-level all-reduce)",
