@@ -45,6 +45,25 @@ __device__ __forceinline__ void unpack(const uint32_t* w, float* f) {
   }
 }
 
+// K vectors from K wave-uniform sources.  Unless the host has vouched for alignment (FAST),
+// one vote over all K addresses picks between a body without per-load checks -- so that the
+// K loads issue back to back -- and the checked, element-wise capable body.
+template <int K, int W, int ES, bool FAST>
+__device__ __forceinline__ void ld_batch(const char* const* sp, uint32_t lane_off, uint32_t (*raw)[W]) {
+  uintptr_t bits = 0;
+  if (!FAST) {
+#pragma unroll
+    for (int k = 0; k < K; ++k) bits |= reinterpret_cast<uintptr_t>(sp[k]);
+  }
+  if (FAST || (bits & (4 * W - 1)) == 0) {
+#pragma unroll
+    for (int k = 0; k < K; ++k) ld_words<W, ES, true>(sp[k], lane_off, raw[k]);
+  } else {
+#pragma unroll
+    for (int k = 0; k < K; ++k) ld_words<W, ES, false>(sp[k], lane_off, raw[k]);
+  }
+}
+
 // VE consecutive results, starting at element `e`, converted to the output dtype
 template <bool OUT_BF16, int VE, bool ALIGNED>
 __device__ __forceinline__ void store_vals(char* dst, size_t e, const float* a) {
@@ -114,8 +133,7 @@ __device__ __forceinline__ void reduce_tile(const ReduceProblem& p, size_t tile)
 #pragma unroll
         for (int g = 0; g < M; ++g) sp[g] = src_ptr<FAST>(p, n, g) + tile_off;
         uint32_t raw[M > 0 ? M : 1][W];
-#pragma unroll
-        for (int g = 0; g < M; ++g) ld_words<W, ES, FAST>(sp[g], lane_off, raw[g]);
+        ld_batch<(M > 0 ? M : 1), W, ES, FAST>(sp, lane_off, raw);
         unpack<IN_BF16, W>(raw[0], t);
 #pragma unroll
         for (int g = 1; g < M; ++g) {
@@ -136,8 +154,7 @@ __device__ __forceinline__ void reduce_tile(const ReduceProblem& p, size_t tile)
 #pragma unroll
           for (int j = 0; j < 4; ++j) sp[j] = src_ptr<FAST>(p, n, g + j) + tile_off;
           uint32_t raw[4][W];
-#pragma unroll
-          for (int j = 0; j < 4; ++j) ld_words<W, ES, FAST>(sp[j], lane_off, raw[j]);
+          ld_batch<4, W, ES, FAST>(sp, lane_off, raw);
 #pragma unroll
           for (int j = 0; j < 4; ++j) {
             float x[VE];
