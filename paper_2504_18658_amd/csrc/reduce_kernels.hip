@@ -261,21 +261,31 @@ hipError_t launch_io(const ReduceProblem& p, hipStream_t st) {
 // LDS-staged two-level reduction for many small chunks.
 //   block  = 16 wavefronts, owns E = 64 * EPL consecutive elements (EPL = elements in one
 //            32-bit word: 1 for fp32, 2 for bf16) of every source;
-//   wave w = sums the M sources of nodes w, w+16, ... of the current node tile, two nodes
-//            per trip so that 2*M independent loads are in flight per lane, and parks the
-//            rounded node partial in LDS as fp32;
+//   tile   = TN = 16 * NPT consecutive nodes; wave w sums the M sources of nodes
+//            w*NPT .. w*NPT+NPT-1 of the tile (NPT*M independent loads in flight per lane)
+//            and parks the rounded node partials in LDS as fp32;
 //   then E threads add the parked partials in ascending node order.
 // Which wave computed which partial never changes the value: the association is fixed by
-// the node-major order, not by the schedule.  The block first writes every source address
-// into an LDS table (copied from the pointer array, or computed from the strides), so that
-// no data load waits on a pointer load; a block whose slice is complete and whose sources are
-// word-aligned then runs a body without any per-load check, which lets all loads of a trip
-// issue back to back.
+// the node-major order, not by the schedule.
+// Two things keep HBM busy from the first to the last cycle of a block:
+//   * no address table and no barrier ahead of the first load: the NPT*M <= 64 source
+//     addresses a wave needs for a tile are consecutive entries of the node-major pointer
+//     array, so ONE per-lane load fetches them (a tile ahead) and v_readlane hands each to
+//     the scalar unit as the base of a load;
+//   * the parking area is double-buffered: the ordered sum of tile k-1 runs while the loads
+//     of tile k are in flight, so only the last tile's sum is exposed.
 constexpr int kLdsBlock = 1024;
 constexpr int kLdsWaves = kLdsBlock / 64;
-constexpr int kLdsNodesPerTrip = 2;
-constexpr size_t kLdsStageBytes = 32 * 1024;  // parked partials
-constexpr size_t kLdsTableBytes = 32 * 1024;  // source address table (up to 4096 sources)
+constexpr int kLdsBatch = 8;  // sources per batch when the per-node count is not a template constant
+
+// nodes per wave and tile: about 32 loads in flight per lane, parking area <= 2 x 32 KB
+constexpr int lds_npt(int m, bool in_bf16) {
+  if (m <= 0) return 1;
+  int npt = 32 / m;
+  const int cap = in_bf16 ? 4 : 8;
+  if (npt > cap) npt = cap;
+  return npt < 1 ? 1 : npt;
+}
 
 // one 32-bit word of a source as EPL fp32 values; CHECKED adds bounds and alignment handling
 template <bool IN_BF16, int EPL, bool CHECKED>
@@ -297,156 +307,153 @@ __device__ __forceinline__ void ld_word(const char* sp, size_t le, size_t count,
   }
 }
 
-// Sum the M sources of node n (addresses from `srcs`, an LDS table row or a computed list).
-template <bool IN_BF16, int EPL, int M, bool CHECKED, typename SrcFn>
-__device__ __forceinline__ void node_loads(SrcFn src, int n, int gpus, size_t le, size_t count,
-                                           float (*x)[EPL]) {
-#pragma unroll
-  for (int g = 0; g < M; ++g) ld_word<IN_BF16, EPL, CHECKED>(src(n, g), le, count, x[g]);
+// Address of source s = n*gpus + g (per lane; 0 when `valid` is false).
+__device__ __forceinline__ uint64_t lds_lane_src(const ReduceProblem& p, int n, int g, int gpus,
+                                                 bool valid) {
+  if (!valid) return 0;
+  if (p.ptrs != nullptr) {
+    const size_t s = (size_t)n * gpus + g;
+    return (int)s == p.override_index
+               ? reinterpret_cast<uint64_t>(p.override_ptr)
+               : reinterpret_cast<uint64_t>(ld_pointer_lane(p.ptrs, s));
+  }
+  return reinterpret_cast<uint64_t>(p.base + (size_t)n * p.stride_n + (size_t)g * p.stride_g);
 }
 
-template <bool IN_BF16, int M, bool TABLE, bool CHECKED>
-__device__ __forceinline__ void lds_fill_tile(const ReduceProblem& p, const char* const* table,
-                                              float* parked, int n0, int tn, int gpus, int wave,
-                                              int lane, size_t le) {
+// Lane `l`'s 64-bit value as a wave-uniform pointer.
+__device__ __forceinline__ const char* lane_pointer(uint64_t v, int l) {
+  const uint32_t lo = __builtin_amdgcn_readlane((int)(uint32_t)v, l);
+  const uint32_t hi = __builtin_amdgcn_readlane((int)(uint32_t)(v >> 32), l);
+  return reinterpret_cast<const char*>(((uint64_t)hi << 32) | lo);
+}
+
+// acc (+)= parked[0..tn) of one element, ascending node order; `first` starts the chain.
+template <int E>
+__device__ __forceinline__ float ordered_sum(const float* parked, int tn, bool first, float acc) {
+  int j = 0;
+  if (first) {
+    acc = parked[threadIdx.x];
+    j = 1;
+  }
+#pragma unroll 8
+  for (; j < tn; ++j) acc = acc + parked[j * E + threadIdx.x];
+  return acc;
+}
+
+template <bool IN_BF16, bool OUT_BF16, int M>
+__global__ __launch_bounds__(kLdsBlock) void k_reduce2l_lds(ReduceProblem p) {
   constexpr int EPL = IN_BF16 ? 2 : 1;
   constexpr int E = 64 * EPL;
-  constexpr int MM = M > 0 ? M : 1;
-  auto src = [&](int n, int g) -> const char* {
-    return TABLE ? table[n * gpus + g] : src_ptr<>(p, n, g);
-  };
-  auto park = [&](int j, const float* t) {
+  constexpr int NPT = lds_npt(M, IN_BF16);
+  constexpr int TN = kLdsWaves * NPT;
+  constexpr int MM = M > 0 ? M : kLdsBatch;
+  __shared__ float parked[2][TN * E];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const size_t e0 = (size_t)blockIdx.x * E;
+  const size_t le = e0 + (size_t)lane * EPL;
+  const int gpus = M > 0 ? M : p.gpus;
+  const bool slice_full = e0 + E <= p.count;  // block-uniform
+  const int ntiles = (p.nodes + TN - 1) / TN;
+
+  auto park = [&](float* buf, int j, const float* t) {
 #pragma unroll
     for (int k = 0; k < EPL; ++k) {
       float r = t[k];
       if (IN_BF16 && p.round_partial) r = round_through_bf16(r);
-      parked[j * E + lane * EPL + k] = r;
+      buf[j * E + lane * EPL + k] = r;
     }
   };
-  for (int j0 = wave; j0 < tn; j0 += kLdsWaves * kLdsNodesPerTrip) {
-    if (M > 0) {
-      const bool full_trip = j0 + (kLdsNodesPerTrip - 1) * kLdsWaves < tn;
-      if (full_trip) {
-        // all source addresses of the trip first (LDS reads), then all loads back to back
-        const char* sp[kLdsNodesPerTrip][MM];
-#pragma unroll
-        for (int q = 0; q < kLdsNodesPerTrip; ++q)
-#pragma unroll
-          for (int g = 0; g < MM; ++g) sp[q][g] = src(n0 + j0 + q * kLdsWaves, g);
-        float x[kLdsNodesPerTrip][MM][EPL];
-#pragma unroll
-        for (int q = 0; q < kLdsNodesPerTrip; ++q)
-#pragma unroll
-          for (int g = 0; g < MM; ++g) ld_word<IN_BF16, EPL, CHECKED>(sp[q][g], le, p.count, x[q][g]);
-#pragma unroll
-        for (int q = 0; q < kLdsNodesPerTrip; ++q) {
-          float t[EPL];
-#pragma unroll
-          for (int k = 0; k < EPL; ++k) {
-            t[k] = x[q][0][k];
-#pragma unroll
-            for (int g = 1; g < MM; ++g) t[k] = t[k] + x[q][g][k];
-          }
-          park(j0 + q * kLdsWaves, t);
-        }
-      } else {
-        for (int j = j0; j < tn; j += kLdsWaves) {
-          float x[MM][EPL];
-          node_loads<IN_BF16, EPL, MM, CHECKED>(src, n0 + j, gpus, le, p.count, x);
-          float t[EPL];
-#pragma unroll
-          for (int k = 0; k < EPL; ++k) {
-            t[k] = x[0][k];
-#pragma unroll
-            for (int g = 1; g < MM; ++g) t[k] = t[k] + x[g][k];
-          }
-          park(j, t);
-        }
-      }
-    } else {
-      for (int j = j0; j < tn && j < j0 + kLdsWaves * kLdsNodesPerTrip; j += kLdsWaves) {
-        float t[EPL];
-        ld_word<IN_BF16, EPL, CHECKED>(src(n0 + j, 0), le, p.count, t);
-        for (int g = 1; g < gpus; ++g) {
-          float x[EPL];
-          ld_word<IN_BF16, EPL, CHECKED>(src(n0 + j, g), le, p.count, x);
-#pragma unroll
-          for (int k = 0; k < EPL; ++k) t[k] = t[k] + x[k];
-        }
-        park(j, t);
-      }
-    }
-  }
-}
-
-template <bool IN_BF16, bool OUT_BF16, int M, bool TABLE>
-__global__ __launch_bounds__(kLdsBlock) void k_reduce2l_lds(ReduceProblem p, int node_tile) {
-  extern __shared__ __align__(16) unsigned char lds_raw[];
-  float* parked = reinterpret_cast<float*>(lds_raw);  // [node_tile][E]
-  const char** table = reinterpret_cast<const char**>(lds_raw + kLdsStageBytes);
-  constexpr int EPL = IN_BF16 ? 2 : 1;
-  constexpr int E = 64 * EPL;
-  const int lane = threadIdx.x & 63;
-  const int wave = threadIdx.x >> 6;
-  const size_t e0 = (size_t)blockIdx.x * E;
-  const size_t le = e0 + (size_t)lane * EPL;
-  const int gpus = M > 0 ? M : p.gpus;
-
-  // source address table; a block-wide vote tells whether every source is word-aligned
-  int unaligned = 0;
-  if (TABLE) {
-    const int nsrc = p.nodes * gpus;
-    for (int s = threadIdx.x; s < nsrc; s += kLdsBlock) {
-      const char* a;
-      if (p.ptrs != nullptr)
-        a = s == p.override_index ? reinterpret_cast<const char*>(p.override_ptr)
-                                  : ld_pointer_lane(p.ptrs, (size_t)s);
-      else
-        a = p.base + (size_t)(s / gpus) * p.stride_n + (size_t)(s % gpus) * p.stride_g;
-      table[s] = a;
-      unaligned |= !aligned_to(a, 4);
-    }
-  }
-  const bool all_aligned = TABLE && !__syncthreads_or(unaligned);
-  const bool unchecked = all_aligned && e0 + E <= p.count;  // block-uniform
 
   float acc = 0.0f;
-  for (int n0 = 0; n0 < p.nodes; n0 += node_tile) {
-    const int tn = min(node_tile, p.nodes - n0);
-    if (unchecked)
-      lds_fill_tile<IN_BF16, M, TABLE, false>(p, table, parked, n0, tn, gpus, wave, lane, le);
-    else
-      lds_fill_tile<IN_BF16, M, TABLE, true>(p, table, parked, n0, tn, gpus, wave, lane, le);
-    __syncthreads();
-    if (threadIdx.x < E) {
-      int j = 0;
-      if (n0 == 0) {
-        acc = parked[threadIdx.x];
-        j = 1;
+  if constexpr (M > 0) {
+    // lane l < NPT*M of wave w holds the address of source (tile*TN + w*NPT + l/M, l%M)
+    auto fetch = [&](int tile) -> uint64_t {
+      const int n = tile * TN + wave * NPT + lane / M;
+      return lds_lane_src(p, n, lane % M, M, lane < NPT * M && n < p.nodes);
+    };
+    uint64_t cur = fetch(0);
+    for (int k = 0; k < ntiles; ++k) {
+      float* buf = parked[k & 1];
+      const uint64_t nxt = k + 1 < ntiles ? fetch(k + 1) : 0;
+      const int nvalid = min(NPT, max(0, p.nodes - (k * TN + wave * NPT)));  // wave-uniform
+      float x[NPT][MM][EPL];
+      const bool plain = nvalid == NPT && slice_full && !__any((int)(cur & 3));
+      if (plain) {
+        // the whole trip without a check: NPT*M loads issue back to back
+#pragma unroll
+        for (int q = 0; q < NPT; ++q)
+#pragma unroll
+          for (int g = 0; g < MM; ++g)
+            ld_word<IN_BF16, EPL, false>(lane_pointer(cur, q * M + g), le, p.count, x[q][g]);
+      } else {
+#pragma unroll
+        for (int q = 0; q < NPT; ++q)
+          if (q < nvalid) {
+#pragma unroll
+            for (int g = 0; g < MM; ++g)
+              ld_word<IN_BF16, EPL, true>(lane_pointer(cur, q * M + g), le, p.count, x[q][g]);
+          }
       }
-#pragma unroll 8
-      for (; j < tn; ++j) acc = acc + parked[j * E + threadIdx.x];
+      // ordered sum of the previous tile while this tile's loads are in flight
+      if (threadIdx.x < E && k > 0) acc = ordered_sum<E>(parked[(k - 1) & 1], TN, k == 1, acc);
+#pragma unroll
+      for (int q = 0; q < NPT; ++q)
+        if (q < nvalid) {
+          float t[EPL];
+#pragma unroll
+          for (int e = 0; e < EPL; ++e) {
+            t[e] = x[q][0][e];
+#pragma unroll
+            for (int g = 1; g < MM; ++g) t[e] = t[e] + x[q][g][e];
+          }
+          park(buf, wave * NPT + q, t);
+        }
+      cur = nxt;
+      __syncthreads();
     }
-    __syncthreads();
+  } else {
+    // any number of sources per node: one node per wave and tile, sources in batches of 8
+    for (int k = 0; k < ntiles; ++k) {
+      float* buf = parked[k & 1];
+      const int n = k * TN + wave;
+      if (threadIdx.x < E && k > 0) acc = ordered_sum<E>(parked[(k - 1) & 1], TN, k == 1, acc);
+      if (n < p.nodes) {
+        float t[EPL];
+        for (int g0 = 0; g0 < gpus; g0 += kLdsBatch) {
+          const int nb = min(kLdsBatch, gpus - g0);
+          const uint64_t a = lds_lane_src(p, n, g0 + lane, gpus, lane < nb);
+          float x[kLdsBatch][EPL];
+#pragma unroll
+          for (int j = 0; j < kLdsBatch; ++j)
+            if (j < nb) ld_word<IN_BF16, EPL, true>(lane_pointer(a, j), le, p.count, x[j]);
+#pragma unroll
+          for (int j = 0; j < kLdsBatch; ++j)
+            if (j < nb) {
+#pragma unroll
+              for (int e = 0; e < EPL; ++e) t[e] = (g0 + j == 0) ? x[j][e] : t[e] + x[j][e];
+            }
+        }
+        park(buf, wave, t);
+      }
+      __syncthreads();
+    }
   }
-  if (threadIdx.x < E && e0 + threadIdx.x < p.count)
-    st_elem<OUT_BF16>(reinterpret_cast<char*>(p.dst), e0 + threadIdx.x, acc);
+  if (threadIdx.x < E) {
+    const int last = ntiles - 1;
+    acc = ordered_sum<E>(parked[last & 1], p.nodes - last * TN, last == 0, acc);
+    if (e0 + threadIdx.x < p.count)
+      st_elem<OUT_BF16>(reinterpret_cast<char*>(p.dst), e0 + threadIdx.x, acc);
+  }
 }
 
 template <bool IN_BF16, bool OUT_BF16, int M>
 hipError_t launch_lds_m(const ReduceProblem& p, hipStream_t st) {
   constexpr int E = IN_BF16 ? 128 : 64;
-  const int max_tile = (int)(kLdsStageBytes / (E * sizeof(float)));
-  const int node_tile = p.nodes < max_tile ? p.nodes : max_tile;
   const size_t blocks = (p.count + E - 1) / E;
   if (blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
-  const size_t nsrc = (size_t)p.nodes * (size_t)p.gpus;
-  if (nsrc * sizeof(void*) <= kLdsTableBytes)
-    hipLaunchKernelGGL((k_reduce2l_lds<IN_BF16, OUT_BF16, M, true>), dim3((unsigned)blocks),
-                       dim3(kLdsBlock), kLdsStageBytes + nsrc * sizeof(void*), st, p, node_tile);
-  else
-    hipLaunchKernelGGL((k_reduce2l_lds<IN_BF16, OUT_BF16, M, false>), dim3((unsigned)blocks),
-                       dim3(kLdsBlock), kLdsStageBytes, st, p, node_tile);
+  hipLaunchKernelGGL((k_reduce2l_lds<IN_BF16, OUT_BF16, M>), dim3((unsigned)blocks),
+                     dim3(kLdsBlock), 0, st, p);
   return hipGetLastError();
 }
 
@@ -457,6 +464,7 @@ hipError_t launch_lds_io(const ReduceProblem& p, hipStream_t st) {
     case 2: return launch_lds_m<IN_BF16, OUT_BF16, 2>(p, st);
     case 4: return launch_lds_m<IN_BF16, OUT_BF16, 4>(p, st);
     case 8: return launch_lds_m<IN_BF16, OUT_BF16, 8>(p, st);
+    case 16: return launch_lds_m<IN_BF16, OUT_BF16, 16>(p, st);
     default: return launch_lds_m<IN_BF16, OUT_BF16, 0>(p, st);
   }
 }

@@ -204,7 +204,8 @@ def test_local_reduce_ptrs_matches_oracle(in_dt, out_dt, nsrc, count):
 @pytest.mark.parametrize("in_dt,out_dt", [(F32, F32), (BF16, BF16), (BF16, F32), (F32, BF16)])
 @pytest.mark.parametrize("nodes,gpus,count,shift", [
     (2, 2, 5, 0), (4, 8, 1000, 0), (16, 8, 4096, 0), (3, 5, 777, 1), (33, 8, 130, 0),
-    (256, 8, 300, 0), (300, 2, 200, 1), (9, 1, 64, 0), (1, 8, 640, 0), (40, 4, 255, 3)])
+    (256, 8, 300, 0), (300, 2, 200, 1), (9, 1, 64, 0), (1, 8, 640, 0), (40, 4, 255, 3),
+    (130, 8, 100, 0), (70, 16, 96, 0), (129, 1, 200, 1), (65, 4, 128, 0), (17, 3, 260, 1), (33, 11, 64, 0)])
 def test_two_level_ptrs_matches_oracle(force, in_dt, out_dt, nodes, gpus, count, shift):
     print("case", force, in_dt, out_dt, nodes, gpus, count, shift, flush=True)
     nsrc = nodes * gpus
