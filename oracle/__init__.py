@@ -34,6 +34,7 @@ def lib():
         L.pccl_oracle_two_level_reduce.argtypes = [vp, vp, vp, i, i, sz, i, i, i]
         L.pccl_oracle_rs_phase1.argtypes = [vp, vp, i, i, sz, i, i]
         L.pccl_oracle_rs_phase2.argtypes = [vp, vp, i, sz, i, i, i]
+        L.pccl_oracle_accumulate.argtypes = [vp, vp, sz, i, i]
         L.pccl_oracle_hier_pack.argtypes = [vp, vp, i, i, sz]
         L.pccl_oracle_hier_unpack.argtypes = [vp, vp, i, i, sz]
         L.pccl_oracle_allgather_reassemble.argtypes = [vp, vp, i, i, sz]
@@ -156,6 +157,64 @@ def reduce_scatter_local(x, my_node=0, inter=None, out_dt=None, nthreads=1):
         rows = [partial[n] if n == my_node else inter[n] for n in range(nodes)]
     shard = rs_phase2(rows, out_dt, nthreads)
     return shard, partial
+
+
+def accumulate(acc, recv, nthreads=1):
+    """The literal vector-reduction step: returns round_io(acc + recv) (acc is not modified)."""
+    out = np.array(_flat(acc), copy=True)
+    recv = _flat(recv)
+    io_dt = _dt(out)
+    assert recv.size == out.size and _dt(recv) == io_dt
+    _check(lib().pccl_oracle_accumulate(out.ctypes.data, recv.ctypes.data, out.size, io_dt, nthreads),
+           "accumulate")
+    return out.reshape(np.shape(acc))
+
+
+def ring_chunk_at_step(p, rank, step):
+    """Chunk that rank `rank` receives and accumulates at step `step` (0..p-2) of a ring
+    reduce-scatter in which every rank sends to rank+1 and rank r ends up owning chunk r."""
+    return (rank - 2 - step) % p
+
+
+def ring_rs_local(msg, recvs, rank, nthreads=1):
+    """One rank's reduction work in a ring reduce-scatter over p ranks.
+    msg: [p][chunk] local message; recvs[s]: what arrives from rank-1 at step s (p-1 chunks).
+    Returns the message buffer after all steps (chunk `rank` is the owned shard)."""
+    p = msg.shape[0]
+    assert len(recvs) == p - 1
+    buf = np.array(msg, copy=True)
+    for s in range(p - 1):
+        c = ring_chunk_at_step(p, rank, s)
+        buf[c] = accumulate(buf[c], recvs[s], nthreads)
+    return buf
+
+
+def halving_kept_range(p, rank, step):
+    """(first chunk, number of chunks) rank `rank` keeps and accumulates into at step `step`
+    (0..log2(p)-1) of a recursive-halving reduce-scatter: partner = rank xor p/2^(step+1)."""
+    if p < 1 or p & (p - 1):
+        raise ValueError("recursive halving needs a power-of-two rank count")
+    lo, ln = 0, p
+    for t in range(step + 1):
+        dist = p >> (t + 1)
+        ln //= 2
+        if rank & dist:
+            lo += ln
+    return lo, ln
+
+
+def halving_rs_local(msg, recvs, rank, nthreads=1):
+    """One rank's reduction work in a recursive-halving reduce-scatter over p = 2^k ranks.
+    msg: [p][chunk]; recvs[t]: the half received at step t ([p/2^(t+1)][chunk]).
+    Returns the message buffer after all steps (chunk `rank` is the owned shard)."""
+    p = msg.shape[0]
+    steps = p.bit_length() - 1
+    assert len(recvs) == steps
+    buf = np.array(msg, copy=True)
+    for t in range(steps):
+        lo, ln = halving_kept_range(p, rank, t)
+        buf[lo:lo + ln] = accumulate(buf[lo:lo + ln], np.asarray(recvs[t]).reshape(ln, -1), nthreads)
+    return buf
 
 
 def _bytes_view(a):

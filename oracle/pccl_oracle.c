@@ -25,7 +25,14 @@
  *   - the per-node partial is stored in the message dtype (rounded to bf16
  *     with round-to-nearest-even when the message is bf16);
  *   - NaN payloads after bf16 rounding are "parity unpinned": a NaN stays a
- *     quiet NaN with its sign, nothing more is promised.
+ *     quiet NaN with its sign, nothing more is promised;
+ *   - the step-wise inter-node algorithms of Section IV-B (ring, recursive
+ *     halving) add each received buffer into the local one and forward the
+ *     result, so every step's result is stored in the message dtype; ring
+ *     direction is rank -> rank+1 with rank r ending up owner of chunk r, and
+ *     recursive halving starts at partner distance p/2 (power-of-two p only).
+ *     The schedules themselves (which chunk at which step) live in the Python
+ *     wrapper and the whole-world simulation next to this file.
  *
  * Loops run over elements (optionally split over OpenMP threads, which does
  * not change any per-element order of operations).  Build with
@@ -170,6 +177,24 @@ int pccl_oracle_rs_phase1(void* partial, const void* const* pieces, int nodes, i
 int pccl_oracle_rs_phase2(void* shard, const void* const* inter, int nodes, size_t chunk,
                           int io_dt, int out_dt, int nthreads) {
   return pccl_oracle_flat_reduce(shard, inter, nodes, chunk, io_dt, out_dt, nthreads);
+}
+
+/* The paper's GPU vector-reduction kernel in its literal form (Section III-B: a
+ * reduce-scatter made of point-to-point messages plus a GPU vector reduction; Section
+ * IV-B: the local reduction of PCCL_ring and PCCL_rec runs on the GPU): the buffer that
+ * has just been received is added into the local data, in place, and the result is what
+ * the next message carries, so it is stored in the message dtype:
+ *   acc[e] = round_io( acc[e] + recv[e] ) */
+int pccl_oracle_accumulate(void* acc, const void* recv, size_t count, int io_dt, int nthreads) {
+  if (!acc || !recv || !dtype_ok(io_dt)) return ORACLE_BAD_ARG;
+  if (nthreads < 1) nthreads = 1;
+#pragma omp parallel for num_threads(nthreads) schedule(static)
+  for (size_t e = 0; e < count; ++e) {
+    float a = load_as_f32(acc, e, io_dt);
+    float r = load_as_f32(recv, e, io_dt);
+    store_from_f32(acc, e, io_dt, a + r);
+  }
+  return ORACLE_OK;
 }
 
 /* ---- permutations ------------------------------------------------------ */
