@@ -157,6 +157,30 @@ def other_workloads(dev):
           *time_calls([lambda s=s: pccl.pccl_allgather_reassemble(
               s[3], src=s[2], nodes=w.nodes, gpus_per_node=w.gpus) for s in sets]))
     del sets
+    # the paper's literal two-source step (acc += recv) and one rank's replay of its inter-node algorithms
+    w = W.cfg3()
+    n = 64 * MB                                                     # 128 MB of bf16
+    sets = [(W.draw(w, n, dev, seed_offset=40 + k), W.draw(w, n, dev, seed_offset=50 + k)) for k in range(4)]
+    entry("step_accumulate_bf16_128MB", 3 * n * 2,
+          *time_calls([lambda s=s: pccl.pccl_accumulate(s[0], s[1]) for s in sets]))
+    del sets
+    p8, c8 = 8, 16 * MB                                             # flat ring over 8 ranks, 256 MB message
+    sets = [(W.draw(w, p8 * c8, dev, seed_offset=60 + k).view(p8, c8),
+             W.draw(w, (p8 - 1) * c8, dev, seed_offset=70 + k).view(p8 - 1, c8)) for k in range(4)]
+    entry("step_ring_rs_local_8_ranks_bf16_256MB", 3 * (p8 - 1) * c8 * 2,
+          *time_calls([lambda s=s: pccl.pccl_ring_reduce_scatter_local(s[0], s[1], 3) for s in sets]),
+          launches_per_call=p8 - 1)
+    del sets
+    sets = [(W.draw(w, w.nodes * w.chunk, dev, seed_offset=80 + k).view(w.nodes, w.chunk),
+             W.draw(w, (w.nodes - 1) * w.chunk, dev, seed_offset=90 + k).view(w.nodes - 1, w.chunk))
+            for k in range(8)]
+    entry("step_ring_rs_local_16_nodes_bf16_32MB", 3 * (w.nodes - 1) * w.chunk * 2,
+          *time_calls([lambda s=s: pccl.pccl_ring_reduce_scatter_local(s[0], s[1], 5) for s in sets]),
+          launches_per_call=w.nodes - 1)
+    entry("step_halving_rs_local_16_nodes_bf16_32MB", 3 * (w.nodes - 1) * w.chunk * 2,
+          *time_calls([lambda s=s: pccl.pccl_halving_reduce_scatter_local(s[0], s[1].view(-1), 5) for s in sets]),
+          launches_per_call=4)
+    del sets
     # cfg5: 40 ZeRO-3-shaped buckets in one batched call
     w = W.cfg5()
     sizes = w.extra["bucket_bytes"]

@@ -162,6 +162,44 @@ pccl_status_t pccl_reduce_scatter_local_batched(const pccl_bucket_t* d_buckets,
                                                 pccl_dtype_t io_dt, pccl_op_t op,
                                                 pccl_stream_t stream);
 
+/* The vector-reduction kernel in the paper's literal form (Section III-B: a reduce-scatter
+ * from point-to-point messages plus a GPU vector reduction; Section IV-B: PCCL_ring and
+ * PCCL_rec schedule their local reduction on the GPU): the buffer a step has just received
+ * is added into the local data, in place,
+ *     acc[e] = round_io( acc[e] + recv[e] ),   e in [0, count)
+ * both buffers holding `count` elements of io_dt; the sum is stored in io_dt because it is
+ * what the next message carries.  Errors: NULLs; size overflow; acc overlapping recv. */
+pccl_status_t pccl_accumulate(void* acc, const void* recv, size_t count, pccl_dtype_t io_dt,
+                              pccl_op_t op, pccl_stream_t stream);
+
+/* One rank's reduction work in a ring reduce-scatter over `nranks` ranks (Section II-B ring;
+ * Section IV-B PCCL_ring): every rank sends to rank+1 and receives from rank-1, and rank r
+ * ends up owning chunk r.  msg is this rank's message, [nranks][chunk_count] of io_dt,
+ * updated in place.  At step s = 0 .. nranks-2 the chunk received from rank-1,
+ *     recv_s = (const char*)recv_base + s*recv_stride_bytes   (chunk_count elements),
+ * is added into chunk (rank - 2 - s) mod nranks of msg; that chunk is what step s+1 would
+ * forward, and after the last step chunk `rank` of msg is the owned shard.  One kernel per
+ * step is enqueued (in a real run a message arrival separates them).
+ * Errors: NULLs; nranks < 1; rank outside [0, nranks); recv_stride_bytes < chunk bytes when
+ * more than one chunk is received; msg overlapping the recv span. */
+pccl_status_t pccl_ring_reduce_scatter_local(void* msg, const void* recv_base,
+                                             size_t recv_stride_bytes, int nranks, int rank,
+                                             size_t chunk_count, pccl_dtype_t io_dt,
+                                             pccl_op_t op, pccl_stream_t stream);
+
+/* One rank's reduction work in a recursive-halving reduce-scatter over nranks = 2^k ranks
+ * (Section II-B; Section IV-B PCCL_rec).  At step t = 0 .. k-1 the partner is
+ * rank xor (nranks >> (t+1)); the rank keeps the half of its active chunk range that
+ * contains `rank` and adds the received copy of that half into it.  msg is
+ * [nranks][chunk_count] of io_dt, updated in place; recv holds the received halves back to
+ * back: step t's half ([nranks >> (t+1)][chunk_count]) starts at element
+ * chunk_count * (nranks - (nranks >> t)), (nranks-1)*chunk_count elements in all.  After the
+ * last step chunk `rank` of msg is the owned shard.  One kernel per step is enqueued.
+ * Errors: NULLs; nranks not a power of two; rank outside [0, nranks); msg overlapping recv. */
+pccl_status_t pccl_halving_reduce_scatter_local(void* msg, const void* recv, int nranks, int rank,
+                                                size_t chunk_count, pccl_dtype_t io_dt,
+                                                pccl_op_t op, pccl_stream_t stream);
+
 /* Static, human-readable name of a status code (never NULL). */
 const char* pccl_status_string(pccl_status_t status);
 

@@ -19,7 +19,8 @@ PCCL_MAX_BUCKETS = 512
 EXPORTS = (
     "pccl_local_reduce", "pccl_local_reduce_ptrs", "pccl_local_reduce_ptrs_two_level",
     "pccl_hier_pack", "pccl_hier_unpack", "pccl_reduce_scatter_local",
-    "pccl_allgather_reassemble", "pccl_reduce_scatter_local_batched", "pccl_status_string",
+    "pccl_allgather_reassemble", "pccl_reduce_scatter_local_batched", "pccl_accumulate",
+    "pccl_ring_reduce_scatter_local", "pccl_halving_reduce_scatter_local", "pccl_status_string",
 )
 
 
@@ -55,6 +56,9 @@ def lib():
         L.pccl_reduce_scatter_local.argtypes = [vp, vp, vp, sz, vp, i, i, i, sz, i, i, vp]
         L.pccl_allgather_reassemble.argtypes = [vp, vp, vp, i, i, sz, vp]
         L.pccl_reduce_scatter_local_batched.argtypes = [vp, vp, i, i, i, i, i, vp]
+        L.pccl_accumulate.argtypes = [vp, vp, sz, i, i, vp]
+        L.pccl_ring_reduce_scatter_local.argtypes = [vp, vp, sz, i, i, sz, i, i, vp]
+        L.pccl_halving_reduce_scatter_local.argtypes = [vp, vp, i, i, sz, i, i, vp]
         for name in EXPORTS[:-1]:
             getattr(L, name).restype = i
         L.pccl_status_string.argtypes = [i]
@@ -229,3 +233,45 @@ def pccl_reduce_scatter_local_batched(table, stream=None):
     _check(lib().pccl_reduce_scatter_local_batched(
         table.device.data_ptr(), ctypes.addressof(table.host), table.nbuckets, table.nodes, table.gpus,
         dtype_code(table.dtype), PCCL_SUM, _stream(stream)), "pccl_reduce_scatter_local_batched")
+
+
+def pccl_accumulate(acc, recv, stream=None):
+    """acc += recv in place (the literal vector-reduction step); both contiguous, same dtype and size."""
+    if acc.dtype != recv.dtype or acc.numel() != recv.numel() or not acc.is_contiguous() or \
+            not recv.is_contiguous():
+        raise ValueError("pccl_accumulate: acc and recv must be contiguous, of one dtype and size")
+    _check(lib().pccl_accumulate(_dev(acc, "acc"), _dev(recv, "recv"), acc.numel(), dtype_code(acc.dtype),
+                                 PCCL_SUM, _stream(stream)), "pccl_accumulate")
+    return acc
+
+
+def pccl_ring_reduce_scatter_local(msg, recv, rank, stream=None):
+    """One rank's reduction work of a ring reduce-scatter.  msg: [nranks][chunk], updated in place;
+    recv: [nranks-1][chunk] (row s = what arrives at step s; rows may be strided apart)."""
+    nranks, chunk = msg.shape
+    if not msg.is_contiguous() or msg.dtype != recv.dtype:
+        raise ValueError("pccl_ring_reduce_scatter_local: msg must be contiguous, recv of the same dtype")
+    if nranks > 1:
+        base, stride, rows, count = _rows(recv, "recv")
+        if rows != nranks - 1 or count != chunk:
+            raise ValueError("pccl_ring_reduce_scatter_local: recv must be [nranks-1][chunk]")
+    else:
+        base, stride = _dev(recv, "recv"), 0
+    _check(lib().pccl_ring_reduce_scatter_local(_dev(msg, "msg"), base, stride, nranks, rank, chunk,
+                                                dtype_code(msg.dtype), PCCL_SUM, _stream(stream)),
+           "pccl_ring_reduce_scatter_local")
+    return msg
+
+
+def pccl_halving_reduce_scatter_local(msg, recv, rank, stream=None):
+    """One rank's reduction work of a recursive-halving reduce-scatter.  msg: [nranks][chunk],
+    updated in place; recv: the received halves back to back, (nranks-1)*chunk elements."""
+    nranks, chunk = msg.shape
+    if not msg.is_contiguous() or not recv.is_contiguous() or msg.dtype != recv.dtype or \
+            recv.numel() != max(nranks - 1, 0) * chunk and nranks > 1:
+        raise ValueError("pccl_halving_reduce_scatter_local: recv must hold (nranks-1)*chunk elements "
+                         "of msg's dtype, both contiguous")
+    _check(lib().pccl_halving_reduce_scatter_local(_dev(msg, "msg"), _dev(recv, "recv"), nranks, rank, chunk,
+                                                   dtype_code(msg.dtype), PCCL_SUM, _stream(stream)),
+           "pccl_halving_reduce_scatter_local")
+    return msg

@@ -56,6 +56,9 @@ bool prefer_lds_two_level(const ReduceProblem& p, bool in_bf16);
 
 hipError_t launch_permute(const PermuteProblem& p, hipStream_t st);
 
+// acc[e] = round_io(acc[e] + recv[e]) for e < count, in place (the two ranges are disjoint).
+hipError_t launch_accumulate(void* acc, const void* recv, size_t count, bool bf16, hipStream_t st);
+
 // Batched two-level reduce-scatter share; h_buckets is the host copy used to size the grid.
 hipError_t launch_rs_batched(const pccl_bucket_t* d_buckets, const pccl_bucket_t* h_buckets,
                              int nbuckets, int nodes, int gpus, bool bf16, hipStream_t st);

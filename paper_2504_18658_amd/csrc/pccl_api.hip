@@ -295,6 +295,82 @@ pccl_status_t pccl_reduce_scatter_local_batched(const pccl_bucket_t* d_buckets,
   return e == hipErrorInvalidValue ? PCCL_ERR_INVALID : from_hip(e);
 }
 
+pccl_status_t pccl_accumulate(void* acc, const void* recv, size_t count, pccl_dtype_t io_dt,
+                              pccl_op_t op, pccl_stream_t stream) {
+  if (acc == nullptr || recv == nullptr) return PCCL_ERR_NULL;
+  if (pccl_status_t s = check_common(io_dt, io_dt, op)) return s;
+  const size_t es = esize(io_dt);
+  size_t bytes;
+  if (!mul_ok(count, es, &bytes)) return PCCL_ERR_INVALID;
+  if (!elem_aligned(acc, es) || !elem_aligned(recv, es)) return PCCL_ERR_INVALID;
+  if (overlaps(acc, bytes, recv, bytes)) return PCCL_ERR_OVERLAP;
+  const hipError_t e = pccl::launch_accumulate(acc, recv, count, io_dt == PCCL_BF16,
+                                               reinterpret_cast<hipStream_t>(stream));
+  return e == hipErrorInvalidValue ? PCCL_ERR_INVALID : from_hip(e);
+}
+
+pccl_status_t pccl_ring_reduce_scatter_local(void* msg, const void* recv_base,
+                                             size_t recv_stride_bytes, int nranks, int rank,
+                                             size_t chunk_count, pccl_dtype_t io_dt,
+                                             pccl_op_t op, pccl_stream_t stream) {
+  if (msg == nullptr || recv_base == nullptr) return PCCL_ERR_NULL;
+  if (pccl_status_t s = check_common(io_dt, io_dt, op)) return s;
+  if (nranks < 1 || rank < 0 || rank >= nranks) return PCCL_ERR_INVALID;
+  const size_t es = esize(io_dt);
+  size_t chunk_bytes, msg_bytes, span;
+  if (!mul_ok(chunk_count, es, &chunk_bytes) || !mul_ok(chunk_bytes, (size_t)nranks, &msg_bytes))
+    return PCCL_ERR_INVALID;
+  if (!elem_aligned(msg, es) || !elem_aligned(recv_base, es)) return PCCL_ERR_INVALID;
+  const int steps = nranks - 1;
+  if (steps > 1 && (recv_stride_bytes < chunk_bytes || recv_stride_bytes % es != 0))
+    return PCCL_ERR_INVALID;
+  if (!mul_ok((size_t)(steps > 1 ? steps - 1 : 0), steps > 1 ? recv_stride_bytes : 0, &span) ||
+      !add_ok(span, chunk_bytes, &span))
+    return PCCL_ERR_INVALID;
+  if (steps > 0 && overlaps(msg, msg_bytes, recv_base, span)) return PCCL_ERR_OVERLAP;
+  if (chunk_count == 0) return PCCL_OK;
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  for (int s = 0; s < steps; ++s) {
+    // rank r forwards chunk r-1 first; what arrives at step s is chunk r-2-s, further reduced
+    const int c = ((rank - 2 - s) % nranks + nranks) % nranks;
+    const hipError_t e = pccl::launch_accumulate(
+        reinterpret_cast<char*>(msg) + (size_t)c * chunk_bytes,
+        reinterpret_cast<const char*>(recv_base) + (size_t)s * recv_stride_bytes, chunk_count,
+        io_dt == PCCL_BF16, st);
+    if (e != hipSuccess) return e == hipErrorInvalidValue ? PCCL_ERR_INVALID : PCCL_ERR_HIP;
+  }
+  return PCCL_OK;
+}
+
+pccl_status_t pccl_halving_reduce_scatter_local(void* msg, const void* recv, int nranks, int rank,
+                                                size_t chunk_count, pccl_dtype_t io_dt,
+                                                pccl_op_t op, pccl_stream_t stream) {
+  if (msg == nullptr || recv == nullptr) return PCCL_ERR_NULL;
+  if (pccl_status_t s = check_common(io_dt, io_dt, op)) return s;
+  if (nranks < 1 || (nranks & (nranks - 1)) != 0 || rank < 0 || rank >= nranks)
+    return PCCL_ERR_INVALID;
+  const size_t es = esize(io_dt);
+  size_t chunk_bytes, msg_bytes;
+  if (!mul_ok(chunk_count, es, &chunk_bytes) || !mul_ok(chunk_bytes, (size_t)nranks, &msg_bytes))
+    return PCCL_ERR_INVALID;
+  if (!elem_aligned(msg, es) || !elem_aligned(recv, es)) return PCCL_ERR_INVALID;
+  if (nranks > 1 && overlaps(msg, msg_bytes, recv, msg_bytes - chunk_bytes)) return PCCL_ERR_OVERLAP;
+  if (chunk_count == 0) return PCCL_OK;
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  size_t lo = 0, len = (size_t)nranks, recv_off = 0;  // active chunk range, received chunks so far
+  for (int dist = nranks >> 1; dist >= 1; dist >>= 1) {
+    len >>= 1;
+    if (rank & dist) lo += len;  // keep the half that contains this rank
+    const hipError_t e = pccl::launch_accumulate(
+        reinterpret_cast<char*>(msg) + lo * chunk_bytes,
+        reinterpret_cast<const char*>(recv) + recv_off * chunk_bytes, len * chunk_count,
+        io_dt == PCCL_BF16, st);
+    if (e != hipSuccess) return e == hipErrorInvalidValue ? PCCL_ERR_INVALID : PCCL_ERR_HIP;
+    recv_off += len;
+  }
+  return PCCL_OK;
+}
+
 const char* pccl_status_string(pccl_status_t status) {
   switch (status) {
     case PCCL_OK: return "PCCL_OK";

@@ -1,0 +1,73 @@
+// The paper's GPU vector-reduction kernel in its literal, step-wise form for gfx950
+// (Section III-B: reduce-scatter from point-to-point messages plus a GPU vector reduction;
+// Section IV-B: PCCL_ring and PCCL_rec run their local reduction on the GPU): the buffer a
+// step has just received is added into the local data in place, and the sum -- stored in the
+// message dtype -- is what the next step forwards.
+//
+// HBM-bound: two loads and one store per element, one add.  A thread owns one 128-bit vector
+// of each operand (measured on MI355X for two sources: 16 bytes per lane and operand moves
+// 6.3 TB/s, 4 bytes 4.3 TB/s -- with only two streams the lane needs the wide access to keep
+// enough bytes in flight).
+#include "device_utils.h"
+#include "kernels.h"
+
+namespace pccl {
+
+namespace {
+
+template <bool BF16, bool FAST>
+__global__ __launch_bounds__(kBlock) void k_accumulate(char* acc, const char* recv, size_t count) {
+  constexpr int W = 4;
+  constexpr int VE = BF16 ? 2 * W : W;
+  constexpr int ES = BF16 ? 2 : 4;
+  const size_t nvec = count / VE;
+  const size_t v = (size_t)blockIdx.x * kBlock + threadIdx.x;
+  if (v < nvec) {
+    const size_t off = v * (4 * W);
+    uint32_t a[W], r[W], o[W];
+    ld_words<W, ES, FAST>(acc, off, a);
+    ld_words<W, ES, FAST>(recv, off, r);
+#pragma unroll
+    for (int k = 0; k < W; ++k) {
+      if (BF16)
+        o[k] = pack_bf16(bf16_lo(a[k]) + bf16_lo(r[k]), bf16_hi(a[k]) + bf16_hi(r[k]));
+      else
+        o[k] = __float_as_uint(__uint_as_float(a[k]) + __uint_as_float(r[k]));
+    }
+    st_words<W, ES, FAST>(acc, off, o);
+  }
+  // ragged tail: fewer than VE <= 8 elements, taken by the last block
+  if (blockIdx.x == gridDim.x - 1) {
+    const size_t e = nvec * VE + threadIdx.x;
+    if (e < count) st_elem<BF16>(acc, e, ld_elem<BF16>(acc, e) + ld_elem<BF16>(recv, e));
+  }
+}
+
+inline bool is16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+template <bool BF16>
+hipError_t launch_acc(char* acc, const char* recv, size_t count, hipStream_t st) {
+  constexpr size_t VE = BF16 ? 8 : 4;
+  const size_t nvec = count / VE;
+  size_t blocks = (nvec + kBlock - 1) / kBlock;
+  if (blocks == 0) blocks = 1;  // a lone ragged tail still needs one block
+  if (blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
+  if (is16(acc) && is16(recv))
+    hipLaunchKernelGGL((k_accumulate<BF16, true>), dim3((unsigned)blocks), dim3(kBlock), 0, st, acc,
+                       recv, count);
+  else
+    hipLaunchKernelGGL((k_accumulate<BF16, false>), dim3((unsigned)blocks), dim3(kBlock), 0, st, acc,
+                       recv, count);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_accumulate(void* acc, const void* recv, size_t count, bool bf16, hipStream_t st) {
+  if (count == 0) return hipSuccess;
+  char* a = reinterpret_cast<char*>(acc);
+  const char* r = reinterpret_cast<const char*>(recv);
+  return bf16 ? launch_acc<true>(a, r, count, st) : launch_acc<false>(a, r, count, st);
+}
+
+}  // namespace pccl

@@ -167,3 +167,65 @@ def test_workload_generators_are_seeded_and_shaped():
     assert sizes == W.bucket_sizes_bytes()
     bits = W.random_bits16(1 << 16, 1)
     assert bits.dtype.itemsize == 2
+
+
+def test_accumulate_rejects_bad_arguments():
+    f = pccl.lib().pccl_accumulate
+    assert f(None, A, 8, 0, 0, None) == pccl.PCCL_ERR_NULL
+    assert f(A, None, 8, 0, 0, None) == pccl.PCCL_ERR_NULL
+    assert f(A, 2 * A, 8, 5, 0, None) == pccl.PCCL_ERR_UNSUPPORTED
+    assert f(A, 2 * A, 8, 0, 3, None) == pccl.PCCL_ERR_UNSUPPORTED
+    assert f(A, 2 * A, 1 << 63, 0, 0, None) == pccl.PCCL_ERR_INVALID       # byte size overflows
+    assert f(A + 2, 2 * A, 8, 0, 0, None) == pccl.PCCL_ERR_INVALID         # fp32 not 4-byte aligned
+    assert f(A, 2 * A + 1, 8, 1, 0, None) == pccl.PCCL_ERR_INVALID         # bf16 not 2-byte aligned
+    assert f(A, A + 16, 8, 0, 0, None) == pccl.PCCL_ERR_OVERLAP            # 32-byte ranges 16 apart
+    assert f(A, A, 8, 1, 0, None) == pccl.PCCL_ERR_OVERLAP
+    assert f(A, 2 * A, 0, 0, 0, None) == pccl.PCCL_OK                      # empty: nothing launched
+
+
+def test_ring_local_rejects_bad_arguments():
+    f = pccl.lib().pccl_ring_reduce_scatter_local
+    ok = dict(msg=A, recv=8 * A, stride=4096, p=8, r=3, c=1024, dt=0, op=0)
+
+    def call(**kw):
+        a = dict(ok, **kw)
+        return f(a["msg"], a["recv"], a["stride"], a["p"], a["r"], a["c"], a["dt"], a["op"], None)
+
+    assert call(msg=None) == pccl.PCCL_ERR_NULL
+    assert call(recv=None) == pccl.PCCL_ERR_NULL
+    assert call(p=0) == pccl.PCCL_ERR_INVALID
+    assert call(r=-1) == pccl.PCCL_ERR_INVALID
+    assert call(r=8) == pccl.PCCL_ERR_INVALID
+    assert call(dt=9) == pccl.PCCL_ERR_UNSUPPORTED
+    assert call(op=2) == pccl.PCCL_ERR_UNSUPPORTED
+    assert call(stride=4092) == pccl.PCCL_ERR_INVALID          # received chunks would overlap
+    assert call(stride=4098) == pccl.PCCL_ERR_INVALID          # not a multiple of the element size
+    assert call(c=1 << 62) == pccl.PCCL_ERR_INVALID
+    assert call(stride=1 << 62, c=4) == pccl.PCCL_ERR_INVALID  # span overflows
+    assert call(recv=A + 4096) == pccl.PCCL_ERR_OVERLAP        # recv inside the message
+    assert call(msg=8 * A + 6 * 4096) == pccl.PCCL_ERR_OVERLAP # message starts inside the last recv chunk
+    assert call(c=0) == pccl.PCCL_OK
+    assert call(p=1, r=0, c=0, recv=A) == pccl.PCCL_OK         # one rank: no step, nothing can overlap
+    assert call(p=2, r=1, stride=0, c=0) == pccl.PCCL_OK       # a single received chunk: stride unused
+
+
+def test_halving_local_rejects_bad_arguments():
+    f = pccl.lib().pccl_halving_reduce_scatter_local
+    ok = dict(msg=A, recv=8 * A, p=8, r=5, c=1024, dt=1, op=0)
+
+    def call(**kw):
+        a = dict(ok, **kw)
+        return f(a["msg"], a["recv"], a["p"], a["r"], a["c"], a["dt"], a["op"], None)
+
+    assert call(msg=None) == pccl.PCCL_ERR_NULL
+    assert call(recv=None) == pccl.PCCL_ERR_NULL
+    for p in (0, -4, 3, 6, 12):
+        assert call(p=p, r=0) == pccl.PCCL_ERR_INVALID         # recursive halving: powers of two only
+    assert call(r=8) == pccl.PCCL_ERR_INVALID
+    assert call(r=-1) == pccl.PCCL_ERR_INVALID
+    assert call(dt=2) == pccl.PCCL_ERR_UNSUPPORTED
+    assert call(c=1 << 62) == pccl.PCCL_ERR_INVALID
+    assert call(msg=A + 1) == pccl.PCCL_ERR_INVALID
+    assert call(recv=A + 2048) == pccl.PCCL_ERR_OVERLAP
+    assert call(msg=8 * A + 7 * 2048 - 2) == pccl.PCCL_ERR_OVERLAP  # last received byte pair
+    assert call(c=0) == pccl.PCCL_OK
