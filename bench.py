@@ -198,6 +198,48 @@ def other_workloads(dev):
     return res
 
 
+def fused_leg(dev, steps, warmup, nsets=4, my_node=5, my_gpu=3):
+    """The same all-reduce share without the pre-shuffle: phase 1 reads the eight node-mates'
+    rank-order 256 MB messages through the node stride (pccl_reduce_scatter_local_unpacked), then
+    pccl_allgather_reassemble.  Saves the 512 MB of traffic of pccl_hier_pack."""
+    w = W.cfg3()
+    n = w.ranks * w.chunk
+    sets = []
+    for k in range(nsets):
+        msgs = W.draw(w, w.gpus * n, dev, seed_offset=200 + k).view(w.gpus, n)
+        inter = W.draw(w, w.nodes * w.chunk, dev, seed_offset=210 + k).view(w.nodes, w.chunk)
+        sets.append(dict(msgs=msgs, inter=inter,
+                         d_inter=pccl.device_pointer_array([inter[j] for j in range(w.nodes)]),
+                         partial=torch.empty(w.nodes * w.chunk, dtype=w.dtype, device=dev),
+                         shard=torch.empty(w.chunk, dtype=w.dtype, device=dev),
+                         gathered=W.draw(w, n, dev, seed_offset=220 + k),
+                         out=torch.empty(n, dtype=w.dtype, device=dev)))
+
+    def run(s):
+        pccl.pccl_reduce_scatter_local_unpacked(s["shard"], s["partial"], msgs=s["msgs"], d_inter=s["d_inter"],
+                                                nodes=w.nodes, gpus_per_node=w.gpus, my_node=my_node, my_gpu=my_gpu)
+        pccl.pccl_allgather_reassemble(s["out"], src=s["gathered"], nodes=w.nodes, gpus_per_node=w.gpus)
+
+    for k in range(warmup):
+        run(sets[k % nsets])
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(steps):
+        run(sets[k % nsets])
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    e = w.esize
+    nbytes = (w.gpus + 1) * w.nodes * w.chunk * e + (w.nodes + 1) * w.chunk * e + 2 * n * e
+    rs_ms = time_calls([lambda s=s: pccl.pccl_reduce_scatter_local_unpacked(
+        s["shard"], s["partial"], msgs=s["msgs"], d_inter=s["d_inter"], nodes=w.nodes, gpus_per_node=w.gpus,
+        my_node=my_node, my_gpu=my_gpu) for s in sets])
+    return dict(what="pccl_reduce_scatter_local_unpacked (no pccl_hier_pack pass) + pccl_allgather_reassemble",
+                ms_per_step=round(ms, 4), algorithmic_bytes_per_step=nbytes,
+                GBps=round(nbytes / (ms * 1e-3) / 1e9, 1),
+                unpacked_reduce_scatter_us=round(rs_ms[0] * 1e3, 2),
+                unpacked_reduce_scatter_GBps=round((nbytes - 2 * n * e) / (rs_ms[0] * 1e-3) / 1e9, 1))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -291,6 +333,10 @@ def main():
     del sets
     torch.cuda.empty_cache()
 
+    fused = None if args.no_others else fused_leg(dev, args.steps, args.warmup)
+    if fused is not None:
+        fused["speedup_vs_three_call_step"] = round(ms_per_step / fused["ms_per_step"], 3)
+    torch.cuda.empty_cache()
     others = None if args.no_others else other_workloads(dev)
     if args.calibration_copy:
         a = torch.empty(256 * MB, dtype=torch.uint8, device=dev)
@@ -310,7 +356,7 @@ def main():
                    "accumulate": "f32", "algorithmic_bytes_per_step": step_bytes, "buffer_sets": args.sets,
                    "kernel_events_in_timed_region": use_ev},
         "roofline": roofline, "cpu_baseline": cpu_baseline, "parity_vs_oracle": parity,
-        "calls": calls, "other_workloads": others,
+        "calls": calls, "fused_step": fused, "other_workloads": others,
     }
     print(json.dumps(out), flush=True)
 

@@ -140,6 +140,25 @@ pccl_status_t pccl_reduce_scatter_local(void* shard, void* partial, const void* 
                                         size_t chunk_count, pccl_dtype_t io_dt, pccl_op_t op,
                                         pccl_stream_t stream);
 
+/* The same share without the pre-shuffle: phase 1 reads the node-mates' messages in RANK
+ * order, so no pccl_hier_pack pass (one read and one write of the whole message on every
+ * GPU, which the paper's timings include as "intra-GPU transposes", Section III-A) is needed.
+ * Message g' (what node-mate g' holds: [nodes][gpus_per_node][chunk_count] of io_dt) is
+ *     d_msgs == NULL: (const char*)msgs_base + g'*msg_stride_bytes
+ *     else          : d_msgs[g']   (device array of gpus_per_node device pointers)
+ * and piece_g'[n][e] = message_g'[(n*gpus_per_node + my_gpu)*chunk_count + e]: the chunks
+ * bound for local id my_gpu on every node, read through the node stride.  Everything else
+ * (partial, shard, d_inter, my_node, order of the sums) is as in pccl_reduce_scatter_local,
+ * and the results are bit-identical to packing every message first.
+ * Errors: as there; my_gpu outside [0, gpus_per_node); nodes > 65535. */
+pccl_status_t pccl_reduce_scatter_local_unpacked(void* shard, void* partial, const void* msgs_base,
+                                                 size_t msg_stride_bytes,
+                                                 const void* const* d_msgs,
+                                                 const void* const* d_inter, int nodes,
+                                                 int gpus_per_node, int my_node, int my_gpu,
+                                                 size_t chunk_count, pccl_dtype_t io_dt,
+                                                 pccl_op_t op, pccl_stream_t stream);
+
 /* The all-gather shuffle with the gathered chunks either contiguous in hierarchical order
  * (d_slots == NULL, `src` used; identical to pccl_hier_unpack) or each in its own buffer
  * (d_slots = device array of P device pointers indexed by hierarchical slot g*N + n, `src`

@@ -217,6 +217,20 @@ def halving_rs_local(msg, recvs, rank, nthreads=1):
     return buf
 
 
+def reduce_scatter_local_unpacked(msgs, nodes, gpus, my_gpu, my_node=0, inter=None, out_dt=None,
+                                  nthreads=1):
+    """The two-level reduce-scatter share straight from the node-mates' rank-order messages
+    (msgs[g2] = [nodes*gpus*chunk], node-mate g2's message): by definition the same as
+    pre-shuffling every message and taking piece `my_gpu` of each.  Returns (shard, partial)."""
+    assert len(msgs) == gpus
+    pieces = []
+    for m in msgs:
+        packed = hier_pack(np.ascontiguousarray(m).reshape(-1), nodes, gpus)
+        pieces.append(packed.reshape(gpus, nodes, -1)[my_gpu])
+    return reduce_scatter_local(np.stack(pieces), my_node=my_node, inter=inter, out_dt=out_dt,
+                                nthreads=nthreads)
+
+
 def _bytes_view(a):
     a = np.ascontiguousarray(a)
     return a.reshape(-1).view(np.uint8)

@@ -8,5 +8,5 @@ from .binding import (  # noqa: F401
     PCCL_F32, PCCL_MAX_BUCKETS, PCCL_OK, PCCL_SUM, BucketTable, PcclError, device_pointer_array, lib,
     pccl_accumulate, pccl_allgather_reassemble, pccl_bucket_t, pccl_halving_reduce_scatter_local, pccl_hier_pack, pccl_hier_unpack, pccl_local_reduce,
     pccl_local_reduce_ptrs, pccl_local_reduce_ptrs_two_level, pccl_reduce_scatter_local,
-    pccl_reduce_scatter_local_batched, pccl_ring_reduce_scatter_local, status_string,
+    pccl_reduce_scatter_local_batched, pccl_reduce_scatter_local_unpacked, pccl_ring_reduce_scatter_local, status_string,
 )

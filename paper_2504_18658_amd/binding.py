@@ -20,7 +20,7 @@ EXPORTS = (
     "pccl_local_reduce", "pccl_local_reduce_ptrs", "pccl_local_reduce_ptrs_two_level",
     "pccl_hier_pack", "pccl_hier_unpack", "pccl_reduce_scatter_local",
     "pccl_allgather_reassemble", "pccl_reduce_scatter_local_batched", "pccl_accumulate",
-    "pccl_ring_reduce_scatter_local", "pccl_halving_reduce_scatter_local", "pccl_status_string",
+    "pccl_reduce_scatter_local_unpacked", "pccl_ring_reduce_scatter_local", "pccl_halving_reduce_scatter_local", "pccl_status_string",
 )
 
 
@@ -57,6 +57,7 @@ def lib():
         L.pccl_allgather_reassemble.argtypes = [vp, vp, vp, i, i, sz, vp]
         L.pccl_reduce_scatter_local_batched.argtypes = [vp, vp, i, i, i, i, i, vp]
         L.pccl_accumulate.argtypes = [vp, vp, sz, i, i, vp]
+        L.pccl_reduce_scatter_local_unpacked.argtypes = [vp, vp, vp, sz, vp, vp, i, i, i, i, sz, i, i, vp]
         L.pccl_ring_reduce_scatter_local.argtypes = [vp, vp, sz, i, i, sz, i, i, vp]
         L.pccl_halving_reduce_scatter_local.argtypes = [vp, vp, i, i, sz, i, i, vp]
         for name in EXPORTS[:-1]:
@@ -275,3 +276,29 @@ def pccl_halving_reduce_scatter_local(msg, recv, rank, stream=None):
                                                    dtype_code(msg.dtype), PCCL_SUM, _stream(stream)),
            "pccl_halving_reduce_scatter_local")
     return msg
+
+
+def pccl_reduce_scatter_local_unpacked(shard, partial, msgs=None, d_msgs=None, d_inter=None, nodes=1,
+                                       gpus_per_node=1, my_node=0, my_gpu=0, stream=None):
+    """The two-level reduce-scatter share straight from the node-mates' rank-order messages.
+
+    msgs: [gpus][nodes*gpus*chunk] tensor (row g' = node-mate g's message, rows may be strided
+    apart), or d_msgs: int64 device tensor of `gpus` pointers to such messages."""
+    chunk = shard.numel()
+    if partial.numel() != nodes * chunk or partial.dtype != shard.dtype or \
+            not partial.is_contiguous() or not shard.is_contiguous():
+        raise ValueError("pccl_reduce_scatter_local_unpacked: partial is [nodes][chunk], shard is [chunk]")
+    if d_msgs is None:
+        base, stride, rows, count = _rows(msgs, "msgs")
+        if rows != gpus_per_node or count != nodes * gpus_per_node * chunk or msgs.dtype != shard.dtype:
+            raise ValueError("pccl_reduce_scatter_local_unpacked: msgs must be [gpus][nodes*gpus*chunk]")
+    else:
+        base, stride = None, 0
+        if d_msgs.numel() != gpus_per_node:
+            raise ValueError("pccl_reduce_scatter_local_unpacked: need gpus_per_node message pointers")
+    _check(lib().pccl_reduce_scatter_local_unpacked(
+        _dev(shard, "shard"), _dev(partial, "partial"), base, stride,
+        None if d_msgs is None else _dev(d_msgs, "d_msgs"),
+        None if d_inter is None else _dev(d_inter, "d_inter"), nodes, gpus_per_node, my_node, my_gpu, chunk,
+        dtype_code(shard.dtype), PCCL_SUM, _stream(stream)), "pccl_reduce_scatter_local_unpacked")
+    return shard

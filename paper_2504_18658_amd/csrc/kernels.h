@@ -15,6 +15,9 @@ namespace pccl {
 // and holds `count` elements.  For every element e:
 //   t_n = x[n][0][e] + ... + x[n][gpus-1][e];  p_n = round_partial ? through in_dt : t_n
 //   partial[n*count + e] = p_n (if partial != nullptr, in in_dt);  dst[e] = p_0 + ... + p_{nodes-1}
+// `rows` > 1 repeats the problem for rows r = 0 .. rows-1 (the streaming kernel's grid.y):
+// row r reads every source at +r*row_stride_src bytes and writes dst at +r*row_stride_dst
+// bytes (partial must be nullptr then).  src_offset is added to pointer-array entries.
 struct ReduceProblem {
   void* dst;
   void* partial;
@@ -24,10 +27,14 @@ struct ReduceProblem {
   size_t stride_n;
   size_t stride_g;
   size_t count;
+  size_t src_offset;
+  size_t row_stride_src;
+  size_t row_stride_dst;
   int nodes;
   int gpus;
   int override_index;  // -1: none
   int round_partial;
+  int rows;
 };
 
 // Chunk-granular transpose: dst chunk (c*rows + r) = src chunk (r*cols + c); src chunk k is

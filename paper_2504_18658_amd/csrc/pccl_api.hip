@@ -40,10 +40,14 @@ ReduceProblem blank_problem() {
   p.stride_n = 0;
   p.stride_g = 0;
   p.count = 0;
+  p.src_offset = 0;
+  p.row_stride_src = 0;
+  p.row_stride_dst = 0;
   p.nodes = 1;
   p.gpus = 1;
   p.override_index = -1;
   p.round_partial = 0;
+  p.rows = 1;
   return p;
 }
 
@@ -81,6 +85,26 @@ pccl_status_t permute_common(void* dst, const void* src, const void* const* slot
   p.rows = rows;
   p.cols = cols;
   const hipError_t e = pccl::launch_permute(p, reinterpret_cast<hipStream_t>(stream));
+  return e == hipErrorInvalidValue ? PCCL_ERR_INVALID : from_hip(e);
+}
+
+// phase 2 (inter-node) of a two-level reduce-scatter share: shard[e] = sum over n' of
+// inter_n'[e], an N-source flat sum over the partial's rows or over received chunks
+pccl_status_t phase2(void* shard, void* partial, const void* const* d_inter, int nodes, int my_node,
+                     size_t chunk_count, size_t chunk_bytes, bool bf, hipStream_t st) {
+  ReduceProblem p2 = blank_problem();
+  p2.dst = shard;
+  p2.count = chunk_count;
+  p2.gpus = nodes;
+  if (d_inter == nullptr) {
+    p2.base = reinterpret_cast<const char*>(partial);
+    p2.stride_g = chunk_bytes;
+  } else {
+    p2.ptrs = d_inter;
+    p2.override_index = my_node;
+    p2.override_ptr = reinterpret_cast<const char*>(partial) + (size_t)my_node * chunk_bytes;
+  }
+  const hipError_t e = pccl::launch_reduce(p2, bf, bf, st);
   return e == hipErrorInvalidValue ? PCCL_ERR_INVALID : from_hip(e);
 }
 
@@ -235,21 +259,65 @@ pccl_status_t pccl_reduce_scatter_local(void* shard, void* partial, const void* 
   hipError_t e = pccl::launch_reduce(p1, bf, bf, st);
   if (e != hipSuccess) return e == hipErrorInvalidValue ? PCCL_ERR_INVALID : PCCL_ERR_HIP;
 
-  // phase 2 (inter-node): shard[e] = sum over n' of inter_n'[e], an N-source flat sum
-  ReduceProblem p2 = blank_problem();
-  p2.dst = shard;
-  p2.count = chunk_count;
-  p2.gpus = nodes;
-  if (d_inter == nullptr) {
-    p2.base = reinterpret_cast<const char*>(partial);
-    p2.stride_g = chunk_bytes;
-  } else {
-    p2.ptrs = d_inter;
-    p2.override_index = my_node;
-    p2.override_ptr = reinterpret_cast<const char*>(partial) + (size_t)my_node * chunk_bytes;
+  return phase2(shard, partial, d_inter, nodes, my_node, chunk_count, chunk_bytes, bf, st);
+}
+
+pccl_status_t pccl_reduce_scatter_local_unpacked(void* shard, void* partial, const void* msgs_base,
+                                                 size_t msg_stride_bytes,
+                                                 const void* const* d_msgs,
+                                                 const void* const* d_inter, int nodes,
+                                                 int gpus_per_node, int my_node, int my_gpu,
+                                                 size_t chunk_count, pccl_dtype_t io_dt,
+                                                 pccl_op_t op, pccl_stream_t stream) {
+  if (shard == nullptr || partial == nullptr || (msgs_base == nullptr && d_msgs == nullptr))
+    return PCCL_ERR_NULL;
+  if (pccl_status_t s = check_common(io_dt, io_dt, op)) return s;
+  if (nodes < 1 || gpus_per_node < 1 || my_node < 0 || my_node >= nodes || my_gpu < 0 ||
+      my_gpu >= gpus_per_node || nodes > 65535)
+    return PCCL_ERR_INVALID;
+  const size_t es = esize(io_dt);
+  size_t chunk_bytes, node_bytes, msg_bytes, piece_bytes, span;
+  if (!mul_ok(chunk_count, es, &chunk_bytes) ||
+      !mul_ok(chunk_bytes, (size_t)gpus_per_node, &node_bytes) ||
+      !mul_ok(node_bytes, (size_t)nodes, &msg_bytes) ||
+      !mul_ok(chunk_bytes, (size_t)nodes, &piece_bytes))
+    return PCCL_ERR_INVALID;
+  if (!elem_aligned(shard, es) || !elem_aligned(partial, es)) return PCCL_ERR_INVALID;
+  if (overlaps(shard, chunk_bytes, partial, piece_bytes)) return PCCL_ERR_OVERLAP;
+  if (d_msgs == nullptr) {
+    if (!elem_aligned(msgs_base, es)) return PCCL_ERR_INVALID;
+    if (gpus_per_node > 1 && (msg_stride_bytes < msg_bytes || msg_stride_bytes % es != 0))
+      return PCCL_ERR_INVALID;
+    if (!mul_ok((size_t)(gpus_per_node - 1), gpus_per_node > 1 ? msg_stride_bytes : 0, &span) ||
+        !add_ok(span, msg_bytes, &span))
+      return PCCL_ERR_INVALID;
+    if (overlaps(partial, piece_bytes, msgs_base, span) ||
+        overlaps(shard, chunk_bytes, msgs_base, span))
+      return PCCL_ERR_OVERLAP;
   }
-  e = pccl::launch_reduce(p2, bf, bf, st);
-  return e == hipErrorInvalidValue ? PCCL_ERR_INVALID : from_hip(e);
+  if (chunk_count == 0) return PCCL_OK;
+  const bool bf = io_dt == PCCL_BF16;
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+
+  // phase 1 straight from the rank-order messages: row n of the partial sums chunk
+  // (n, my_gpu) of every node-mate's message, i.e. rows that are M chunks apart
+  ReduceProblem p1 = blank_problem();
+  p1.dst = partial;
+  p1.count = chunk_count;
+  p1.gpus = gpus_per_node;
+  p1.rows = nodes;
+  p1.row_stride_src = node_bytes;
+  p1.row_stride_dst = chunk_bytes;
+  if (d_msgs == nullptr) {
+    p1.base = reinterpret_cast<const char*>(msgs_base) + (size_t)my_gpu * chunk_bytes;
+    p1.stride_g = gpus_per_node > 1 ? msg_stride_bytes : 0;
+  } else {
+    p1.ptrs = d_msgs;
+    p1.src_offset = (size_t)my_gpu * chunk_bytes;
+  }
+  const hipError_t e = pccl::launch_reduce(p1, bf, bf, st);
+  if (e != hipSuccess) return e == hipErrorInvalidValue ? PCCL_ERR_INVALID : PCCL_ERR_HIP;
+  return phase2(shard, partial, d_inter, nodes, my_node, chunk_count, chunk_bytes, bf, st);
 }
 
 pccl_status_t pccl_reduce_scatter_local_batched(const pccl_bucket_t* d_buckets,

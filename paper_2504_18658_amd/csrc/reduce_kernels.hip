@@ -25,8 +25,9 @@ template <bool FAST = false>
 __device__ __forceinline__ const char* src_ptr(const ReduceProblem& p, int n, int g) {
   if (!FAST && p.ptrs != nullptr) {
     const int idx = n * p.gpus + g;
-    return idx == p.override_index ? reinterpret_cast<const char*>(p.override_ptr)
-                                   : ld_pointer(p.ptrs, idx);
+    return (idx == p.override_index ? reinterpret_cast<const char*>(p.override_ptr)
+                                    : ld_pointer(p.ptrs, idx)) +
+           p.src_offset;
   }
   return p.base + (size_t)n * p.stride_n + (size_t)g * p.stride_g;
 }
@@ -212,6 +213,11 @@ inline int pick_m(int gpus) {
 
 template <bool IN_BF16, bool OUT_BF16, int M, bool FAST>
 __global__ __launch_bounds__(kBlock) void k_reduce(ReduceProblem p) {
+  // grid.y = rows: the same reduction over `rows` strided rows of every source
+  const size_t row = blockIdx.y;
+  p.base += row * p.row_stride_src;
+  p.src_offset += row * p.row_stride_src;
+  p.dst = reinterpret_cast<char*>(p.dst) + row * p.row_stride_dst;
   reduce_tile<IN_BF16, OUT_BF16, M, words_for(M), FAST>(p, blockIdx.x);
 }
 
@@ -228,20 +234,20 @@ inline bool is16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) =
 inline bool fast_eligible(const ReduceProblem& p, bool in_bf16) {
   const size_t es = in_bf16 ? 2 : 4;
   return p.ptrs == nullptr && is16(p.base) && is16(p.dst) && p.stride_n % 16 == 0 &&
-         p.stride_g % 16 == 0 &&
+         p.stride_g % 16 == 0 && p.row_stride_src % 16 == 0 && p.row_stride_dst % 16 == 0 &&
          (p.partial == nullptr || (is16(p.partial) && (p.count * es) % 16 == 0));
 }
 
 template <bool IN_BF16, bool OUT_BF16, int M>
 hipError_t launch_m(const ReduceProblem& p, hipStream_t st) {
   const size_t tiles = tiles_for(p.count, M, IN_BF16);
-  if (tiles > 0x7FFFFFFFull) return hipErrorInvalidValue;
+  if (tiles > 0x7FFFFFFFull || p.rows < 1 || p.rows > 65535) return hipErrorInvalidValue;
+  if (p.rows > 1 && p.partial != nullptr) return hipErrorInvalidValue;
+  const dim3 grid((unsigned)tiles, (unsigned)p.rows);
   if (fast_eligible(p, IN_BF16))
-    hipLaunchKernelGGL((k_reduce<IN_BF16, OUT_BF16, M, true>), dim3((unsigned)tiles), dim3(kBlock), 0,
-                       st, p);
+    hipLaunchKernelGGL((k_reduce<IN_BF16, OUT_BF16, M, true>), grid, dim3(kBlock), 0, st, p);
   else
-    hipLaunchKernelGGL((k_reduce<IN_BF16, OUT_BF16, M, false>), dim3((unsigned)tiles), dim3(kBlock), 0,
-                       st, p);
+    hipLaunchKernelGGL((k_reduce<IN_BF16, OUT_BF16, M, false>), grid, dim3(kBlock), 0, st, p);
   return hipGetLastError();
 }
 
@@ -494,6 +500,10 @@ __global__ __launch_bounds__(kBlock) void k_rs_batched(const pccl_bucket_t* __re
   p.round_partial = 0;
   p.nodes = 1;
   p.stride_n = 0;
+  p.src_offset = 0;
+  p.row_stride_src = 0;
+  p.row_stride_dst = 0;
+  p.rows = 1;
   if (PHASE == 1) {  // partial[n][e] = sum over g' of piece_g'[n][e]
     p.dst = b.partial;
     p.base = reinterpret_cast<const char*>(b.intra_base);

@@ -229,3 +229,32 @@ def test_halving_local_rejects_bad_arguments():
     assert call(recv=A + 2048) == pccl.PCCL_ERR_OVERLAP
     assert call(msg=8 * A + 7 * 2048 - 2) == pccl.PCCL_ERR_OVERLAP  # last received byte pair
     assert call(c=0) == pccl.PCCL_OK
+
+
+def test_unpacked_reduce_scatter_rejects_bad_arguments():
+    f = pccl.lib().pccl_reduce_scatter_local_unpacked
+    # 4 nodes x 2 gpus, 256-element fp32 chunks: a message is 8 KiB, a piece 4 KiB
+    ok = dict(shard=A, partial=2 * A, msgs=8 * A, stride=8192, d_msgs=None, d_inter=None, n=4, m=2, my_n=1,
+              my_g=1, c=256, dt=0, op=0)
+
+    def call(**kw):
+        a = dict(ok, **kw)
+        return f(a["shard"], a["partial"], a["msgs"], a["stride"], a["d_msgs"], a["d_inter"], a["n"], a["m"],
+                 a["my_n"], a["my_g"], a["c"], a["dt"], a["op"], None)
+
+    assert call(shard=None) == pccl.PCCL_ERR_NULL
+    assert call(partial=None) == pccl.PCCL_ERR_NULL
+    assert call(msgs=None) == pccl.PCCL_ERR_NULL               # neither a base nor a pointer array
+    assert call(my_g=2) == pccl.PCCL_ERR_INVALID
+    assert call(my_g=-1) == pccl.PCCL_ERR_INVALID
+    assert call(my_n=4) == pccl.PCCL_ERR_INVALID
+    assert call(n=0) == pccl.PCCL_ERR_INVALID
+    assert call(n=70000, my_n=0) == pccl.PCCL_ERR_INVALID      # rows of the launch grid
+    assert call(stride=8188) == pccl.PCCL_ERR_INVALID          # messages would overlap
+    assert call(c=1 << 61) == pccl.PCCL_ERR_INVALID
+    assert call(dt=4) == pccl.PCCL_ERR_UNSUPPORTED
+    assert call(op=1) == pccl.PCCL_ERR_UNSUPPORTED
+    assert call(partial=8 * A + 100 * 4) == pccl.PCCL_ERR_OVERLAP   # partial inside message 0
+    assert call(shard=8 * A + 16380) == pccl.PCCL_ERR_OVERLAP       # shard reaches the last message word
+    assert call(shard=2 * A + 4092) == pccl.PCCL_ERR_OVERLAP        # shard reaches into the partial
+    assert call(c=0) == pccl.PCCL_OK

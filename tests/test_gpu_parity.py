@@ -433,6 +433,66 @@ def _make_buckets(w, sizes_bytes, device):
     return buckets
 
 
+@pytest.mark.parametrize("dtype", [F32, BF16])
+@pytest.mark.parametrize("use_ptrs", [False, True])
+@pytest.mark.parametrize("nodes,gpus,chunk,my_n,my_g", [(2, 2, 3, 0, 1), (4, 8, 1000, 3, 7), (16, 8, 2048 + 8, 5, 0),
+                                                         (3, 5, 333, 2, 4), (1, 4, 100, 0, 2), (5, 1, 64, 4, 0)])
+def test_unpacked_reduce_scatter_matches_oracle(dtype, use_ptrs, nodes, gpus, chunk, my_n, my_g):
+    print("case", dtype, use_ptrs, nodes, gpus, chunk, my_n, my_g, flush=True)
+    P = nodes * gpus
+    msgs_h = _draw(gpus * P * chunk, dtype, 900 + P + chunk).view(gpus, P * chunk)
+    inter_h = _draw(nodes * chunk, dtype, 901 + P + chunk).view(nodes, chunk)
+    msgs = msgs_h.to(DEV)
+    inter = inter_h.to(DEV)
+    d_inter = pccl.device_pointer_array([inter[n] for n in range(nodes)])
+    partial = Guarded(nodes * chunk, dtype)
+    shard = Guarded(chunk, dtype)
+    if use_ptrs:
+        separate = [msgs[g].clone() for g in reversed(range(gpus))][::-1]   # own allocations, not monotone
+        pccl.pccl_reduce_scatter_local_unpacked(shard.view, partial.view, d_msgs=pccl.device_pointer_array(separate),
+                                                d_inter=d_inter, nodes=nodes, gpus_per_node=gpus, my_node=my_n,
+                                                my_gpu=my_g)
+    else:
+        pccl.pccl_reduce_scatter_local_unpacked(shard.view, partial.view, msgs=msgs, d_inter=d_inter, nodes=nodes,
+                                                gpus_per_node=gpus, my_node=my_n, my_gpu=my_g)
+    _sync()
+    want_shard, want_partial = oracle.reduce_scatter_local_unpacked(
+        [to_np(msgs_h[g]) for g in range(gpus)], nodes, gpus, my_g, my_node=my_n,
+        inter=[to_np(inter_h[n]) for n in range(nodes)])
+    assert same_bits(to_np(partial.view), want_partial.reshape(-1)), first_diff(to_np(partial.view), want_partial)
+    assert same_bits(to_np(shard.view), want_shard), first_diff(to_np(shard.view), want_shard)
+    partial.check()
+    shard.check()
+    # and it is the packed path bit for bit
+    packed = torch.empty_like(msgs)
+    for g in range(gpus):
+        pccl.pccl_hier_pack(packed[g], msgs[g], nodes, gpus)
+    x = packed.view(gpus, gpus, nodes, chunk)[:, my_g]          # piece my_g of every message (strided rows)
+    p2 = torch.empty(nodes * chunk, dtype=dtype, device=DEV)
+    s2 = torch.empty(chunk, dtype=dtype, device=DEV)
+    pccl.pccl_reduce_scatter_local(s2, p2, x, d_inter=d_inter, my_node=my_n)
+    _sync()
+    assert same_bits(to_np(p2), to_np(partial.view)) and same_bits(to_np(s2), to_np(shard.view))
+
+
+def test_unpacked_reduce_scatter_unaligned_and_self_simulated():
+    nodes, gpus, chunk, my_g = 3, 4, 1001, 2
+    P = nodes * gpus
+    raw = _draw(gpus * (P * chunk + 8) + 3, BF16, 77).to(DEV)
+    msgs = torch.as_strided(raw, (gpus, P * chunk), (P * chunk + 8, 1), 3)   # odd element offset, padded rows
+    partial = Guarded(nodes * chunk, BF16, offset_elems=1)
+    shard = Guarded(chunk, BF16, offset_elems=1)
+    pccl.pccl_reduce_scatter_local_unpacked(shard.view, partial.view, msgs=msgs, nodes=nodes, gpus_per_node=gpus,
+                                            my_gpu=my_g)
+    _sync()
+    want_shard, want_partial = oracle.reduce_scatter_local_unpacked(
+        [to_np(msgs[g]) for g in range(gpus)], nodes, gpus, my_g)
+    assert same_bits(to_np(partial.view), want_partial.reshape(-1))
+    assert same_bits(to_np(shard.view), want_shard)
+    partial.check()
+    shard.check()
+
+
 @pytest.mark.parametrize("dtype", [BF16, F32])
 def test_batched_small_buckets_match_unbatched_oracle(dtype):
     w = W.cfg5()

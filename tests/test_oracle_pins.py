@@ -413,3 +413,29 @@ def test_world_allreduce_is_reduce_scatter_then_allgather(nodes, gpus):
     Yb = [_torch_bf16_bits(y.reshape(-1)).reshape(P, chunk) for y in Y]
     for out in world.hier_allreduce(Yb, nodes, gpus):
         assert _same_bits(oracle.bf16_to_f32(out), want)
+
+
+@pytest.mark.parametrize("nodes,gpus", [(2, 3), (4, 2)])
+def test_unpacked_share_equals_the_world(nodes, gpus):
+    """Reading the node-mates' rank-order messages directly gives every rank the partial and the
+    shard of the whole-world two-level reduce-scatter (which pre-shuffles every message)."""
+    P, chunk = nodes * gpus, 5
+    rng = np.random.default_rng(77 + P)
+    Y = [rng.standard_normal((P, chunk)).astype(np.float32) for _ in range(P)]
+    shards, partial = world.hier_reduce_scatter(Y, nodes, gpus)
+    for n in range(nodes):
+        for g in range(gpus):
+            msgs = [Y[n * gpus + g2].reshape(-1) for g2 in range(gpus)]
+            inter = [partial[n2 * gpus + g][n] for n2 in range(nodes)]
+            shard, part = oracle.reduce_scatter_local_unpacked(msgs, nodes, gpus, g, my_node=n, inter=inter)
+            assert _same_bits(part, partial[n * gpus + g])
+            assert _same_bits(shard, shards[n * gpus + g])
+    # integers: the shard is the plain sum over all ranks of the chunk bound for this rank
+    Yi = [rng.integers(-30, 31, (P, chunk)).astype(np.float32) for _ in range(P)]
+    shards, partial = world.hier_reduce_scatter(Yi, nodes, gpus)
+    total = np.sum(np.stack(Yi), axis=0).astype(np.float32)
+    n, g = nodes - 1, gpus - 1
+    shard, _ = oracle.reduce_scatter_local_unpacked(
+        [Yi[n * gpus + g2].reshape(-1) for g2 in range(gpus)], nodes, gpus, g, my_node=n,
+        inter=[partial[n2 * gpus + g][n] for n2 in range(nodes)])
+    assert _same_bits(shard, total[n * gpus + g])
