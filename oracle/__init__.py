@@ -6,7 +6,8 @@ Python binding) never imports this package, and this package never imports
 the product.
 
 All arithmetic lives in pccl_oracle.c; this module only marshals numpy arrays.
-bf16 data is carried as numpy uint16 bit patterns, fp32 data as numpy float32.
+bf16 data is carried as numpy uint16 bit patterns, fp32 data as numpy float32, fp16 data as
+numpy float16.
 """
 import ctypes
 import os
@@ -17,6 +18,7 @@ from . import build as _build
 
 F32 = 0
 BF16 = 1
+F16 = 2
 
 _lib = None
 
@@ -30,10 +32,16 @@ def lib():
         L.pccl_oracle_f32_to_bf16.argtypes = [ctypes.c_uint32]
         L.pccl_oracle_f32_to_bf16_array.restype = None
         L.pccl_oracle_f32_to_bf16_array.argtypes = [vp, vp, sz]
-        L.pccl_oracle_flat_reduce.argtypes = [vp, vp, i, sz, i, i, i]
-        L.pccl_oracle_two_level_reduce.argtypes = [vp, vp, vp, i, i, sz, i, i, i]
+        L.pccl_oracle_f32_to_f16.restype = ctypes.c_uint16
+        L.pccl_oracle_f32_to_f16.argtypes = [ctypes.c_uint32]
+        L.pccl_oracle_f32_to_f16_array.restype = None
+        L.pccl_oracle_f32_to_f16_array.argtypes = [vp, vp, sz]
+        L.pccl_oracle_f16_to_f32_array.restype = None
+        L.pccl_oracle_f16_to_f32_array.argtypes = [vp, vp, sz]
+        L.pccl_oracle_flat_reduce.argtypes = [vp, vp, i, sz, i, i, i, i]
+        L.pccl_oracle_two_level_reduce.argtypes = [vp, vp, vp, i, i, sz, i, i, i, i]
         L.pccl_oracle_rs_phase1.argtypes = [vp, vp, i, i, sz, i, i]
-        L.pccl_oracle_rs_phase2.argtypes = [vp, vp, i, sz, i, i, i]
+        L.pccl_oracle_rs_phase2.argtypes = [vp, vp, i, sz, i, i, i, i]
         L.pccl_oracle_accumulate.argtypes = [vp, vp, sz, i, i]
         L.pccl_oracle_hier_pack.argtypes = [vp, vp, i, i, sz]
         L.pccl_oracle_hier_unpack.argtypes = [vp, vp, i, i, sz]
@@ -47,11 +55,13 @@ def _dt(a):
         return F32
     if a.dtype == np.uint16:
         return BF16
-    raise TypeError("oracle takes float32 (fp32) or uint16 (bf16 bits) arrays, got %s" % a.dtype)
+    if a.dtype == np.float16:
+        return F16
+    raise TypeError("oracle takes float32 (fp32), uint16 (bf16 bits) or float16 arrays, got %s" % a.dtype)
 
 
 def _np_dtype(code):
-    return np.float32 if code == F32 else np.uint16
+    return {F32: np.float32, BF16: np.uint16, F16: np.float16}[code]
 
 
 def _flat(a):
@@ -79,14 +89,31 @@ def f32_to_bf16(x):
     return out
 
 
+def f32_to_f16(x):
+    """Round float32 values to binary16 (round to nearest, ties to even); returns numpy float16."""
+    x = _flat(np.asarray(x, dtype=np.float32))
+    out = np.empty(x.shape, dtype=np.uint16)
+    lib().pccl_oracle_f32_to_f16_array(out.ctypes.data, x.ctypes.data, x.size)
+    return out.view(np.float16)
+
+
+def f16_to_f32(h):
+    """Widen binary16 values (numpy float16 or uint16 bit patterns) to float32 (exact)."""
+    h = _flat(np.asarray(h)).view(np.uint16)
+    out = np.empty(h.shape, dtype=np.uint32)
+    lib().pccl_oracle_f16_to_f32_array(out.ctypes.data, h.ctypes.data, h.size)
+    return out.view(np.float32)
+
+
 def bf16_to_f32(bits):
     """Widen bf16 bit patterns to float32 (exact)."""
     bits = np.asarray(bits, dtype=np.uint16)
     return (bits.astype(np.uint32) << np.uint32(16)).view(np.float32)
 
 
-def flat_reduce(srcs, out_dt=None, nthreads=1):
-    """out[e] = ((x0[e] + x1[e]) + ...) in fp32, sources in the order given."""
+def flat_reduce(srcs, out_dt=None, nthreads=1, average=False):
+    """out[e] = ((x0[e] + x1[e]) + ...) in fp32, sources in the order given; with average the
+    finished sum is divided by the number of sources before the output rounding."""
     srcs = [_flat(s) for s in srcs]
     in_dt = _dt(srcs[0])
     out_dt = in_dt if out_dt is None else out_dt
@@ -94,13 +121,14 @@ def flat_reduce(srcs, out_dt=None, nthreads=1):
     assert all(s.size == count and _dt(s) == in_dt for s in srcs)
     out = np.empty(count, dtype=_np_dtype(out_dt))
     rc = lib().pccl_oracle_flat_reduce(out.ctypes.data, _ptr_array(srcs), len(srcs), count,
-                                       in_dt, out_dt, nthreads)
+                                       in_dt, out_dt, len(srcs) if average else 0, nthreads)
     _check(rc, "flat_reduce")
     return out
 
 
-def two_level_reduce(srcs, nodes, gpus, out_dt=None, want_partials=False, nthreads=1):
-    """Two-level sum of nodes*gpus sources given node-major (srcs[n*gpus+g])."""
+def two_level_reduce(srcs, nodes, gpus, out_dt=None, want_partials=False, nthreads=1, average=False):
+    """Two-level sum of nodes*gpus sources given node-major (srcs[n*gpus+g]); with average the
+    finished sum is divided by nodes*gpus (the partials stay plain sums)."""
     srcs = [_flat(s) for s in srcs]
     assert len(srcs) == nodes * gpus
     in_dt = _dt(srcs[0])
@@ -111,7 +139,7 @@ def two_level_reduce(srcs, nodes, gpus, out_dt=None, want_partials=False, nthrea
     partials = np.empty((nodes, count), dtype=_np_dtype(in_dt)) if want_partials else None
     rc = lib().pccl_oracle_two_level_reduce(
         out.ctypes.data, partials.ctypes.data if want_partials else None, _ptr_array(srcs),
-        nodes, gpus, count, in_dt, out_dt, nthreads)
+        nodes, gpus, count, in_dt, out_dt, nodes * gpus if average else 0, nthreads)
     _check(rc, "two_level_reduce")
     return (out, partials) if want_partials else out
 
@@ -128,26 +156,28 @@ def rs_phase1(pieces, nodes, chunk, nthreads=1):
     return partial
 
 
-def rs_phase2(inter, out_dt=None, nthreads=1):
-    """shard[e] = round_out(sum over n of inter[n][e])."""
+def rs_phase2(inter, out_dt=None, nthreads=1, divisor=0):
+    """shard[e] = round_out(sum over n of inter[n][e]), the sum divided by `divisor` first if > 0."""
     inter = [_flat(c) for c in inter]
     io_dt = _dt(inter[0])
     out_dt = io_dt if out_dt is None else out_dt
     chunk = inter[0].size
     shard = np.empty(chunk, dtype=_np_dtype(out_dt))
     rc = lib().pccl_oracle_rs_phase2(shard.ctypes.data, _ptr_array(inter), len(inter), chunk,
-                                     io_dt, out_dt, nthreads)
+                                     io_dt, out_dt, divisor, nthreads)
     _check(rc, "rs_phase2")
     return shard
 
 
-def reduce_scatter_local(x, my_node=0, inter=None, out_dt=None, nthreads=1):
+def reduce_scatter_local(x, my_node=0, inter=None, out_dt=None, nthreads=1, average=False):
     """One GPU's share of a two-level reduce-scatter.
 
     x: array [gpus][nodes][chunk] (piece g = what node-mate g sent).
     inter: None -> the partial's own rows stand in for what every node sent;
            else a list of `nodes` chunks, entry my_node is ignored and
            partial[my_node] is used in its place.
+    average: the shard is the sum over all nodes*gpus ranks divided by that count (one binary32
+             division after the last add); the partial stays a plain sum.
     Returns (shard, partial)."""
     gpus, nodes, chunk = x.shape
     partial = rs_phase1([x[g] for g in range(gpus)], nodes, chunk, nthreads)
@@ -155,7 +185,7 @@ def reduce_scatter_local(x, my_node=0, inter=None, out_dt=None, nthreads=1):
         rows = [partial[n] for n in range(nodes)]
     else:
         rows = [partial[n] if n == my_node else inter[n] for n in range(nodes)]
-    shard = rs_phase2(rows, out_dt, nthreads)
+    shard = rs_phase2(rows, out_dt, nthreads, divisor=gpus * nodes if average else 0)
     return shard, partial
 
 
@@ -218,7 +248,7 @@ def halving_rs_local(msg, recvs, rank, nthreads=1):
 
 
 def reduce_scatter_local_unpacked(msgs, nodes, gpus, my_gpu, my_node=0, inter=None, out_dt=None,
-                                  nthreads=1):
+                                  nthreads=1, average=False):
     """The two-level reduce-scatter share straight from the node-mates' rank-order messages
     (msgs[g2] = [nodes*gpus*chunk], node-mate g2's message): by definition the same as
     pre-shuffling every message and taking piece `my_gpu` of each.  Returns (shard, partial)."""
@@ -228,7 +258,7 @@ def reduce_scatter_local_unpacked(msgs, nodes, gpus, my_gpu, my_node=0, inter=No
         packed = hier_pack(np.ascontiguousarray(m).reshape(-1), nodes, gpus)
         pieces.append(packed.reshape(gpus, nodes, -1)[my_gpu])
     return reduce_scatter_local(np.stack(pieces), my_node=my_node, inter=inter, out_dt=out_dt,
-                                nthreads=nthreads)
+                                nthreads=nthreads, average=average)
 
 
 def _bytes_view(a):

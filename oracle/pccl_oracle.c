@@ -33,6 +33,13 @@
  *     recursive halving starts at partner distance p/2 (power-of-two p only).
  *     The schedules themselves (which chunk at which step) live in the Python
  *     wrapper and the whole-world simulation next to this file.
+ *   - fp16 (IEEE binary16) is accepted next to bf16 as a 16-bit message dtype,
+ *     with the same rules (exact widening, round-to-nearest-even narrowing,
+ *     overflow to infinity, subnormal halves kept);
+ *   - op = average (data-parallel training averages gradients, Section II-A):
+ *     the finished binary32 sum is divided by the number of contributing
+ *     ranks -- one IEEE binary32 division -- before the output rounding; node
+ *     partials stay plain sums.
  *
  * Loops run over elements (optionally split over OpenMP threads, which does
  * not change any per-element order of operations).  Build with
@@ -45,6 +52,7 @@
 
 #define ORACLE_F32 0
 #define ORACLE_BF16 1
+#define ORACLE_F16 2
 
 #define ORACLE_OK 0
 #define ORACLE_BAD_ARG 1
@@ -87,14 +95,97 @@ void pccl_oracle_f32_to_bf16_array(uint16_t* out, const uint32_t* f32_bits, size
   for (size_t i = 0; i < n; ++i) out[i] = pccl_oracle_f32_to_bf16(f32_bits[i]);
 }
 
+/* ---- fp16 (IEEE binary16) <-> f32 --------------------------------------- */
+
+/* binary16: 1 sign, 5 exponent (bias 15), 10 mantissa bits.  Widening is exact. */
+static float f16_bits_to_f32(uint16_t h) {
+  uint32_t sign = (uint32_t)(h & 0x8000u) << 16;
+  uint32_t eh = (h >> 10) & 0x1Fu;
+  uint32_t mh = h & 0x3FFu;
+  uint32_t u;
+  if (eh == 0x1Fu) {
+    u = sign | 0x7F800000u | (mh << 13); /* inf, or NaN with its payload moved up */
+  } else if (eh != 0) {
+    u = sign | ((eh + 112u) << 23) | (mh << 13); /* rebias 15 -> 127 */
+  } else if (mh == 0) {
+    u = sign; /* +-0 */
+  } else {
+    /* subnormal: mh * 2^-24; normalise by hand */
+    uint32_t e = 113u; /* exponent field of 2^-14 */
+    while (!(mh & 0x400u)) {
+      mh <<= 1;
+      e -= 1u;
+    }
+    u = sign | (e << 23) | ((mh & 0x3FFu) << 13);
+  }
+  float f;
+  memcpy(&f, &u, sizeof f);
+  return f;
+}
+
+/* Round a binary32 to the nearest binary16, ties to the even mantissa.  The value is
+ * written as sig * 2^k with a 24-bit integer significand; the half keeps the top bits,
+ * the rule on (kept, dropped) is the same textbook rule as for bf16.  Results too small
+ * for a normal half become subnormal halves (multiples of 2^-24) or zero; a carry out of
+ * the mantissa moves into the exponent, so values from 65520 up round to infinity. */
+static uint16_t f32_to_f16_bits(float f) {
+  uint32_t u;
+  memcpy(&u, &f, sizeof u);
+  uint16_t sign = (uint16_t)((u >> 16) & 0x8000u);
+  uint32_t e = (u >> 23) & 0xFFu;
+  uint32_t m = u & 0x7FFFFFu;
+  if (e == 0xFFu) {
+    if (m == 0) return (uint16_t)(sign | 0x7C00u);            /* infinity */
+    return (uint16_t)(sign | 0x7E00u | (m >> 13));            /* NaN: quiet bit forced */
+  }
+  int eh = (int)e - 127 + 15; /* exponent field the half would have */
+  if (eh >= 0x1F) return (uint16_t)(sign | 0x7C00u);          /* beyond the half range */
+  uint32_t kept, dropped, half_ulp;
+  if (eh >= 1) {
+    kept = ((uint32_t)eh << 10) | (m >> 13);
+    dropped = m & 0x1FFFu;
+    half_ulp = 0x1000u;
+  } else {
+    if (e == 0) return sign;                                   /* fp32 subnormals are far below 2^-25 */
+    uint32_t sig = m | 0x800000u;                              /* 1.m as a 24-bit integer */
+    int r = 14 - eh;                                           /* |x| = (sig / 2^r) * 2^-24: r bits are dropped */
+    if (r > 24) return sign;                                   /* below half of the smallest subnormal */
+    kept = sig >> r;
+    dropped = sig & ((1u << r) - 1u);
+    half_ulp = 1u << (r - 1);
+  }
+  if (dropped > half_ulp || (dropped == half_ulp && (kept & 1u))) kept += 1u;
+  return (uint16_t)(sign | kept);
+}
+
+uint16_t pccl_oracle_f32_to_f16(uint32_t f32_bits) {
+  float f;
+  memcpy(&f, &f32_bits, sizeof f);
+  return f32_to_f16_bits(f);
+}
+
+void pccl_oracle_f32_to_f16_array(uint16_t* out, const uint32_t* f32_bits, size_t n) {
+  for (size_t i = 0; i < n; ++i) out[i] = pccl_oracle_f32_to_f16(f32_bits[i]);
+}
+
+void pccl_oracle_f16_to_f32_array(uint32_t* out, const uint16_t* f16_bits, size_t n) {
+  for (size_t i = 0; i < n; ++i) {
+    float f = f16_bits_to_f32(f16_bits[i]);
+    memcpy(&out[i], &f, sizeof f);
+  }
+}
+
 static float load_as_f32(const void* buf, size_t e, int dt) {
   if (dt == ORACLE_BF16) return bf16_bits_to_f32(((const uint16_t*)buf)[e]);
+  if (dt == ORACLE_F16) return f16_bits_to_f32(((const uint16_t*)buf)[e]);
   return ((const float*)buf)[e];
 }
 
 static void store_from_f32(void* buf, size_t e, int dt, float v) {
   if (dt == ORACLE_BF16)
     ((uint16_t*)buf)[e] = f32_to_bf16_bits(v);
+  else if (dt == ORACLE_F16)
+    ((uint16_t*)buf)[e] = f32_to_f16_bits(v);
   else
     ((float*)buf)[e] = v;
 }
@@ -102,10 +193,19 @@ static void store_from_f32(void* buf, size_t e, int dt, float v) {
 /* Value of v after a trip through storage of type dt. */
 static float round_through(float v, int dt) {
   if (dt == ORACLE_BF16) return bf16_bits_to_f32(f32_to_bf16_bits(v));
+  if (dt == ORACLE_F16) return f16_bits_to_f32(f32_to_f16_bits(v));
   return v;
 }
 
-static int dtype_ok(int dt) { return dt == ORACLE_F32 || dt == ORACLE_BF16; }
+static int dtype_ok(int dt) { return dt == ORACLE_F32 || dt == ORACLE_BF16 || dt == ORACLE_F16; }
+
+/* op = average (data-parallel training averages gradients, Section II-A): the finished
+ * binary32 sum is divided by the number of contributing ranks, one IEEE binary32
+ * division, before it is rounded to the output dtype.  divisor == 0 means plain sum. */
+static float finish(float acc, int divisor) {
+  if (divisor > 0) return acc / (float)divisor;
+  return acc;
+}
 
 /* ---- reductions -------------------------------------------------------- */
 
@@ -114,14 +214,15 @@ static int dtype_ok(int dt) { return dt == ORACLE_F32 || dt == ORACLE_BF16; }
  *   out[e] = ((x_0[e] + x_1[e]) + x_2[e]) + ... + x_{nsrc-1}[e]
  * accumulated in binary32, sources in the order given. */
 int pccl_oracle_flat_reduce(void* out, const void* const* srcs, int nsrc, size_t count,
-                            int in_dt, int out_dt, int nthreads) {
-  if (!out || !srcs || nsrc < 1 || !dtype_ok(in_dt) || !dtype_ok(out_dt)) return ORACLE_BAD_ARG;
+                            int in_dt, int out_dt, int divisor, int nthreads) {
+  if (!out || !srcs || nsrc < 1 || !dtype_ok(in_dt) || !dtype_ok(out_dt) || divisor < 0)
+    return ORACLE_BAD_ARG;
   if (nthreads < 1) nthreads = 1;
 #pragma omp parallel for num_threads(nthreads) schedule(static)
   for (size_t e = 0; e < count; ++e) {
     float acc = load_as_f32(srcs[0], e, in_dt);
     for (int s = 1; s < nsrc; ++s) acc = acc + load_as_f32(srcs[s], e, in_dt);
-    store_from_f32(out, e, out_dt, acc);
+    store_from_f32(out, e, out_dt, finish(acc, divisor));
   }
   return ORACLE_OK;
 }
@@ -134,8 +235,10 @@ int pccl_oracle_flat_reduce(void* out, const void* const* srcs, int nsrc, size_t
  *   out  = (p_0 + p_1) + ... + p_{nodes-1}              (left to right)
  * If partials != NULL it receives p_n as [nodes][count] of in_dt. */
 int pccl_oracle_two_level_reduce(void* out, void* partials, const void* const* srcs, int nodes,
-                                 int gpus, size_t count, int in_dt, int out_dt, int nthreads) {
-  if (!out || !srcs || nodes < 1 || gpus < 1 || !dtype_ok(in_dt) || !dtype_ok(out_dt))
+                                 int gpus, size_t count, int in_dt, int out_dt, int divisor,
+                                 int nthreads) {
+  if (!out || !srcs || nodes < 1 || gpus < 1 || !dtype_ok(in_dt) || !dtype_ok(out_dt) ||
+      divisor < 0)
     return ORACLE_BAD_ARG;
   if (nthreads < 1) nthreads = 1;
 #pragma omp parallel for num_threads(nthreads) schedule(static)
@@ -148,7 +251,7 @@ int pccl_oracle_two_level_reduce(void* out, void* partials, const void* const* s
       if (partials) store_from_f32(partials, (size_t)n * count + e, in_dt, p);
       acc = (n == 0) ? p : acc + p;
     }
-    store_from_f32(out, e, out_dt, acc);
+    store_from_f32(out, e, out_dt, finish(acc, divisor));
   }
   return ORACLE_OK;
 }
@@ -173,10 +276,11 @@ int pccl_oracle_rs_phase1(void* partial, const void* const* pieces, int nodes, i
 
 /* Phase 2 (inter-node): inter[n] is the chunk received from node n (this
  * node's own partial included, at its own index).
- *   shard[e] = round_out( inter_0[e] + inter_1[e] + ... + inter_{nodes-1}[e] ) */
+ *   shard[e] = round_out( inter_0[e] + inter_1[e] + ... + inter_{nodes-1}[e] )
+ * (divided by `divisor`, the total rank count, first when the op is average) */
 int pccl_oracle_rs_phase2(void* shard, const void* const* inter, int nodes, size_t chunk,
-                          int io_dt, int out_dt, int nthreads) {
-  return pccl_oracle_flat_reduce(shard, inter, nodes, chunk, io_dt, out_dt, nthreads);
+                          int io_dt, int out_dt, int divisor, int nthreads) {
+  return pccl_oracle_flat_reduce(shard, inter, nodes, chunk, io_dt, out_dt, divisor, nthreads);
 }
 
 /* The paper's GPU vector-reduction kernel in its literal form (Section III-B: a
