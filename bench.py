@@ -157,6 +157,20 @@ def other_workloads(dev):
           *time_calls([lambda s=s: pccl.pccl_allgather_reassemble(
               s[3], src=s[2], nodes=w.nodes, gpus_per_node=w.gpus) for s in sets]))
     del sets
+    # op = average and fp16 messages on the 256 MB two-level share (same bytes as the headline's reduce call)
+    w = W.cfg3()
+    nb = (w.gpus + 1) * w.nodes * w.chunk * 2 + (w.nodes + 1) * w.chunk * 2
+    for tag, dt, avg in (("bf16_average", torch.bfloat16, True), ("f16_sum", torch.float16, False)):
+        sets = []
+        for k in range(4):
+            x = W.uniform_pm1(w.gpus * w.nodes * w.chunk, 300 + k, dev, dt).view(w.gpus, w.nodes, w.chunk)
+            inter = W.uniform_pm1(w.nodes * w.chunk, 310 + k, dev, dt).view(w.nodes, w.chunk)
+            sets.append((torch.empty(w.chunk, dtype=dt, device=dev), torch.empty(w.nodes * w.chunk, dtype=dt, device=dev),
+                         x, pccl.device_pointer_array([inter[j] for j in range(w.nodes)]), inter))
+        entry("cfg3_reduce_scatter_local_%s_256MB" % tag, nb,
+              *time_calls([lambda s=s: pccl.pccl_reduce_scatter_local(s[0], s[1], s[2], d_inter=s[3], my_node=5,
+                                                                      average=avg) for s in sets]))
+        del sets
     # the paper's literal two-source step (acc += recv) and one rank's replay of its inter-node algorithms
     w = W.cfg3()
     n = 64 * MB                                                     # 128 MB of bf16

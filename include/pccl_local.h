@@ -39,9 +39,10 @@
  *              pointer-array forms it is undefined behaviour.
  *   Arithmetic Every sum is accumulated in IEEE binary32 with round-to-nearest-even adds,
  *              no FMA, no reassociation, subnormals kept; the accumulator starts from the
- *              first source.  bf16 -> fp32 widening is exact; fp32 -> bf16 rounds to
- *              nearest even (a NaN stays a quiet NaN of the same sign; its payload is
- *              unspecified).  Results are therefore bit-reproducible.
+ *              first source.  bf16 / fp16 -> fp32 widening is exact; fp32 -> bf16 / fp16
+ *              rounds to nearest even, overflows to infinity and keeps subnormals (a NaN
+ *              stays a quiet NaN of the same sign; its payload is unspecified).  Results
+ *              are therefore bit-reproducible.
  */
 #ifndef PCCL_LOCAL_H
 #define PCCL_LOCAL_H
@@ -57,13 +58,22 @@ typedef enum {
   PCCL_OK = 0,
   PCCL_ERR_NULL = 1,        /* a required pointer is NULL */
   PCCL_ERR_INVALID = 2,     /* a count, stride, index or size is out of range or overflows */
-  PCCL_ERR_UNSUPPORTED = 3, /* unknown dtype / op */
+  PCCL_ERR_UNSUPPORTED = 3, /* unknown dtype, dtype pair or op */
   PCCL_ERR_OVERLAP = 4,     /* an output range overlaps an input range */
   PCCL_ERR_HIP = 5          /* the HIP runtime refused a launch */
 } pccl_status_t;
 
-typedef enum { PCCL_F32 = 0, PCCL_BF16 = 1 } pccl_dtype_t;
-typedef enum { PCCL_SUM = 0 } pccl_op_t; /* the paper's collectives are sums */
+/* fp32, bf16 and fp16 (IEEE binary16) elements.  Where an entry point takes an input and an
+ * output dtype, the pair is a type with itself or fp32 on one side (bf16 with fp16 is
+ * PCCL_ERR_UNSUPPORTED). */
+typedef enum { PCCL_F32 = 0, PCCL_BF16 = 1, PCCL_F16 = 2 } pccl_dtype_t;
+/* PCCL_SUM: the paper's collectives are sums.  PCCL_AVG (data-parallel training averages
+ * gradients, Section II-A): the finished binary32 sum is divided by the number of
+ * contributing ranks -- nsrc, or nodes*gpus_per_node -- with one IEEE binary32 division
+ * before the output rounding; node partials stay plain sums.  The rank count must not
+ * exceed 2^24.  The step-wise entry points (pccl_accumulate and the ring / halving replays)
+ * take PCCL_SUM only. */
+typedef enum { PCCL_SUM = 0, PCCL_AVG = 1 } pccl_op_t;
 typedef void* pccl_stream_t;             /* a hipStream_t */
 
 /* One bucket of a batched two-level reduce-scatter share (see

@@ -12,8 +12,8 @@ import torch
 from . import build as _build
 
 PCCL_OK, PCCL_ERR_NULL, PCCL_ERR_INVALID, PCCL_ERR_UNSUPPORTED, PCCL_ERR_OVERLAP, PCCL_ERR_HIP = range(6)
-PCCL_F32, PCCL_BF16 = 0, 1
-PCCL_SUM = 0
+PCCL_F32, PCCL_BF16, PCCL_F16 = 0, 1, 2
+PCCL_SUM, PCCL_AVG = 0, 1
 PCCL_MAX_BUCKETS = 512
 
 EXPORTS = (
@@ -82,7 +82,13 @@ def dtype_code(dt):
         return PCCL_F32
     if dt == torch.bfloat16:
         return PCCL_BF16
-    raise TypeError("pccl: dtype must be torch.float32 or torch.bfloat16, got %s" % dt)
+    if dt == torch.float16:
+        return PCCL_F16
+    raise TypeError("pccl: dtype must be torch.float32, torch.bfloat16 or torch.float16, got %s" % dt)
+
+
+def _op(average):
+    return PCCL_AVG if average else PCCL_SUM
 
 
 def _stream(stream):
@@ -115,32 +121,33 @@ def device_pointer_array(tensors, device=None):
 
 
 # ------------------------------------------------------------------------------- entry points
-def pccl_local_reduce(dst, src, stream=None):
+def pccl_local_reduce(dst, src, stream=None, average=False):
     """dst[e] = sum over rows s of src[s][e], rows in order; src is [nsrc, ...] with contiguous rows."""
     base, stride, nsrc, count = _rows(src, "src")
     if dst.numel() != count or not dst.is_contiguous():
         raise ValueError("pccl_local_reduce: dst must be contiguous with one source's element count")
     _check(lib().pccl_local_reduce(_dev(dst, "dst"), base, stride, nsrc, count, dtype_code(src.dtype),
-                                   dtype_code(dst.dtype), PCCL_SUM, _stream(stream)),
+                                   dtype_code(dst.dtype), _op(average), _stream(stream)),
            "pccl_local_reduce")
     return dst
 
 
-def pccl_local_reduce_ptrs(dst, d_srcs, count, in_dtype, stream=None):
+def pccl_local_reduce_ptrs(dst, d_srcs, count, in_dtype, stream=None, average=False):
     """Flat sum over a device pointer array (int64 tensor) of sources holding `count` elements."""
     _check(lib().pccl_local_reduce_ptrs(_dev(dst, "dst"), _dev(d_srcs, "d_srcs"), d_srcs.numel(), count,
-                                        dtype_code(in_dtype), dtype_code(dst.dtype), PCCL_SUM,
+                                        dtype_code(in_dtype), dtype_code(dst.dtype), _op(average),
                                         _stream(stream)), "pccl_local_reduce_ptrs")
     return dst
 
 
-def pccl_local_reduce_ptrs_two_level(dst, d_srcs, nodes, gpus_per_node, count, in_dtype, stream=None):
+def pccl_local_reduce_ptrs_two_level(dst, d_srcs, nodes, gpus_per_node, count, in_dtype, stream=None,
+                                     average=False):
     """Two-level sum over a node-major device pointer array: d_srcs[n*gpus_per_node + g]."""
     if d_srcs.numel() != nodes * gpus_per_node:
         raise ValueError("pccl_local_reduce_ptrs_two_level: need nodes*gpus_per_node pointers")
     _check(lib().pccl_local_reduce_ptrs_two_level(
         _dev(dst, "dst"), _dev(d_srcs, "d_srcs"), nodes, gpus_per_node, count, dtype_code(in_dtype),
-        dtype_code(dst.dtype), PCCL_SUM, _stream(stream)), "pccl_local_reduce_ptrs_two_level")
+        dtype_code(dst.dtype), _op(average), _stream(stream)), "pccl_local_reduce_ptrs_two_level")
     return dst
 
 
@@ -171,7 +178,7 @@ def pccl_hier_unpack(dst, src, nodes, gpus_per_node, stream=None):
     return dst
 
 
-def pccl_reduce_scatter_local(shard, partial, intra, d_inter=None, my_node=0, stream=None):
+def pccl_reduce_scatter_local(shard, partial, intra, d_inter=None, my_node=0, stream=None, average=False):
     """One GPU's share of a two-level reduce-scatter.
 
     intra: [gpus][nodes][chunk] (piece g' = intra[g'], rows may be strided apart);
@@ -189,7 +196,7 @@ def pccl_reduce_scatter_local(shard, partial, intra, d_inter=None, my_node=0, st
     _check(lib().pccl_reduce_scatter_local(
         _dev(shard, "shard"), _dev(partial, "partial"), base, stride,
         None if d_inter is None else _dev(d_inter, "d_inter"), nodes, gpus, my_node, chunk,
-        dtype_code(intra.dtype), PCCL_SUM, _stream(stream)), "pccl_reduce_scatter_local")
+        dtype_code(intra.dtype), _op(average), _stream(stream)), "pccl_reduce_scatter_local")
     return shard
 
 
@@ -227,13 +234,13 @@ class BucketTable:
         self._keep = buckets  # the table holds raw pointers: keep the tensors alive
 
 
-def pccl_reduce_scatter_local_batched(table, stream=None):
+def pccl_reduce_scatter_local_batched(table, stream=None, average=False):
     """All buckets of a BucketTable: phase 1 in one launch, phase 2 in one launch."""
     if table.nbuckets == 0:
         return
     _check(lib().pccl_reduce_scatter_local_batched(
         table.device.data_ptr(), ctypes.addressof(table.host), table.nbuckets, table.nodes, table.gpus,
-        dtype_code(table.dtype), PCCL_SUM, _stream(stream)), "pccl_reduce_scatter_local_batched")
+        dtype_code(table.dtype), _op(average), _stream(stream)), "pccl_reduce_scatter_local_batched")
 
 
 def pccl_accumulate(acc, recv, stream=None):
@@ -279,7 +286,7 @@ def pccl_halving_reduce_scatter_local(msg, recv, rank, stream=None):
 
 
 def pccl_reduce_scatter_local_unpacked(shard, partial, msgs=None, d_msgs=None, d_inter=None, nodes=1,
-                                       gpus_per_node=1, my_node=0, my_gpu=0, stream=None):
+                                       gpus_per_node=1, my_node=0, my_gpu=0, stream=None, average=False):
     """The two-level reduce-scatter share straight from the node-mates' rank-order messages.
 
     msgs: [gpus][nodes*gpus*chunk] tensor (row g' = node-mate g's message, rows may be strided
@@ -300,5 +307,5 @@ def pccl_reduce_scatter_local_unpacked(shard, partial, msgs=None, d_msgs=None, d
         _dev(shard, "shard"), _dev(partial, "partial"), base, stride,
         None if d_msgs is None else _dev(d_msgs, "d_msgs"),
         None if d_inter is None else _dev(d_inter, "d_inter"), nodes, gpus_per_node, my_node, my_gpu, chunk,
-        dtype_code(shard.dtype), PCCL_SUM, _stream(stream)), "pccl_reduce_scatter_local_unpacked")
+        dtype_code(shard.dtype), _op(average), _stream(stream)), "pccl_reduce_scatter_local_unpacked")
     return shard

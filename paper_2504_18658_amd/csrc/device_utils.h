@@ -1,5 +1,5 @@
 // Device-side helpers for the gfx950 kernels: 128-bit streaming loads/stores with an
-// element-wise fallback for unaligned buffers, and bf16 <-> fp32 conversion.
+// element-wise fallback for unaligned buffers, and bf16 / fp16 <-> fp32 conversion.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -13,20 +13,51 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kBlock = 256;  // threads per block of the streaming kernels (4 wavefronts)
 
-// ---- bf16 ----------------------------------------------------------------------------
-// A 32-bit word holds two bf16: element 2k in the low half, 2k+1 in the high half.
-__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
-__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
+// ---- message dtypes ----------------------------------------------------------------------
+// Values of pccl_dtype_t, used as template parameters.  A 32-bit word holds two 16-bit
+// elements: element 2k in the low half, 2k+1 in the high half.
+constexpr int kF32 = 0;
+constexpr int kBF16 = 1;
+constexpr int kF16 = 2;
+constexpr bool narrow(int dt) { return dt != kF32; }  // a 16-bit element type
 
-// fp32 pair -> packed bf16 pair, round to nearest even (v_cvt_pk_bf16_f32 on gfx950).
-__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
-  f32x2 v = {lo, hi};
-  bf16x2 b = __builtin_convertvector(v, bf16x2);
-  return __builtin_bit_cast(uint32_t, b);
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+
+// low / high element of a packed pair, widened to fp32 (exact for both 16-bit types)
+template <int DT>
+__device__ __forceinline__ float lo16(uint32_t w) {
+  if constexpr (DT == kF16) return (float)__builtin_bit_cast(f16x2, w)[0];
+  return __uint_as_float(w << 16);
 }
-__device__ __forceinline__ uint16_t to_bf16(float x) { return (uint16_t)(pack_bf16(x, 0.0f) & 0xFFFFu); }
-// Value of x after a trip through bf16 storage.
-__device__ __forceinline__ float round_through_bf16(float x) { return bf16_lo(pack_bf16(x, 0.0f)); }
+template <int DT>
+__device__ __forceinline__ float hi16(uint32_t w) {
+  if constexpr (DT == kF16) return (float)__builtin_bit_cast(f16x2, w)[1];
+  return __uint_as_float(w & 0xFFFF0000u);
+}
+
+// fp32 pair -> packed 16-bit pair, round to nearest even (v_cvt_pk_bf16_f32 on gfx950 for
+// bf16; v_cvt_f16_f32 for fp16, which rounds to nearest even and keeps subnormal halves).
+template <int DT>
+__device__ __forceinline__ uint32_t pack16(float lo, float hi) {
+  f32x2 v = {lo, hi};
+  if constexpr (DT == kF16) {
+    f16x2 h = __builtin_convertvector(v, f16x2);
+    return __builtin_bit_cast(uint32_t, h);
+  } else {
+    bf16x2 b = __builtin_convertvector(v, bf16x2);
+    return __builtin_bit_cast(uint32_t, b);
+  }
+}
+template <int DT>
+__device__ __forceinline__ uint16_t to16(float x) {
+  return (uint16_t)(pack16<DT>(x, 0.0f) & 0xFFFFu);
+}
+// Value of x after a trip through storage of type DT.
+template <int DT>
+__device__ __forceinline__ float round_through(float x) {
+  if constexpr (DT == kF32) return x;
+  return lo16<DT>(pack16<DT>(x, 0.0f));
+}
 
 // ---- streaming global access ------------------------------------------------------------
 // Every buffer the library touches is device global memory.  Pointers arrive inside
@@ -122,17 +153,17 @@ __device__ __forceinline__ void st_words(char* base, size_t byte_off, const uint
 }
 
 // One element as fp32 / from fp32.
-template <bool BF16>
+template <int DT>
 __device__ __forceinline__ float ld_elem(const char* base, size_t e) {
-  if (BF16) return __uint_as_float((uint32_t)ld_stream<uint16_t>(base + 2 * e) << 16);
-  return ld_stream<float>(base + 4 * e);
+  if constexpr (DT == kF32) return ld_stream<float>(base + 4 * e);
+  return lo16<DT>((uint32_t)ld_stream<uint16_t>(base + 2 * e));
 }
-template <bool BF16>
+template <int DT>
 __device__ __forceinline__ void st_elem(char* base, size_t e, float v) {
-  if (BF16)
-    st_stream<uint16_t>(base + 2 * e, to_bf16(v));
-  else
+  if constexpr (DT == kF32)
     st_stream<float>(base + 4 * e, v);
+  else
+    st_stream<uint16_t>(base + 2 * e, to16<DT>(v));
 }
 
 }  // namespace pccl

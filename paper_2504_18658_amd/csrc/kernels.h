@@ -14,7 +14,8 @@ namespace pccl {
 //   else            : base + n*stride_n + g*stride_g
 // and holds `count` elements.  For every element e:
 //   t_n = x[n][0][e] + ... + x[n][gpus-1][e];  p_n = round_partial ? through in_dt : t_n
-//   partial[n*count + e] = p_n (if partial != nullptr, in in_dt);  dst[e] = p_0 + ... + p_{nodes-1}
+//   partial[n*count + e] = p_n (if partial != nullptr, in in_dt);  dst[e] = p_0 + ... + p_{nodes-1},
+//   divided by `divisor` (one IEEE division) when divisor != 0: op = average
 // `rows` > 1 repeats the problem for rows r = 0 .. rows-1 (the streaming kernel's grid.y):
 // row r reads every source at +r*row_stride_src bytes and writes dst at +r*row_stride_dst
 // bytes (partial must be nullptr then).  src_offset is added to pointer-array entries.
@@ -35,6 +36,7 @@ struct ReduceProblem {
   int override_index;  // -1: none
   int round_partial;
   int rows;
+  float divisor;
 };
 
 // Chunk-granular transpose: dst chunk (c*rows + r) = src chunk (r*cols + c); src chunk k is
@@ -55,19 +57,22 @@ struct BatchTiles {
   uint32_t first_tile[kMaxBuckets + 1];
 };
 
-hipError_t launch_reduce(const ReduceProblem& p, bool in_bf16, bool out_bf16, hipStream_t st);
-hipError_t launch_reduce_two_level_lds(const ReduceProblem& p, bool in_bf16, bool out_bf16,
+// in_dt / out_dt are pccl_dtype_t values; unsupported pairs return hipErrorInvalidValue.
+hipError_t launch_reduce(const ReduceProblem& p, int in_dt, int out_dt, hipStream_t st);
+hipError_t launch_reduce_two_level_lds(const ReduceProblem& p, int in_dt, int out_dt,
                                        hipStream_t st);
 // True when the LDS-staged kernel is the better choice for this shape.
-bool prefer_lds_two_level(const ReduceProblem& p, bool in_bf16);
+bool prefer_lds_two_level(const ReduceProblem& p, int in_dt);
 
 hipError_t launch_permute(const PermuteProblem& p, hipStream_t st);
 
 // acc[e] = round_io(acc[e] + recv[e]) for e < count, in place (the two ranges are disjoint).
-hipError_t launch_accumulate(void* acc, const void* recv, size_t count, bool bf16, hipStream_t st);
+hipError_t launch_accumulate(void* acc, const void* recv, size_t count, int dt, hipStream_t st);
 
 // Batched two-level reduce-scatter share; h_buckets is the host copy used to size the grid.
+// Phase 2 divides by `divisor` when it is not 0 (op = average).
 hipError_t launch_rs_batched(const pccl_bucket_t* d_buckets, const pccl_bucket_t* h_buckets,
-                             int nbuckets, int nodes, int gpus, bool bf16, hipStream_t st);
+                             int nbuckets, int nodes, int gpus, int dt, float divisor,
+                             hipStream_t st);
 
 }  // namespace pccl

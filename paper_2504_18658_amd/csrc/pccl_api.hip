@@ -11,8 +11,8 @@ namespace {
 using pccl::PermuteProblem;
 using pccl::ReduceProblem;
 
-inline bool dtype_ok(pccl_dtype_t d) { return d == PCCL_F32 || d == PCCL_BF16; }
-inline size_t esize(pccl_dtype_t d) { return d == PCCL_BF16 ? 2 : 4; }
+inline bool dtype_ok(pccl_dtype_t d) { return d == PCCL_F32 || d == PCCL_BF16 || d == PCCL_F16; }
+inline size_t esize(pccl_dtype_t d) { return d == PCCL_F32 ? 4 : 2; }
 
 inline bool mul_ok(size_t a, size_t b, size_t* out) { return !__builtin_mul_overflow(a, b, out); }
 inline bool add_ok(size_t a, size_t b, size_t* out) { return !__builtin_add_overflow(a, b, out); }
@@ -48,6 +48,7 @@ ReduceProblem blank_problem() {
   p.override_index = -1;
   p.round_partial = 0;
   p.rows = 1;
+  p.divisor = 0.0f;
   return p;
 }
 
@@ -61,11 +62,18 @@ int forced_two_level_kernel() {
   return 0;
 }
 
+// dtype pairs: a type with itself, or fp32 on one side (never bf16 mixed with fp16)
 pccl_status_t check_common(pccl_dtype_t in_dt, pccl_dtype_t out_dt, pccl_op_t op) {
   if (!dtype_ok(in_dt) || !dtype_ok(out_dt)) return PCCL_ERR_UNSUPPORTED;
-  if (op != PCCL_SUM) return PCCL_ERR_UNSUPPORTED;
+  if (in_dt != out_dt && in_dt != PCCL_F32 && out_dt != PCCL_F32) return PCCL_ERR_UNSUPPORTED;
+  if (op != PCCL_SUM && op != PCCL_AVG) return PCCL_ERR_UNSUPPORTED;
   return PCCL_OK;
 }
+
+// op = average divides the finished sum by the number of contributing ranks; the count must
+// be exact in binary32
+inline bool divisor_ok(pccl_op_t op, size_t ranks) { return op != PCCL_AVG || ranks <= (1u << 24); }
+inline float divisor_for(pccl_op_t op, size_t ranks) { return op == PCCL_AVG ? (float)ranks : 0.0f; }
 
 pccl_status_t permute_common(void* dst, const void* src, const void* const* slots, int rows,
                              int cols, size_t chunk_bytes, pccl_stream_t stream) {
@@ -91,11 +99,12 @@ pccl_status_t permute_common(void* dst, const void* src, const void* const* slot
 // phase 2 (inter-node) of a two-level reduce-scatter share: shard[e] = sum over n' of
 // inter_n'[e], an N-source flat sum over the partial's rows or over received chunks
 pccl_status_t phase2(void* shard, void* partial, const void* const* d_inter, int nodes, int my_node,
-                     size_t chunk_count, size_t chunk_bytes, bool bf, hipStream_t st) {
+                     size_t chunk_count, size_t chunk_bytes, int dt, float divisor, hipStream_t st) {
   ReduceProblem p2 = blank_problem();
   p2.dst = shard;
   p2.count = chunk_count;
   p2.gpus = nodes;
+  p2.divisor = divisor;
   if (d_inter == nullptr) {
     p2.base = reinterpret_cast<const char*>(partial);
     p2.stride_g = chunk_bytes;
@@ -104,7 +113,7 @@ pccl_status_t phase2(void* shard, void* partial, const void* const* d_inter, int
     p2.override_index = my_node;
     p2.override_ptr = reinterpret_cast<const char*>(partial) + (size_t)my_node * chunk_bytes;
   }
-  const hipError_t e = pccl::launch_reduce(p2, bf, bf, st);
+  const hipError_t e = pccl::launch_reduce(p2, dt, dt, st);
   return e == hipErrorInvalidValue ? PCCL_ERR_INVALID : from_hip(e);
 }
 
@@ -117,7 +126,7 @@ pccl_status_t pccl_local_reduce(void* dst, const void* src_base, size_t src_stri
                                 pccl_dtype_t out_dt, pccl_op_t op, pccl_stream_t stream) {
   if (dst == nullptr || src_base == nullptr) return PCCL_ERR_NULL;
   if (pccl_status_t s = check_common(in_dt, out_dt, op)) return s;
-  if (nsrc < 1) return PCCL_ERR_INVALID;
+  if (nsrc < 1 || !divisor_ok(op, (size_t)nsrc)) return PCCL_ERR_INVALID;
   const size_t ei = esize(in_dt), eo = esize(out_dt);
   size_t in_bytes, out_bytes, span;
   if (!mul_ok(count, ei, &in_bytes) || !mul_ok(count, eo, &out_bytes)) return PCCL_ERR_INVALID;
@@ -135,8 +144,8 @@ pccl_status_t pccl_local_reduce(void* dst, const void* src_base, size_t src_stri
   p.stride_g = nsrc > 1 ? src_stride_bytes : 0;
   p.count = count;
   p.gpus = nsrc;
-  const hipError_t e = pccl::launch_reduce(p, in_dt == PCCL_BF16, out_dt == PCCL_BF16,
-                                           reinterpret_cast<hipStream_t>(stream));
+  p.divisor = divisor_for(op, (size_t)nsrc);
+  const hipError_t e = pccl::launch_reduce(p, in_dt, out_dt, reinterpret_cast<hipStream_t>(stream));
   return e == hipErrorInvalidValue ? PCCL_ERR_INVALID : from_hip(e);
 }
 
@@ -145,7 +154,7 @@ pccl_status_t pccl_local_reduce_ptrs(void* dst, const void* const* d_srcs, int n
                                      pccl_op_t op, pccl_stream_t stream) {
   if (dst == nullptr || d_srcs == nullptr) return PCCL_ERR_NULL;
   if (pccl_status_t s = check_common(in_dt, out_dt, op)) return s;
-  if (nsrc < 1) return PCCL_ERR_INVALID;
+  if (nsrc < 1 || !divisor_ok(op, (size_t)nsrc)) return PCCL_ERR_INVALID;
   size_t bytes;
   if (!mul_ok(count, esize(in_dt), &bytes) || !mul_ok(count, esize(out_dt), &bytes))
     return PCCL_ERR_INVALID;
@@ -156,7 +165,8 @@ pccl_status_t pccl_local_reduce_ptrs(void* dst, const void* const* d_srcs, int n
   p.ptrs = d_srcs;
   p.count = count;
   p.gpus = nsrc;
-  const bool ib = in_dt == PCCL_BF16, ob = out_dt == PCCL_BF16;
+  p.divisor = divisor_for(op, (size_t)nsrc);
+  const int ib = in_dt, ob = out_dt;
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   // A long flat chain over short buffers: stage the sources through LDS (a flat sum is the
   // two-level sum with one GPU per node) so that the loads of many sources overlap.
@@ -177,7 +187,8 @@ pccl_status_t pccl_local_reduce_ptrs_two_level(void* dst, const void* const* d_s
   if (pccl_status_t s = check_common(in_dt, out_dt, op)) return s;
   if (nodes < 1 || gpus_per_node < 1) return PCCL_ERR_INVALID;
   size_t ranks, bytes;
-  if (!mul_ok((size_t)nodes, (size_t)gpus_per_node, &ranks) || ranks > 0x7FFFFFFFull)
+  if (!mul_ok((size_t)nodes, (size_t)gpus_per_node, &ranks) || ranks > 0x7FFFFFFFull ||
+      !divisor_ok(op, ranks))
     return PCCL_ERR_INVALID;
   if (!mul_ok(count, esize(in_dt), &bytes) || !mul_ok(count, esize(out_dt), &bytes))
     return PCCL_ERR_INVALID;
@@ -190,7 +201,8 @@ pccl_status_t pccl_local_reduce_ptrs_two_level(void* dst, const void* const* d_s
   p.nodes = nodes;
   p.gpus = gpus_per_node;
   p.round_partial = 1;
-  const bool ib = in_dt == PCCL_BF16, ob = out_dt == PCCL_BF16;
+  p.divisor = divisor_for(op, ranks);
+  const int ib = in_dt, ob = out_dt;
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   const int forced = forced_two_level_kernel();
   const bool lds = forced == 2 || (forced == 0 && pccl::prefer_lds_two_level(p, ib));
@@ -228,6 +240,7 @@ pccl_status_t pccl_reduce_scatter_local(void* shard, void* partial, const void* 
   if (shard == nullptr || partial == nullptr || intra_base == nullptr) return PCCL_ERR_NULL;
   if (pccl_status_t s = check_common(io_dt, io_dt, op)) return s;
   if (nodes < 1 || gpus_per_node < 1 || my_node < 0 || my_node >= nodes) return PCCL_ERR_INVALID;
+  if (!divisor_ok(op, (size_t)nodes * (size_t)gpus_per_node)) return PCCL_ERR_INVALID;
   const size_t es = esize(io_dt);
   size_t piece_count, piece_bytes, chunk_bytes, span;
   if (!mul_ok((size_t)nodes, chunk_count, &piece_count) || !mul_ok(piece_count, es, &piece_bytes))
@@ -245,7 +258,8 @@ pccl_status_t pccl_reduce_scatter_local(void* shard, void* partial, const void* 
       overlaps(shard, chunk_bytes, partial, piece_bytes))
     return PCCL_ERR_OVERLAP;
   if (chunk_count == 0) return PCCL_OK;
-  const bool bf = io_dt == PCCL_BF16;
+  const int dt = io_dt;
+  const float divisor = divisor_for(op, (size_t)nodes * (size_t)gpus_per_node);
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
 
   // phase 1 (intra-node): partial[n][e] = sum over g' of piece_g'[n][e], an M-source flat
@@ -256,10 +270,10 @@ pccl_status_t pccl_reduce_scatter_local(void* shard, void* partial, const void* 
   p1.stride_g = gpus_per_node > 1 ? intra_stride_bytes : 0;
   p1.count = piece_count;
   p1.gpus = gpus_per_node;
-  hipError_t e = pccl::launch_reduce(p1, bf, bf, st);
+  hipError_t e = pccl::launch_reduce(p1, dt, dt, st);
   if (e != hipSuccess) return e == hipErrorInvalidValue ? PCCL_ERR_INVALID : PCCL_ERR_HIP;
 
-  return phase2(shard, partial, d_inter, nodes, my_node, chunk_count, chunk_bytes, bf, st);
+  return phase2(shard, partial, d_inter, nodes, my_node, chunk_count, chunk_bytes, dt, divisor, st);
 }
 
 pccl_status_t pccl_reduce_scatter_local_unpacked(void* shard, void* partial, const void* msgs_base,
@@ -273,7 +287,8 @@ pccl_status_t pccl_reduce_scatter_local_unpacked(void* shard, void* partial, con
     return PCCL_ERR_NULL;
   if (pccl_status_t s = check_common(io_dt, io_dt, op)) return s;
   if (nodes < 1 || gpus_per_node < 1 || my_node < 0 || my_node >= nodes || my_gpu < 0 ||
-      my_gpu >= gpus_per_node || nodes > 65535)
+      my_gpu >= gpus_per_node || nodes > 65535 ||
+      !divisor_ok(op, (size_t)nodes * (size_t)gpus_per_node))
     return PCCL_ERR_INVALID;
   const size_t es = esize(io_dt);
   size_t chunk_bytes, node_bytes, msg_bytes, piece_bytes, span;
@@ -296,7 +311,8 @@ pccl_status_t pccl_reduce_scatter_local_unpacked(void* shard, void* partial, con
       return PCCL_ERR_OVERLAP;
   }
   if (chunk_count == 0) return PCCL_OK;
-  const bool bf = io_dt == PCCL_BF16;
+  const int dt = io_dt;
+  const float divisor = divisor_for(op, (size_t)nodes * (size_t)gpus_per_node);
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
 
   // phase 1 straight from the rank-order messages: row n of the partial sums chunk
@@ -315,9 +331,9 @@ pccl_status_t pccl_reduce_scatter_local_unpacked(void* shard, void* partial, con
     p1.ptrs = d_msgs;
     p1.src_offset = (size_t)my_gpu * chunk_bytes;
   }
-  const hipError_t e = pccl::launch_reduce(p1, bf, bf, st);
+  const hipError_t e = pccl::launch_reduce(p1, dt, dt, st);
   if (e != hipSuccess) return e == hipErrorInvalidValue ? PCCL_ERR_INVALID : PCCL_ERR_HIP;
-  return phase2(shard, partial, d_inter, nodes, my_node, chunk_count, chunk_bytes, bf, st);
+  return phase2(shard, partial, d_inter, nodes, my_node, chunk_count, chunk_bytes, dt, divisor, st);
 }
 
 pccl_status_t pccl_reduce_scatter_local_batched(const pccl_bucket_t* d_buckets,
@@ -329,6 +345,7 @@ pccl_status_t pccl_reduce_scatter_local_batched(const pccl_bucket_t* d_buckets,
   if (nbuckets > 0 && (d_buckets == nullptr || h_buckets == nullptr)) return PCCL_ERR_NULL;
   if (pccl_status_t s = check_common(io_dt, io_dt, op)) return s;
   if (nodes < 1 || gpus_per_node < 1) return PCCL_ERR_INVALID;
+  if (!divisor_ok(op, (size_t)nodes * (size_t)gpus_per_node)) return PCCL_ERR_INVALID;
   const size_t es = esize(io_dt);
   bool any = false;
   for (int b = 0; b < nbuckets; ++b) {
@@ -358,8 +375,9 @@ pccl_status_t pccl_reduce_scatter_local_batched(const pccl_bucket_t* d_buckets,
   }
   if (!any) return PCCL_OK;
   const hipError_t e =
-      pccl::launch_rs_batched(d_buckets, h_buckets, nbuckets, nodes, gpus_per_node,
-                              io_dt == PCCL_BF16, reinterpret_cast<hipStream_t>(stream));
+      pccl::launch_rs_batched(d_buckets, h_buckets, nbuckets, nodes, gpus_per_node, io_dt,
+                              divisor_for(op, (size_t)nodes * (size_t)gpus_per_node),
+                              reinterpret_cast<hipStream_t>(stream));
   return e == hipErrorInvalidValue ? PCCL_ERR_INVALID : from_hip(e);
 }
 
@@ -367,12 +385,13 @@ pccl_status_t pccl_accumulate(void* acc, const void* recv, size_t count, pccl_dt
                               pccl_op_t op, pccl_stream_t stream) {
   if (acc == nullptr || recv == nullptr) return PCCL_ERR_NULL;
   if (pccl_status_t s = check_common(io_dt, io_dt, op)) return s;
+  if (op != PCCL_SUM) return PCCL_ERR_UNSUPPORTED;  // a step adds; scaling belongs to the last store
   const size_t es = esize(io_dt);
   size_t bytes;
   if (!mul_ok(count, es, &bytes)) return PCCL_ERR_INVALID;
   if (!elem_aligned(acc, es) || !elem_aligned(recv, es)) return PCCL_ERR_INVALID;
   if (overlaps(acc, bytes, recv, bytes)) return PCCL_ERR_OVERLAP;
-  const hipError_t e = pccl::launch_accumulate(acc, recv, count, io_dt == PCCL_BF16,
+  const hipError_t e = pccl::launch_accumulate(acc, recv, count, io_dt,
                                                reinterpret_cast<hipStream_t>(stream));
   return e == hipErrorInvalidValue ? PCCL_ERR_INVALID : from_hip(e);
 }
@@ -383,6 +402,7 @@ pccl_status_t pccl_ring_reduce_scatter_local(void* msg, const void* recv_base,
                                              pccl_op_t op, pccl_stream_t stream) {
   if (msg == nullptr || recv_base == nullptr) return PCCL_ERR_NULL;
   if (pccl_status_t s = check_common(io_dt, io_dt, op)) return s;
+  if (op != PCCL_SUM) return PCCL_ERR_UNSUPPORTED;
   if (nranks < 1 || rank < 0 || rank >= nranks) return PCCL_ERR_INVALID;
   const size_t es = esize(io_dt);
   size_t chunk_bytes, msg_bytes, span;
@@ -404,7 +424,7 @@ pccl_status_t pccl_ring_reduce_scatter_local(void* msg, const void* recv_base,
     const hipError_t e = pccl::launch_accumulate(
         reinterpret_cast<char*>(msg) + (size_t)c * chunk_bytes,
         reinterpret_cast<const char*>(recv_base) + (size_t)s * recv_stride_bytes, chunk_count,
-        io_dt == PCCL_BF16, st);
+        io_dt, st);
     if (e != hipSuccess) return e == hipErrorInvalidValue ? PCCL_ERR_INVALID : PCCL_ERR_HIP;
   }
   return PCCL_OK;
@@ -415,6 +435,7 @@ pccl_status_t pccl_halving_reduce_scatter_local(void* msg, const void* recv, int
                                                 pccl_op_t op, pccl_stream_t stream) {
   if (msg == nullptr || recv == nullptr) return PCCL_ERR_NULL;
   if (pccl_status_t s = check_common(io_dt, io_dt, op)) return s;
+  if (op != PCCL_SUM) return PCCL_ERR_UNSUPPORTED;
   if (nranks < 1 || (nranks & (nranks - 1)) != 0 || rank < 0 || rank >= nranks)
     return PCCL_ERR_INVALID;
   const size_t es = esize(io_dt);
@@ -432,7 +453,7 @@ pccl_status_t pccl_halving_reduce_scatter_local(void* msg, const void* recv, int
     const hipError_t e = pccl::launch_accumulate(
         reinterpret_cast<char*>(msg) + lo * chunk_bytes,
         reinterpret_cast<const char*>(recv) + recv_off * chunk_bytes, len * chunk_count,
-        io_dt == PCCL_BF16, st);
+        io_dt, st);
     if (e != hipSuccess) return e == hipErrorInvalidValue ? PCCL_ERR_INVALID : PCCL_ERR_HIP;
     recv_off += len;
   }
@@ -444,7 +465,7 @@ const char* pccl_status_string(pccl_status_t status) {
     case PCCL_OK: return "PCCL_OK";
     case PCCL_ERR_NULL: return "PCCL_ERR_NULL: a required pointer is NULL";
     case PCCL_ERR_INVALID: return "PCCL_ERR_INVALID: a count, stride, index or size is out of range";
-    case PCCL_ERR_UNSUPPORTED: return "PCCL_ERR_UNSUPPORTED: unknown dtype or reduction op";
+    case PCCL_ERR_UNSUPPORTED: return "PCCL_ERR_UNSUPPORTED: unknown dtype, dtype pair or reduction op";
     case PCCL_ERR_OVERLAP: return "PCCL_ERR_OVERLAP: an output range overlaps an input range";
     case PCCL_ERR_HIP: return "PCCL_ERR_HIP: the HIP runtime refused a kernel launch";
   }

@@ -32,14 +32,14 @@ __device__ __forceinline__ const char* src_ptr(const ReduceProblem& p, int n, in
   return p.base + (size_t)n * p.stride_n + (size_t)g * p.stride_g;
 }
 
-// W packed words -> fp32 values (2 per word for bf16, 1 per word for fp32)
-template <bool IN_BF16, int W>
+// W packed words -> fp32 values (2 per word for bf16 / fp16, 1 per word for fp32)
+template <int IN, int W>
 __device__ __forceinline__ void unpack(const uint32_t* w, float* f) {
 #pragma unroll
   for (int k = 0; k < W; ++k) {
-    if (IN_BF16) {
-      f[2 * k] = bf16_lo(w[k]);
-      f[2 * k + 1] = bf16_hi(w[k]);
+    if (narrow(IN)) {
+      f[2 * k] = lo16<IN>(w[k]);
+      f[2 * k + 1] = hi16<IN>(w[k]);
     } else {
       f[k] = __uint_as_float(w[k]);
     }
@@ -66,15 +66,15 @@ __device__ __forceinline__ void ld_batch(const char* const* sp, uint32_t lane_of
 }
 
 // VE consecutive results, starting at element `e`, converted to the output dtype
-template <bool OUT_BF16, int VE, bool ALIGNED>
+template <int OUT, int VE, bool ALIGNED>
 __device__ __forceinline__ void store_vals(char* dst, size_t e, const float* a) {
-  if constexpr (OUT_BF16) {
+  if constexpr (narrow(OUT)) {
     if constexpr (VE == 1) {
-      st_elem<true>(dst, e, a[0]);
+      st_elem<OUT>(dst, e, a[0]);
     } else {
       uint32_t w[VE / 2];
 #pragma unroll
-      for (int k = 0; k < VE / 2; ++k) w[k] = pack_bf16(a[2 * k], a[2 * k + 1]);
+      for (int k = 0; k < VE / 2; ++k) w[k] = pack16<OUT>(a[2 * k], a[2 * k + 1]);
       st_words<VE / 2, 2, ALIGNED>(dst, e * 2, w);
     }
   } else {
@@ -92,18 +92,19 @@ __device__ __forceinline__ void store_vals(char* dst, size_t e, const float* a) 
 
 // ------------------------------------------------------------------------------------------
 // element-wise path: ragged tails, and the reference semantics in the simplest form
-template <bool IN_BF16, bool OUT_BF16>
+template <int IN, int OUT>
 __device__ void reduce_elem(const ReduceProblem& p, size_t e) {
   float acc = 0.0f;
   for (int n = 0; n < p.nodes; ++n) {
-    float t = ld_elem<IN_BF16>(src_ptr<>(p, n, 0), e);
-    for (int g = 1; g < p.gpus; ++g) t = t + ld_elem<IN_BF16>(src_ptr<>(p, n, g), e);
-    if (IN_BF16 && p.round_partial) t = round_through_bf16(t);
+    float t = ld_elem<IN>(src_ptr<>(p, n, 0), e);
+    for (int g = 1; g < p.gpus; ++g) t = t + ld_elem<IN>(src_ptr<>(p, n, g), e);
+    if (narrow(IN) && p.round_partial) t = round_through<IN>(t);
     if (p.partial != nullptr)
-      st_elem<IN_BF16>(reinterpret_cast<char*>(p.partial), (size_t)n * p.count + e, t);
+      st_elem<IN>(reinterpret_cast<char*>(p.partial), (size_t)n * p.count + e, t);
     acc = (n == 0) ? t : acc + t;
   }
-  st_elem<OUT_BF16>(reinterpret_cast<char*>(p.dst), e, acc);
+  if (p.divisor != 0.0f) acc = acc / p.divisor;
+  st_elem<OUT>(reinterpret_cast<char*>(p.dst), e, acc);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -113,10 +114,10 @@ __device__ void reduce_elem(const ReduceProblem& p, size_t e) {
 // M == 0: any number of sources, walked in batches of four.
 // W is picked so that a lane keeps about 32 bytes of loads in flight (M * 4W): measured on
 // MI355X, more bytes per lane at full occupancy lowers the achieved HBM bandwidth.
-template <bool IN_BF16, bool OUT_BF16, int M, int W, bool FAST>
+template <int IN, int OUT, int M, int W, bool FAST>
 __device__ __forceinline__ void reduce_tile(const ReduceProblem& p, size_t tile) {
-  constexpr int VE = IN_BF16 ? 2 * W : W;  // elements per vector
-  constexpr int ES = IN_BF16 ? 2 : 4;
+  constexpr int VE = narrow(IN) ? 2 * W : W;  // elements per vector
+  constexpr int ES = narrow(IN) ? 2 : 4;
   constexpr int VB = 4 * W;  // bytes per vector
   const size_t nvec = p.count / VE;
   const size_t ntiles_vec = (nvec + kBlock - 1) / kBlock;
@@ -135,11 +136,11 @@ __device__ __forceinline__ void reduce_tile(const ReduceProblem& p, size_t tile)
         for (int g = 0; g < M; ++g) sp[g] = src_ptr<FAST>(p, n, g) + tile_off;
         uint32_t raw[M > 0 ? M : 1][W];
         ld_batch<(M > 0 ? M : 1), W, ES, FAST>(sp, lane_off, raw);
-        unpack<IN_BF16, W>(raw[0], t);
+        unpack<IN, W>(raw[0], t);
 #pragma unroll
         for (int g = 1; g < M; ++g) {
           float x[VE];
-          unpack<IN_BF16, W>(raw[g], x);
+          unpack<IN, W>(raw[g], x);
 #pragma unroll
           for (int k = 0; k < VE; ++k) t[k] = t[k] + x[k];
         }
@@ -147,7 +148,7 @@ __device__ __forceinline__ void reduce_tile(const ReduceProblem& p, size_t tile)
         {
           uint32_t r[W];
           ld_words<W, ES, FAST>(src_ptr<FAST>(p, n, 0) + tile_off, lane_off, r);
-          unpack<IN_BF16, W>(r, t);
+          unpack<IN, W>(r, t);
         }
         int g = 1;
         for (; g + 4 <= p.gpus; g += 4) {
@@ -159,7 +160,7 @@ __device__ __forceinline__ void reduce_tile(const ReduceProblem& p, size_t tile)
 #pragma unroll
           for (int j = 0; j < 4; ++j) {
             float x[VE];
-            unpack<IN_BF16, W>(raw[j], x);
+            unpack<IN, W>(raw[j], x);
 #pragma unroll
             for (int k = 0; k < VE; ++k) t[k] = t[k] + x[k];
           }
@@ -168,7 +169,7 @@ __device__ __forceinline__ void reduce_tile(const ReduceProblem& p, size_t tile)
           uint32_t r[W];
           ld_words<W, ES, FAST>(src_ptr<FAST>(p, n, g) + tile_off, lane_off, r);
           float x[VE];
-          unpack<IN_BF16, W>(r, x);
+          unpack<IN, W>(r, x);
 #pragma unroll
           for (int k = 0; k < VE; ++k) t[k] = t[k] + x[k];
         }
@@ -177,13 +178,13 @@ __device__ __forceinline__ void reduce_tile(const ReduceProblem& p, size_t tile)
       // node partial: round through the message dtype, optionally keep it
       const bool keep = p.partial != nullptr;
       char* prow = reinterpret_cast<char*>(p.partial) + (size_t)n * p.count * ES + tile_off;
-      if (IN_BF16) {
+      if (narrow(IN)) {
         if (p.round_partial || keep) {
           uint32_t w[W];
 #pragma unroll
-          for (int k = 0; k < W; ++k) w[k] = pack_bf16(t[2 * k], t[2 * k + 1]);
+          for (int k = 0; k < W; ++k) w[k] = pack16<IN>(t[2 * k], t[2 * k + 1]);
           if (keep) st_words<W, ES, FAST>(prow, lane_off, w);
-          if (p.round_partial) unpack<true, W>(w, t);
+          if (p.round_partial) unpack<IN, W>(w, t);
         }
       } else if (keep) {
         uint32_t w[W];
@@ -195,13 +196,17 @@ __device__ __forceinline__ void reduce_tile(const ReduceProblem& p, size_t tile)
 #pragma unroll
       for (int k = 0; k < VE; ++k) acc[k] = (n == 0) ? t[k] : acc[k] + t[k];
     }
-    store_vals<OUT_BF16, VE, FAST>(reinterpret_cast<char*>(p.dst), v * VE, acc);
+    if (p.divisor != 0.0f) {  // op = average: one IEEE division of the finished sum
+#pragma unroll
+      for (int k = 0; k < VE; ++k) acc[k] = acc[k] / p.divisor;
+    }
+    store_vals<OUT, VE, FAST>(reinterpret_cast<char*>(p.dst), v * VE, acc);
   }
 
   // ragged tail (count not a multiple of the vector width): fewer than VE <= 8 elements
   if (tile == last_tile) {
     const size_t e = nvec * VE + threadIdx.x;
-    if (e < p.count) reduce_elem<IN_BF16, OUT_BF16>(p, e);
+    if (e < p.count) reduce_elem<IN, OUT>(p, e);
   }
 }
 
@@ -211,18 +216,18 @@ inline int pick_m(int gpus) {
   return (gpus == 1 || gpus == 2 || gpus == 4 || gpus == 8 || gpus == 16) ? gpus : 0;
 }
 
-template <bool IN_BF16, bool OUT_BF16, int M, bool FAST>
+template <int IN, int OUT, int M, bool FAST>
 __global__ __launch_bounds__(kBlock) void k_reduce(ReduceProblem p) {
   // grid.y = rows: the same reduction over `rows` strided rows of every source
   const size_t row = blockIdx.y;
   p.base += row * p.row_stride_src;
   p.src_offset += row * p.row_stride_src;
   p.dst = reinterpret_cast<char*>(p.dst) + row * p.row_stride_dst;
-  reduce_tile<IN_BF16, OUT_BF16, M, words_for(M), FAST>(p, blockIdx.x);
+  reduce_tile<IN, OUT, M, words_for(M), FAST>(p, blockIdx.x);
 }
 
-inline size_t tiles_for(size_t count, int m, bool in_bf16) {
-  const size_t ve = (size_t)words_for(m) * (in_bf16 ? 2 : 1);
+inline size_t tiles_for(size_t count, int m, bool in_narrow) {
+  const size_t ve = (size_t)words_for(m) * (in_narrow ? 2 : 1);
   const size_t nvec = count / ve;
   const size_t t = (nvec + kBlock - 1) / kBlock;
   return t == 0 ? 1 : t;  // a lone ragged tail still needs one block
@@ -231,42 +236,42 @@ inline size_t tiles_for(size_t count, int m, bool in_bf16) {
 inline bool is16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
 // strided sources with every base, stride, row and output 16-byte aligned
-inline bool fast_eligible(const ReduceProblem& p, bool in_bf16) {
-  const size_t es = in_bf16 ? 2 : 4;
+inline bool fast_eligible(const ReduceProblem& p, bool in_narrow) {
+  const size_t es = in_narrow ? 2 : 4;
   return p.ptrs == nullptr && is16(p.base) && is16(p.dst) && p.stride_n % 16 == 0 &&
          p.stride_g % 16 == 0 && p.row_stride_src % 16 == 0 && p.row_stride_dst % 16 == 0 &&
          (p.partial == nullptr || (is16(p.partial) && (p.count * es) % 16 == 0));
 }
 
-template <bool IN_BF16, bool OUT_BF16, int M>
+template <int IN, int OUT, int M>
 hipError_t launch_m(const ReduceProblem& p, hipStream_t st) {
-  const size_t tiles = tiles_for(p.count, M, IN_BF16);
+  const size_t tiles = tiles_for(p.count, M, narrow(IN));
   if (tiles > 0x7FFFFFFFull || p.rows < 1 || p.rows > 65535) return hipErrorInvalidValue;
   if (p.rows > 1 && p.partial != nullptr) return hipErrorInvalidValue;
   const dim3 grid((unsigned)tiles, (unsigned)p.rows);
-  if (fast_eligible(p, IN_BF16))
-    hipLaunchKernelGGL((k_reduce<IN_BF16, OUT_BF16, M, true>), grid, dim3(kBlock), 0, st, p);
+  if (fast_eligible(p, narrow(IN)))
+    hipLaunchKernelGGL((k_reduce<IN, OUT, M, true>), grid, dim3(kBlock), 0, st, p);
   else
-    hipLaunchKernelGGL((k_reduce<IN_BF16, OUT_BF16, M, false>), grid, dim3(kBlock), 0, st, p);
+    hipLaunchKernelGGL((k_reduce<IN, OUT, M, false>), grid, dim3(kBlock), 0, st, p);
   return hipGetLastError();
 }
 
-template <bool IN_BF16, bool OUT_BF16>
+template <int IN, int OUT>
 hipError_t launch_io(const ReduceProblem& p, hipStream_t st) {
   switch (pick_m(p.gpus)) {
-    case 1: return launch_m<IN_BF16, OUT_BF16, 1>(p, st);
-    case 2: return launch_m<IN_BF16, OUT_BF16, 2>(p, st);
-    case 4: return launch_m<IN_BF16, OUT_BF16, 4>(p, st);
-    case 8: return launch_m<IN_BF16, OUT_BF16, 8>(p, st);
-    case 16: return launch_m<IN_BF16, OUT_BF16, 16>(p, st);
-    default: return launch_m<IN_BF16, OUT_BF16, 0>(p, st);
+    case 1: return launch_m<IN, OUT, 1>(p, st);
+    case 2: return launch_m<IN, OUT, 2>(p, st);
+    case 4: return launch_m<IN, OUT, 4>(p, st);
+    case 8: return launch_m<IN, OUT, 8>(p, st);
+    case 16: return launch_m<IN, OUT, 16>(p, st);
+    default: return launch_m<IN, OUT, 0>(p, st);
   }
 }
 
 // ------------------------------------------------------------------------------------------
 // LDS-staged two-level reduction for many small chunks.
 //   block  = 16 wavefronts, owns E = 64 * EPL consecutive elements (EPL = elements in one
-//            32-bit word: 1 for fp32, 2 for bf16) of every source;
+//            32-bit word: 1 for fp32, 2 for bf16 / fp16) of every source;
 //   tile   = TN = 16 * NPT consecutive nodes; wave w sums the M sources of nodes
 //            w*NPT .. w*NPT+NPT-1 of the tile (NPT*M independent loads in flight per lane)
 //            and parks the rounded node partials in LDS as fp32;
@@ -285,18 +290,18 @@ constexpr int kLdsWaves = kLdsBlock / 64;
 constexpr int kLdsBatch = 8;  // sources per batch when the per-node count is not a template constant
 
 // nodes per wave and tile: about 32 loads in flight per lane, parking area <= 2 x 32 KB
-constexpr int lds_npt(int m, bool in_bf16) {
+constexpr int lds_npt(int m, bool in_narrow) {
   if (m <= 0) return 1;
   int npt = 32 / m;
-  const int cap = in_bf16 ? 4 : 8;
+  const int cap = in_narrow ? 4 : 8;
   if (npt > cap) npt = cap;
   return npt < 1 ? 1 : npt;
 }
 
 // one 32-bit word of a source as EPL fp32 values; CHECKED adds bounds and alignment handling
-template <bool IN_BF16, int EPL, bool CHECKED>
+template <int IN, int EPL, bool CHECKED>
 __device__ __forceinline__ void ld_word(const char* sp, size_t le, size_t count, float* x) {
-  if (!IN_BF16) {
+  if (!narrow(IN)) {
     if (CHECKED)
       x[0] = (le < count) ? ld_stream<float>(sp + 4 * le) : 0.0f;
     else
@@ -304,11 +309,11 @@ __device__ __forceinline__ void ld_word(const char* sp, size_t le, size_t count,
   } else {
     if (!CHECKED || (le + 1 < count && aligned_to(sp, 4))) {
       const uint32_t w = ld_stream<uint32_t>(sp + 2 * le);
-      x[0] = bf16_lo(w);
-      x[1] = bf16_hi(w);
+      x[0] = lo16<IN>(w);
+      x[1] = hi16<IN>(w);
     } else {
-      x[0] = (le < count) ? ld_elem<true>(sp, le) : 0.0f;
-      x[1] = (le + 1 < count) ? ld_elem<true>(sp, le + 1) : 0.0f;
+      x[0] = (le < count) ? ld_elem<IN>(sp, le) : 0.0f;
+      x[1] = (le + 1 < count) ? ld_elem<IN>(sp, le + 1) : 0.0f;
     }
   }
 }
@@ -346,11 +351,11 @@ __device__ __forceinline__ float ordered_sum(const float* parked, int tn, bool f
   return acc;
 }
 
-template <bool IN_BF16, bool OUT_BF16, int M>
+template <int IN, int OUT, int M>
 __global__ __launch_bounds__(kLdsBlock) void k_reduce2l_lds(ReduceProblem p) {
-  constexpr int EPL = IN_BF16 ? 2 : 1;
+  constexpr int EPL = narrow(IN) ? 2 : 1;
   constexpr int E = 64 * EPL;
-  constexpr int NPT = lds_npt(M, IN_BF16);
+  constexpr int NPT = lds_npt(M, narrow(IN));
   constexpr int TN = kLdsWaves * NPT;
   constexpr int MM = M > 0 ? M : kLdsBatch;
   __shared__ float parked[2][TN * E];
@@ -366,7 +371,7 @@ __global__ __launch_bounds__(kLdsBlock) void k_reduce2l_lds(ReduceProblem p) {
 #pragma unroll
     for (int k = 0; k < EPL; ++k) {
       float r = t[k];
-      if (IN_BF16 && p.round_partial) r = round_through_bf16(r);
+      if (narrow(IN) && p.round_partial) r = round_through<IN>(r);
       buf[j * E + lane * EPL + k] = r;
     }
   };
@@ -391,14 +396,14 @@ __global__ __launch_bounds__(kLdsBlock) void k_reduce2l_lds(ReduceProblem p) {
         for (int q = 0; q < NPT; ++q)
 #pragma unroll
           for (int g = 0; g < MM; ++g)
-            ld_word<IN_BF16, EPL, false>(lane_pointer(cur, q * M + g), le, p.count, x[q][g]);
+            ld_word<IN, EPL, false>(lane_pointer(cur, q * M + g), le, p.count, x[q][g]);
       } else {
 #pragma unroll
         for (int q = 0; q < NPT; ++q)
           if (q < nvalid) {
 #pragma unroll
             for (int g = 0; g < MM; ++g)
-              ld_word<IN_BF16, EPL, true>(lane_pointer(cur, q * M + g), le, p.count, x[q][g]);
+              ld_word<IN, EPL, true>(lane_pointer(cur, q * M + g), le, p.count, x[q][g]);
           }
       }
       // ordered sum of the previous tile while this tile's loads are in flight
@@ -432,7 +437,7 @@ __global__ __launch_bounds__(kLdsBlock) void k_reduce2l_lds(ReduceProblem p) {
           float x[kLdsBatch][EPL];
 #pragma unroll
           for (int j = 0; j < kLdsBatch; ++j)
-            if (j < nb) ld_word<IN_BF16, EPL, true>(lane_pointer(a, j), le, p.count, x[j]);
+            if (j < nb) ld_word<IN, EPL, true>(lane_pointer(a, j), le, p.count, x[j]);
 #pragma unroll
           for (int j = 0; j < kLdsBatch; ++j)
             if (j < nb) {
@@ -448,41 +453,42 @@ __global__ __launch_bounds__(kLdsBlock) void k_reduce2l_lds(ReduceProblem p) {
   if (threadIdx.x < E) {
     const int last = ntiles - 1;
     acc = ordered_sum<E>(parked[last & 1], p.nodes - last * TN, last == 0, acc);
+    if (p.divisor != 0.0f) acc = acc / p.divisor;
     if (e0 + threadIdx.x < p.count)
-      st_elem<OUT_BF16>(reinterpret_cast<char*>(p.dst), e0 + threadIdx.x, acc);
+      st_elem<OUT>(reinterpret_cast<char*>(p.dst), e0 + threadIdx.x, acc);
   }
 }
 
-template <bool IN_BF16, bool OUT_BF16, int M>
+template <int IN, int OUT, int M>
 hipError_t launch_lds_m(const ReduceProblem& p, hipStream_t st) {
-  constexpr int E = IN_BF16 ? 128 : 64;
+  constexpr int E = narrow(IN) ? 128 : 64;
   const size_t blocks = (p.count + E - 1) / E;
   if (blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
-  hipLaunchKernelGGL((k_reduce2l_lds<IN_BF16, OUT_BF16, M>), dim3((unsigned)blocks),
+  hipLaunchKernelGGL((k_reduce2l_lds<IN, OUT, M>), dim3((unsigned)blocks),
                      dim3(kLdsBlock), 0, st, p);
   return hipGetLastError();
 }
 
-template <bool IN_BF16, bool OUT_BF16>
+template <int IN, int OUT>
 hipError_t launch_lds_io(const ReduceProblem& p, hipStream_t st) {
   switch (p.gpus) {
-    case 1: return launch_lds_m<IN_BF16, OUT_BF16, 1>(p, st);
-    case 2: return launch_lds_m<IN_BF16, OUT_BF16, 2>(p, st);
-    case 4: return launch_lds_m<IN_BF16, OUT_BF16, 4>(p, st);
-    case 8: return launch_lds_m<IN_BF16, OUT_BF16, 8>(p, st);
-    case 16: return launch_lds_m<IN_BF16, OUT_BF16, 16>(p, st);
-    default: return launch_lds_m<IN_BF16, OUT_BF16, 0>(p, st);
+    case 1: return launch_lds_m<IN, OUT, 1>(p, st);
+    case 2: return launch_lds_m<IN, OUT, 2>(p, st);
+    case 4: return launch_lds_m<IN, OUT, 4>(p, st);
+    case 8: return launch_lds_m<IN, OUT, 8>(p, st);
+    case 16: return launch_lds_m<IN, OUT, 16>(p, st);
+    default: return launch_lds_m<IN, OUT, 0>(p, st);
   }
 }
 
 // ------------------------------------------------------------------------------------------
 // batched two-level reduce-scatter share: a flat tile space over all buckets, one launch
 // per phase.  Each block finds its bucket by bisection in the tile prefix (kernel argument).
-template <bool BF16, int M, int PHASE, bool FAST>
+template <int DT, int M, int PHASE, bool FAST>
 __global__ __launch_bounds__(kBlock) void k_rs_batched(const pccl_bucket_t* __restrict__ buckets,
                                                        BatchTiles tiles, int nbuckets, int nodes,
-                                                       int gpus) {
-  constexpr int ES = BF16 ? 2 : 4;
+                                                       int gpus, float divisor) {
+  constexpr int ES = narrow(DT) ? 2 : 4;
   int lo = 0, hi = nbuckets;
   while (hi - lo > 1) {
     const int mid = (lo + hi) >> 1;
@@ -504,6 +510,7 @@ __global__ __launch_bounds__(kBlock) void k_rs_batched(const pccl_bucket_t* __re
   p.row_stride_src = 0;
   p.row_stride_dst = 0;
   p.rows = 1;
+  p.divisor = PHASE == 2 ? divisor : 0.0f;
   if (PHASE == 1) {  // partial[n][e] = sum over g' of piece_g'[n][e]
     p.dst = b.partial;
     p.base = reinterpret_cast<const char*>(b.intra_base);
@@ -517,26 +524,26 @@ __global__ __launch_bounds__(kBlock) void k_rs_batched(const pccl_bucket_t* __re
     p.count = b.chunk_count;
     p.gpus = nodes;
   }
-  reduce_tile<BF16, BF16, M, words_for(M), FAST>(p, blockIdx.x - tiles.first_tile[lo]);
+  reduce_tile<DT, DT, M, words_for(M), FAST>(p, blockIdx.x - tiles.first_tile[lo]);
 }
 
-template <bool BF16, int M, int PHASE>
+template <int DT, int M, int PHASE>
 hipError_t launch_batched_phase(const pccl_bucket_t* d_buckets, const pccl_bucket_t* h_buckets,
-                                int nbuckets, int nodes, int gpus, hipStream_t st) {
+                                int nbuckets, int nodes, int gpus, float divisor, hipStream_t st) {
   BatchTiles tiles;
   size_t total = 0;
   for (int b = 0; b < nbuckets; ++b) {
     tiles.first_tile[b] = (uint32_t)total;
     const size_t count = PHASE == 1 ? (size_t)nodes * h_buckets[b].chunk_count
                                     : h_buckets[b].chunk_count;
-    if (count != 0) total += tiles_for(count, M, BF16);
+    if (count != 0) total += tiles_for(count, M, narrow(DT));
     if (total > 0x7FFFFFFFull) return hipErrorInvalidValue;
   }
   for (int b = nbuckets; b <= kMaxBuckets; ++b) tiles.first_tile[b] = (uint32_t)total;
   if (total == 0) return hipSuccess;
   // every bucket 16-byte aligned in all its bases, strides and rows -> no run-time checks
   bool fast = true;
-  const size_t es = BF16 ? 2 : 4;
+  const size_t es = narrow(DT) ? 2 : 4;
   for (int b = 0; b < nbuckets; ++b) {
     const pccl_bucket_t& k = h_buckets[b];
     if (k.chunk_count == 0) continue;
@@ -544,59 +551,74 @@ hipError_t launch_batched_phase(const pccl_bucket_t* d_buckets, const pccl_bucke
            k.intra_stride_bytes % 16 == 0 && (k.chunk_count * es) % 16 == 0;
   }
   if (fast)
-    hipLaunchKernelGGL((k_rs_batched<BF16, M, PHASE, true>), dim3((unsigned)total), dim3(kBlock), 0,
-                       st, d_buckets, tiles, nbuckets, nodes, gpus);
+    hipLaunchKernelGGL((k_rs_batched<DT, M, PHASE, true>), dim3((unsigned)total), dim3(kBlock), 0,
+                       st, d_buckets, tiles, nbuckets, nodes, gpus, divisor);
   else
-    hipLaunchKernelGGL((k_rs_batched<BF16, M, PHASE, false>), dim3((unsigned)total), dim3(kBlock), 0,
-                       st, d_buckets, tiles, nbuckets, nodes, gpus);
+    hipLaunchKernelGGL((k_rs_batched<DT, M, PHASE, false>), dim3((unsigned)total), dim3(kBlock), 0,
+                       st, d_buckets, tiles, nbuckets, nodes, gpus, divisor);
   return hipGetLastError();
 }
 
-template <bool BF16, int PHASE>
+template <int DT, int PHASE>
 hipError_t launch_batched_io(const pccl_bucket_t* d, const pccl_bucket_t* h, int nb, int nodes,
-                             int gpus, hipStream_t st) {
+                             int gpus, float divisor, hipStream_t st) {
   const int srcs = PHASE == 1 ? gpus : nodes;
   switch (pick_m(srcs)) {
-    case 1: return launch_batched_phase<BF16, 1, PHASE>(d, h, nb, nodes, gpus, st);
-    case 2: return launch_batched_phase<BF16, 2, PHASE>(d, h, nb, nodes, gpus, st);
-    case 4: return launch_batched_phase<BF16, 4, PHASE>(d, h, nb, nodes, gpus, st);
-    case 8: return launch_batched_phase<BF16, 8, PHASE>(d, h, nb, nodes, gpus, st);
-    case 16: return launch_batched_phase<BF16, 16, PHASE>(d, h, nb, nodes, gpus, st);
-    default: return launch_batched_phase<BF16, 0, PHASE>(d, h, nb, nodes, gpus, st);
+    case 1: return launch_batched_phase<DT, 1, PHASE>(d, h, nb, nodes, gpus, divisor, st);
+    case 2: return launch_batched_phase<DT, 2, PHASE>(d, h, nb, nodes, gpus, divisor, st);
+    case 4: return launch_batched_phase<DT, 4, PHASE>(d, h, nb, nodes, gpus, divisor, st);
+    case 8: return launch_batched_phase<DT, 8, PHASE>(d, h, nb, nodes, gpus, divisor, st);
+    case 16: return launch_batched_phase<DT, 16, PHASE>(d, h, nb, nodes, gpus, divisor, st);
+    default: return launch_batched_phase<DT, 0, PHASE>(d, h, nb, nodes, gpus, divisor, st);
   }
 }
 
 }  // namespace
 
 // ------------------------------------------------------------------------------------------
-hipError_t launch_reduce(const ReduceProblem& p, bool in_bf16, bool out_bf16, hipStream_t st) {
-  if (in_bf16) return out_bf16 ? launch_io<true, true>(p, st) : launch_io<true, false>(p, st);
-  return out_bf16 ? launch_io<false, true>(p, st) : launch_io<false, false>(p, st);
+// The (input, output) dtype pairs the kernels are built for: fp32 with itself, and each 16-bit
+// message type with itself or with fp32 on either side.
+#define PCCL_DISPATCH_IO(FN, in_dt, out_dt, ...)                                   \
+  do {                                                                             \
+    if (in_dt == kF32 && out_dt == kF32) return FN<kF32, kF32>(__VA_ARGS__);       \
+    if (in_dt == kBF16 && out_dt == kBF16) return FN<kBF16, kBF16>(__VA_ARGS__);   \
+    if (in_dt == kBF16 && out_dt == kF32) return FN<kBF16, kF32>(__VA_ARGS__);     \
+    if (in_dt == kF32 && out_dt == kBF16) return FN<kF32, kBF16>(__VA_ARGS__);     \
+    if (in_dt == kF16 && out_dt == kF16) return FN<kF16, kF16>(__VA_ARGS__);       \
+    if (in_dt == kF16 && out_dt == kF32) return FN<kF16, kF32>(__VA_ARGS__);       \
+    if (in_dt == kF32 && out_dt == kF16) return FN<kF32, kF16>(__VA_ARGS__);       \
+    return hipErrorInvalidValue;                                                   \
+  } while (0)
+
+hipError_t launch_reduce(const ReduceProblem& p, int in_dt, int out_dt, hipStream_t st) {
+  PCCL_DISPATCH_IO(launch_io, in_dt, out_dt, p, st);
 }
 
-hipError_t launch_reduce_two_level_lds(const ReduceProblem& p, bool in_bf16, bool out_bf16,
+hipError_t launch_reduce_two_level_lds(const ReduceProblem& p, int in_dt, int out_dt,
                                        hipStream_t st) {
-  if (in_bf16)
-    return out_bf16 ? launch_lds_io<true, true>(p, st) : launch_lds_io<true, false>(p, st);
-  return out_bf16 ? launch_lds_io<false, true>(p, st) : launch_lds_io<false, false>(p, st);
+  PCCL_DISPATCH_IO(launch_lds_io, in_dt, out_dt, p, st);
 }
 
-bool prefer_lds_two_level(const ReduceProblem& p, bool in_bf16) {
+bool prefer_lds_two_level(const ReduceProblem& p, int in_dt) {
   // The streaming kernel has count/VE threads, each walking all sources one after another.
   // Below about two wavefronts per SIMD of the chip that leaves HBM idle; the LDS kernel
   // spreads the nodes over 16 wavefronts per element slice instead.
-  const size_t ve = in_bf16 ? 8 : 4;
+  const size_t ve = narrow(in_dt) ? 8 : 4;
   const size_t stream_threads = p.count / ve;
   return p.nodes * p.gpus >= 16 && stream_threads < (size_t)256 * 4 * 2 * 64;
 }
 
 hipError_t launch_rs_batched(const pccl_bucket_t* d_buckets, const pccl_bucket_t* h_buckets,
-                             int nbuckets, int nodes, int gpus, bool bf16, hipStream_t st) {
-  hipError_t e = bf16 ? launch_batched_io<true, 1>(d_buckets, h_buckets, nbuckets, nodes, gpus, st)
-                      : launch_batched_io<false, 1>(d_buckets, h_buckets, nbuckets, nodes, gpus, st);
+                             int nbuckets, int nodes, int gpus, int dt, float divisor,
+                             hipStream_t st) {
+  hipError_t e = hipErrorInvalidValue;
+  if (dt == kF32) e = launch_batched_io<kF32, 1>(d_buckets, h_buckets, nbuckets, nodes, gpus, 0.0f, st);
+  if (dt == kBF16) e = launch_batched_io<kBF16, 1>(d_buckets, h_buckets, nbuckets, nodes, gpus, 0.0f, st);
+  if (dt == kF16) e = launch_batched_io<kF16, 1>(d_buckets, h_buckets, nbuckets, nodes, gpus, 0.0f, st);
   if (e != hipSuccess) return e;
-  return bf16 ? launch_batched_io<true, 2>(d_buckets, h_buckets, nbuckets, nodes, gpus, st)
-              : launch_batched_io<false, 2>(d_buckets, h_buckets, nbuckets, nodes, gpus, st);
+  if (dt == kF32) return launch_batched_io<kF32, 2>(d_buckets, h_buckets, nbuckets, nodes, gpus, divisor, st);
+  if (dt == kBF16) return launch_batched_io<kBF16, 2>(d_buckets, h_buckets, nbuckets, nodes, gpus, divisor, st);
+  return launch_batched_io<kF16, 2>(d_buckets, h_buckets, nbuckets, nodes, gpus, divisor, st);
 }
 
 }  // namespace pccl

@@ -15,11 +15,11 @@ namespace pccl {
 
 namespace {
 
-template <bool BF16, bool FAST>
+template <int DT, bool FAST>
 __global__ __launch_bounds__(kBlock) void k_accumulate(char* acc, const char* recv, size_t count) {
   constexpr int W = 4;
-  constexpr int VE = BF16 ? 2 * W : W;
-  constexpr int ES = BF16 ? 2 : 4;
+  constexpr int VE = narrow(DT) ? 2 * W : W;
+  constexpr int ES = narrow(DT) ? 2 : 4;
   const size_t nvec = count / VE;
   const size_t v = (size_t)blockIdx.x * kBlock + threadIdx.x;
   if (v < nvec) {
@@ -29,8 +29,8 @@ __global__ __launch_bounds__(kBlock) void k_accumulate(char* acc, const char* re
     ld_words<W, ES, FAST>(recv, off, r);
 #pragma unroll
     for (int k = 0; k < W; ++k) {
-      if (BF16)
-        o[k] = pack_bf16(bf16_lo(a[k]) + bf16_lo(r[k]), bf16_hi(a[k]) + bf16_hi(r[k]));
+      if (narrow(DT))
+        o[k] = pack16<DT>(lo16<DT>(a[k]) + lo16<DT>(r[k]), hi16<DT>(a[k]) + hi16<DT>(r[k]));
       else
         o[k] = __float_as_uint(__uint_as_float(a[k]) + __uint_as_float(r[k]));
     }
@@ -39,35 +39,38 @@ __global__ __launch_bounds__(kBlock) void k_accumulate(char* acc, const char* re
   // ragged tail: fewer than VE <= 8 elements, taken by the last block
   if (blockIdx.x == gridDim.x - 1) {
     const size_t e = nvec * VE + threadIdx.x;
-    if (e < count) st_elem<BF16>(acc, e, ld_elem<BF16>(acc, e) + ld_elem<BF16>(recv, e));
+    if (e < count) st_elem<DT>(acc, e, ld_elem<DT>(acc, e) + ld_elem<DT>(recv, e));
   }
 }
 
 inline bool is16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
-template <bool BF16>
+template <int DT>
 hipError_t launch_acc(char* acc, const char* recv, size_t count, hipStream_t st) {
-  constexpr size_t VE = BF16 ? 8 : 4;
+  constexpr size_t VE = narrow(DT) ? 8 : 4;
   const size_t nvec = count / VE;
   size_t blocks = (nvec + kBlock - 1) / kBlock;
   if (blocks == 0) blocks = 1;  // a lone ragged tail still needs one block
   if (blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
   if (is16(acc) && is16(recv))
-    hipLaunchKernelGGL((k_accumulate<BF16, true>), dim3((unsigned)blocks), dim3(kBlock), 0, st, acc,
+    hipLaunchKernelGGL((k_accumulate<DT, true>), dim3((unsigned)blocks), dim3(kBlock), 0, st, acc,
                        recv, count);
   else
-    hipLaunchKernelGGL((k_accumulate<BF16, false>), dim3((unsigned)blocks), dim3(kBlock), 0, st, acc,
+    hipLaunchKernelGGL((k_accumulate<DT, false>), dim3((unsigned)blocks), dim3(kBlock), 0, st, acc,
                        recv, count);
   return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t launch_accumulate(void* acc, const void* recv, size_t count, bool bf16, hipStream_t st) {
+hipError_t launch_accumulate(void* acc, const void* recv, size_t count, int dt, hipStream_t st) {
   if (count == 0) return hipSuccess;
   char* a = reinterpret_cast<char*>(acc);
   const char* r = reinterpret_cast<const char*>(recv);
-  return bf16 ? launch_acc<true>(a, r, count, st) : launch_acc<false>(a, r, count, st);
+  if (dt == kF32) return launch_acc<kF32>(a, r, count, st);
+  if (dt == kBF16) return launch_acc<kBF16>(a, r, count, st);
+  if (dt == kF16) return launch_acc<kF16>(a, r, count, st);
+  return hipErrorInvalidValue;
 }
 
 }  // namespace pccl

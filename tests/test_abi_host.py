@@ -13,6 +13,16 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 A = 1 << 20  # a fake, 16-byte aligned "device address"; never dereferenced on these paths
 
 
+@pytest.fixture(autouse=True)
+def _only_without_a_gpu():
+    """Every call below must be turned away before any launch.  Should an expectation ever be
+    wrong, the call would launch on a made-up address: harmless where no GPU exists (the launch
+    fails), not on a GPU machine -- so there these checks do not run."""
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("host argument checks run on machines without a GPU")
+
+
 def _header_symbols():
     text = open(os.path.join(ROOT, "include", "pccl_local.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
@@ -32,7 +42,8 @@ def test_header_and_binding_constants_agree():
     text = open(os.path.join(ROOT, "include", "pccl_local.h")).read()
     assert int(re.search(r"#define PCCL_MAX_BUCKETS (\d+)", text).group(1)) == pccl.PCCL_MAX_BUCKETS
     for name in ("PCCL_OK", "PCCL_ERR_NULL", "PCCL_ERR_INVALID", "PCCL_ERR_UNSUPPORTED",
-                 "PCCL_ERR_OVERLAP", "PCCL_ERR_HIP", "PCCL_F32", "PCCL_BF16", "PCCL_SUM"):
+                 "PCCL_ERR_OVERLAP", "PCCL_ERR_HIP", "PCCL_F32", "PCCL_BF16", "PCCL_F16", "PCCL_SUM",
+                 "PCCL_AVG"):
         m = re.search(r"\b%s = (\d+)" % name, text)
         assert m and int(m.group(1)) == getattr(pccl, name), name
     assert ctypes.sizeof(pccl.pccl_bucket_t) == 40
@@ -56,9 +67,12 @@ def test_local_reduce_rejects_bad_arguments():
     assert call(src=None) == pccl.PCCL_ERR_NULL
     assert call(nsrc=0) == pccl.PCCL_ERR_INVALID
     assert call(nsrc=-3) == pccl.PCCL_ERR_INVALID
-    assert call(i=2) == pccl.PCCL_ERR_UNSUPPORTED
+    assert call(i=3) == pccl.PCCL_ERR_UNSUPPORTED
     assert call(o=7) == pccl.PCCL_ERR_UNSUPPORTED
-    assert call(op=1) == pccl.PCCL_ERR_UNSUPPORTED
+    assert call(i=1, o=2) == pccl.PCCL_ERR_UNSUPPORTED         # bf16 in, fp16 out: no such pair
+    assert call(i=2, o=1) == pccl.PCCL_ERR_UNSUPPORTED
+    assert call(op=2) == pccl.PCCL_ERR_UNSUPPORTED
+    assert call(op=1, nsrc=(1 << 24) + 1, stride=1 << 12) == pccl.PCCL_ERR_INVALID  # average: count not exact in fp32
     assert call(stride=4092) == pccl.PCCL_ERR_INVALID          # sources would overlap
     assert call(stride=4098, i=0) == pccl.PCCL_ERR_INVALID     # not a multiple of the element size
     assert call(count=(1 << 63)) == pccl.PCCL_ERR_INVALID      # byte size overflows
@@ -175,6 +189,7 @@ def test_accumulate_rejects_bad_arguments():
     assert f(A, None, 8, 0, 0, None) == pccl.PCCL_ERR_NULL
     assert f(A, 2 * A, 8, 5, 0, None) == pccl.PCCL_ERR_UNSUPPORTED
     assert f(A, 2 * A, 8, 0, 3, None) == pccl.PCCL_ERR_UNSUPPORTED
+    assert f(A, 2 * A, 8, 0, 1, None) == pccl.PCCL_ERR_UNSUPPORTED         # average is not a step op
     assert f(A, 2 * A, 1 << 63, 0, 0, None) == pccl.PCCL_ERR_INVALID       # byte size overflows
     assert f(A + 2, 2 * A, 8, 0, 0, None) == pccl.PCCL_ERR_INVALID         # fp32 not 4-byte aligned
     assert f(A, 2 * A + 1, 8, 1, 0, None) == pccl.PCCL_ERR_INVALID         # bf16 not 2-byte aligned
@@ -198,6 +213,7 @@ def test_ring_local_rejects_bad_arguments():
     assert call(r=8) == pccl.PCCL_ERR_INVALID
     assert call(dt=9) == pccl.PCCL_ERR_UNSUPPORTED
     assert call(op=2) == pccl.PCCL_ERR_UNSUPPORTED
+    assert call(op=1) == pccl.PCCL_ERR_UNSUPPORTED             # a step only adds
     assert call(stride=4092) == pccl.PCCL_ERR_INVALID          # received chunks would overlap
     assert call(stride=4098) == pccl.PCCL_ERR_INVALID          # not a multiple of the element size
     assert call(c=1 << 62) == pccl.PCCL_ERR_INVALID
@@ -223,7 +239,8 @@ def test_halving_local_rejects_bad_arguments():
         assert call(p=p, r=0) == pccl.PCCL_ERR_INVALID         # recursive halving: powers of two only
     assert call(r=8) == pccl.PCCL_ERR_INVALID
     assert call(r=-1) == pccl.PCCL_ERR_INVALID
-    assert call(dt=2) == pccl.PCCL_ERR_UNSUPPORTED
+    assert call(dt=3) == pccl.PCCL_ERR_UNSUPPORTED
+    assert call(op=1) == pccl.PCCL_ERR_UNSUPPORTED             # a step only adds
     assert call(c=1 << 62) == pccl.PCCL_ERR_INVALID
     assert call(msg=A + 1) == pccl.PCCL_ERR_INVALID
     assert call(recv=A + 2048) == pccl.PCCL_ERR_OVERLAP
@@ -253,7 +270,7 @@ def test_unpacked_reduce_scatter_rejects_bad_arguments():
     assert call(stride=8188) == pccl.PCCL_ERR_INVALID          # messages would overlap
     assert call(c=1 << 61) == pccl.PCCL_ERR_INVALID
     assert call(dt=4) == pccl.PCCL_ERR_UNSUPPORTED
-    assert call(op=1) == pccl.PCCL_ERR_UNSUPPORTED
+    assert call(op=2) == pccl.PCCL_ERR_UNSUPPORTED
     assert call(partial=8 * A + 100 * 4) == pccl.PCCL_ERR_OVERLAP   # partial inside message 0
     assert call(shard=8 * A + 16380) == pccl.PCCL_ERR_OVERLAP       # shard reaches the last message word
     assert call(shard=2 * A + 4092) == pccl.PCCL_ERR_OVERLAP        # shard reaches into the partial
