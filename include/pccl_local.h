@@ -229,6 +229,39 @@ pccl_status_t pccl_halving_reduce_scatter_local(void* msg, const void* recv, int
                                                 size_t chunk_count, pccl_dtype_t io_dt,
                                                 pccl_op_t op, pccl_stream_t stream);
 
+/* ---- closed-form cost model (host arithmetic only, no GPU work) -----------------------------
+ * The paper's two cost equations (Section II-B): for p processes and an m-byte buffer, with
+ * alpha the start-up latency per message and beta the inverse point-to-point bandwidth,
+ *     ring:                         T = alpha*(p-1)   + beta*((p-1)/p)*m        (Eq. 1)
+ *     recursive doubling / halving: T = alpha*log2(p) + beta*((p-1)/p)*m        (Eq. 2)
+ * They stand in for the learned dispatcher of Section IV-C, whose training set is machine
+ * measurements: with one (alpha, beta) pair fitted per algorithm the cheaper algorithm is a
+ * closed form.  (With a single shared pair Eq. 2 never loses; the cross-over the paper
+ * measures between PCCL_ring and PCCL_rec needs each algorithm's own effective beta.)
+ * Both return seconds; NaN for p < 1 or a negative / non-finite argument; pccl_model_rec
+ * returns +infinity when p is not a power of two. */
+typedef enum { PCCL_ALGO_RING = 0, PCCL_ALGO_REC = 1 } pccl_algo_t;
+typedef struct {
+  double alpha_ring_s, beta_ring_s_per_byte; /* fitted to the ring implementation      */
+  double alpha_rec_s, beta_rec_s_per_byte;   /* fitted to the recursive implementation */
+} pccl_link_model_t;
+double pccl_model_ring(int p, double m_bytes, double alpha_s, double beta_s_per_byte);
+double pccl_model_rec(int p, double m_bytes, double alpha_s, double beta_s_per_byte);
+/* *algo = the cheaper algorithm under `model` (the ring on a tie or when p is not a power of
+ * two); the two modelled times are stored through t_ring_s / t_rec_s when not NULL (HOST
+ * pointers).  Errors: NULL model or algo; arguments the two functions above reject. */
+pccl_status_t pccl_choose_algorithm(int p, double m_bytes, const pccl_link_model_t* model,
+                                    pccl_algo_t* algo, double* t_ring_s, double* t_rec_s);
+/* Modelled time of one two-level collective on an m-byte buffer (Section IV-A): the
+ * inter-node algorithm over `nodes` processes on m/gpus_per_node bytes, the intra-node ring
+ * over gpus_per_node processes on m bytes, and the device-local kernels as
+ * local_bytes / hbm_bytes_per_s (local_bytes = the algorithmic bytes of the transposes and
+ * reductions this library runs for the collective).  NaN on invalid arguments. */
+double pccl_model_two_level(int nodes, int gpus_per_node, double m_bytes, pccl_algo_t inter_algo,
+                            double alpha_inter_s, double beta_inter_s_per_byte,
+                            double alpha_intra_s, double beta_intra_s_per_byte,
+                            double local_bytes, double hbm_bytes_per_s);
+
 /* Static, human-readable name of a status code (never NULL). */
 const char* pccl_status_string(pccl_status_t status);
 

@@ -20,8 +20,16 @@ EXPORTS = (
     "pccl_local_reduce", "pccl_local_reduce_ptrs", "pccl_local_reduce_ptrs_two_level",
     "pccl_hier_pack", "pccl_hier_unpack", "pccl_reduce_scatter_local",
     "pccl_allgather_reassemble", "pccl_reduce_scatter_local_batched", "pccl_accumulate",
-    "pccl_reduce_scatter_local_unpacked", "pccl_ring_reduce_scatter_local", "pccl_halving_reduce_scatter_local", "pccl_status_string",
+    "pccl_reduce_scatter_local_unpacked", "pccl_ring_reduce_scatter_local", "pccl_halving_reduce_scatter_local", "pccl_model_ring", "pccl_model_rec",
+    "pccl_choose_algorithm", "pccl_model_two_level", "pccl_status_string",
 )
+PCCL_ALGO_RING, PCCL_ALGO_REC = 0, 1
+_NO_STATUS = ("pccl_status_string", "pccl_model_ring", "pccl_model_rec", "pccl_model_two_level")
+
+
+class pccl_link_model_t(ctypes.Structure):
+    _fields_ = [("alpha_ring_s", ctypes.c_double), ("beta_ring_s_per_byte", ctypes.c_double),
+                ("alpha_rec_s", ctypes.c_double), ("beta_rec_s_per_byte", ctypes.c_double)]
 
 
 class pccl_bucket_t(ctypes.Structure):
@@ -60,8 +68,16 @@ def lib():
         L.pccl_reduce_scatter_local_unpacked.argtypes = [vp, vp, vp, sz, vp, vp, i, i, i, i, sz, i, i, vp]
         L.pccl_ring_reduce_scatter_local.argtypes = [vp, vp, sz, i, i, sz, i, i, vp]
         L.pccl_halving_reduce_scatter_local.argtypes = [vp, vp, i, i, sz, i, i, vp]
-        for name in EXPORTS[:-1]:
-            getattr(L, name).restype = i
+        d = ctypes.c_double
+        for name in ("pccl_model_ring", "pccl_model_rec"):
+            getattr(L, name).argtypes = [i, d, d, d]
+            getattr(L, name).restype = d
+        L.pccl_choose_algorithm.argtypes = [i, d, vp, vp, vp, vp]
+        L.pccl_model_two_level.argtypes = [i, i, d, i, d, d, d, d, d, d]
+        L.pccl_model_two_level.restype = d
+        for name in EXPORTS:
+            if name not in _NO_STATUS:
+                getattr(L, name).restype = i
         L.pccl_status_string.argtypes = [i]
         L.pccl_status_string.restype = ctypes.c_char_p
         _lib = L
@@ -309,3 +325,12 @@ def pccl_reduce_scatter_local_unpacked(shard, partial, msgs=None, d_msgs=None, d
         None if d_inter is None else _dev(d_inter, "d_inter"), nodes, gpus_per_node, my_node, my_gpu, chunk,
         dtype_code(shard.dtype), _op(average), _stream(stream)), "pccl_reduce_scatter_local_unpacked")
     return shard
+
+
+def pccl_choose_algorithm(p, m_bytes, alpha_ring, beta_ring, alpha_rec, beta_rec):
+    """(PCCL_ALGO_RING or PCCL_ALGO_REC, modelled ring seconds, modelled recursive seconds)."""
+    model = pccl_link_model_t(alpha_ring, beta_ring, alpha_rec, beta_rec)
+    algo, tr, tc = ctypes.c_int(-1), ctypes.c_double(), ctypes.c_double()
+    _check(lib().pccl_choose_algorithm(p, m_bytes, ctypes.byref(model), ctypes.byref(algo), ctypes.byref(tr),
+                                       ctypes.byref(tc)), "pccl_choose_algorithm")
+    return algo.value, tr.value, tc.value

@@ -6,7 +6,8 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpccl_local.so")
-SOURCES = ["pccl_api.hip", "reduce_kernels.hip", "permute_kernels.hip", "step_kernels.hip"]
+SOURCES = ["pccl_api.hip", "reduce_kernels.hip", "permute_kernels.hip", "step_kernels.hip",
+           "cost_model.hip"]
 HEADERS = ["device_utils.h", "kernels.h", os.path.join("..", "..", "include", "pccl_local.h")]
 
 HIPCC_FLAGS = [
