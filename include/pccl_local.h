@@ -34,6 +34,10 @@
  *   Alignment  Any element-aligned pointer is accepted.  Pointers, strides and chunk sizes
  *              that are multiples of 16 bytes take the 128-bit path; others take a slower
  *              element-wise path with identical results.
+ *   Sizes      Counts and byte sizes are size_t; buffers beyond 4 GiB are fine.  The largest
+ *              launches: a reduction of up to 2^31 * 65535 / 256 vector tiles (far beyond
+ *              device memory), a permutation with chunks below 64 GiB; beyond that
+ *              PCCL_ERR_INVALID is returned.
  *   Aliasing   Outputs must not overlap inputs.  Where both ranges are visible to the
  *              host (strided forms) an overlap is rejected with PCCL_ERR_OVERLAP; for
  *              pointer-array forms it is undefined behaviour.

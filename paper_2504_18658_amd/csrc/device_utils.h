@@ -13,6 +13,13 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kBlock = 256;  // threads per block of the streaming kernels (4 wavefronts)
 
+// A grid dimension holds fewer than 2^32 work-items (blocks x threads), so a launch with more
+// blocks than that spreads them over x and z; this is the block's index in the whole launch.
+// Blocks past the last one (the x*z rectangle is rounded up) must return at once.
+__device__ __forceinline__ size_t linear_block_xz() {
+  return (size_t)blockIdx.z * gridDim.x + blockIdx.x;
+}
+
 // ---- message dtypes ----------------------------------------------------------------------
 // Values of pccl_dtype_t, used as template parameters.  A 32-bit word holds two 16-bit
 // elements: element 2k in the low half, 2k+1 in the high half.

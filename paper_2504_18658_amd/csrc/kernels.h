@@ -64,6 +64,12 @@ hipError_t launch_reduce_two_level_lds(const ReduceProblem& p, int in_dt, int ou
 // True when the LDS-staged kernel is the better choice for this shape.
 bool prefer_lds_two_level(const ReduceProblem& p, int in_dt);
 
+// x and z extents for `blocks` thread blocks of `threads` threads each, keeping blocks*threads
+// of the x dimension below 2^32 work-items (kernels index with linear_block_xz()).  False when
+// even 65535 z-slices do not hold them.  PCCL_GRID_X_LIMIT (work-items, for tests) lowers the
+// x limit so that small problems exercise the split.
+bool split_grid_xz(size_t blocks, unsigned threads, unsigned* gx, unsigned* gz);
+
 hipError_t launch_permute(const PermuteProblem& p, hipStream_t st);
 
 // acc[e] = round_io(acc[e] + recv[e]) for e < count, in place (the two ranges are disjoint).

@@ -223,7 +223,7 @@ __global__ __launch_bounds__(kBlock) void k_reduce(ReduceProblem p) {
   p.base += row * p.row_stride_src;
   p.src_offset += row * p.row_stride_src;
   p.dst = reinterpret_cast<char*>(p.dst) + row * p.row_stride_dst;
-  reduce_tile<IN, OUT, M, words_for(M), FAST>(p, blockIdx.x);
+  reduce_tile<IN, OUT, M, words_for(M), FAST>(p, linear_block_xz());
 }
 
 inline size_t tiles_for(size_t count, int m, bool in_narrow) {
@@ -246,9 +246,10 @@ inline bool fast_eligible(const ReduceProblem& p, bool in_narrow) {
 template <int IN, int OUT, int M>
 hipError_t launch_m(const ReduceProblem& p, hipStream_t st) {
   const size_t tiles = tiles_for(p.count, M, narrow(IN));
-  if (tiles > 0x7FFFFFFFull || p.rows < 1 || p.rows > 65535) return hipErrorInvalidValue;
+  unsigned gx, gz;
+  if (p.rows < 1 || p.rows > 65535 || !split_grid_xz(tiles, kBlock, &gx, &gz)) return hipErrorInvalidValue;
   if (p.rows > 1 && p.partial != nullptr) return hipErrorInvalidValue;
-  const dim3 grid((unsigned)tiles, (unsigned)p.rows);
+  const dim3 grid(gx, (unsigned)p.rows, gz);  // tiles past the last one find nothing to do
   if (fast_eligible(p, narrow(IN)))
     hipLaunchKernelGGL((k_reduce<IN, OUT, M, true>), grid, dim3(kBlock), 0, st, p);
   else
@@ -361,7 +362,8 @@ __global__ __launch_bounds__(kLdsBlock) void k_reduce2l_lds(ReduceProblem p) {
   __shared__ float parked[2][TN * E];
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const size_t e0 = (size_t)blockIdx.x * E;
+  const size_t e0 = linear_block_xz() * E;
+  if (e0 >= p.count) return;  // the x*z rectangle is rounded up: whole blocks past the end leave
   const size_t le = e0 + (size_t)lane * EPL;
   const int gpus = M > 0 ? M : p.gpus;
   const bool slice_full = e0 + E <= p.count;  // block-uniform
@@ -463,9 +465,9 @@ template <int IN, int OUT, int M>
 hipError_t launch_lds_m(const ReduceProblem& p, hipStream_t st) {
   constexpr int E = narrow(IN) ? 128 : 64;
   const size_t blocks = (p.count + E - 1) / E;
-  if (blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
-  hipLaunchKernelGGL((k_reduce2l_lds<IN, OUT, M>), dim3((unsigned)blocks),
-                     dim3(kLdsBlock), 0, st, p);
+  unsigned gx, gz;
+  if (!split_grid_xz(blocks, kLdsBlock, &gx, &gz)) return hipErrorInvalidValue;
+  hipLaunchKernelGGL((k_reduce2l_lds<IN, OUT, M>), dim3(gx, 1, gz), dim3(kLdsBlock), 0, st, p);
   return hipGetLastError();
 }
 
@@ -489,10 +491,12 @@ __global__ __launch_bounds__(kBlock) void k_rs_batched(const pccl_bucket_t* __re
                                                        BatchTiles tiles, int nbuckets, int nodes,
                                                        int gpus, float divisor) {
   constexpr int ES = narrow(DT) ? 2 : 4;
+  const size_t block = linear_block_xz();
+  if (block >= tiles.first_tile[nbuckets]) return;  // the x*z rectangle is rounded up
   int lo = 0, hi = nbuckets;
   while (hi - lo > 1) {
     const int mid = (lo + hi) >> 1;
-    if (tiles.first_tile[mid] <= blockIdx.x)
+    if (tiles.first_tile[mid] <= block)
       lo = mid;
     else
       hi = mid;
@@ -524,7 +528,7 @@ __global__ __launch_bounds__(kBlock) void k_rs_batched(const pccl_bucket_t* __re
     p.count = b.chunk_count;
     p.gpus = nodes;
   }
-  reduce_tile<DT, DT, M, words_for(M), FAST>(p, blockIdx.x - tiles.first_tile[lo]);
+  reduce_tile<DT, DT, M, words_for(M), FAST>(p, block - tiles.first_tile[lo]);
 }
 
 template <int DT, int M, int PHASE>
@@ -537,7 +541,7 @@ hipError_t launch_batched_phase(const pccl_bucket_t* d_buckets, const pccl_bucke
     const size_t count = PHASE == 1 ? (size_t)nodes * h_buckets[b].chunk_count
                                     : h_buckets[b].chunk_count;
     if (count != 0) total += tiles_for(count, M, narrow(DT));
-    if (total > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    if (total > 0xFFFFFFFFull) return hipErrorInvalidValue;  // the prefix holds 32-bit tile indices
   }
   for (int b = nbuckets; b <= kMaxBuckets; ++b) tiles.first_tile[b] = (uint32_t)total;
   if (total == 0) return hipSuccess;
@@ -550,12 +554,14 @@ hipError_t launch_batched_phase(const pccl_bucket_t* d_buckets, const pccl_bucke
     fast = fast && is16(k.shard) && is16(k.partial) && is16(k.intra_base) &&
            k.intra_stride_bytes % 16 == 0 && (k.chunk_count * es) % 16 == 0;
   }
+  unsigned gx, gz;
+  if (!split_grid_xz(total, kBlock, &gx, &gz)) return hipErrorInvalidValue;
   if (fast)
-    hipLaunchKernelGGL((k_rs_batched<DT, M, PHASE, true>), dim3((unsigned)total), dim3(kBlock), 0,
-                       st, d_buckets, tiles, nbuckets, nodes, gpus, divisor);
+    hipLaunchKernelGGL((k_rs_batched<DT, M, PHASE, true>), dim3(gx, 1, gz), dim3(kBlock), 0, st,
+                       d_buckets, tiles, nbuckets, nodes, gpus, divisor);
   else
-    hipLaunchKernelGGL((k_rs_batched<DT, M, PHASE, false>), dim3((unsigned)total), dim3(kBlock), 0,
-                       st, d_buckets, tiles, nbuckets, nodes, gpus, divisor);
+    hipLaunchKernelGGL((k_rs_batched<DT, M, PHASE, false>), dim3(gx, 1, gz), dim3(kBlock), 0, st,
+                       d_buckets, tiles, nbuckets, nodes, gpus, divisor);
   return hipGetLastError();
 }
 

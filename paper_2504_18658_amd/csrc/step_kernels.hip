@@ -21,7 +21,8 @@ __global__ __launch_bounds__(kBlock) void k_accumulate(char* acc, const char* re
   constexpr int VE = narrow(DT) ? 2 * W : W;
   constexpr int ES = narrow(DT) ? 2 : 4;
   const size_t nvec = count / VE;
-  const size_t v = (size_t)blockIdx.x * kBlock + threadIdx.x;
+  const size_t block = linear_block_xz();
+  const size_t v = block * kBlock + threadIdx.x;
   if (v < nvec) {
     const size_t off = v * (4 * W);
     uint32_t a[W], r[W], o[W];
@@ -36,8 +37,8 @@ __global__ __launch_bounds__(kBlock) void k_accumulate(char* acc, const char* re
     }
     st_words<W, ES, FAST>(acc, off, o);
   }
-  // ragged tail: fewer than VE <= 8 elements, taken by the last block
-  if (blockIdx.x == gridDim.x - 1) {
+  // ragged tail: fewer than VE <= 8 elements, taken by the last block that holds vectors
+  if (block == (nvec == 0 ? 0 : (nvec - 1) / kBlock)) {
     const size_t e = nvec * VE + threadIdx.x;
     if (e < count) st_elem<DT>(acc, e, ld_elem<DT>(acc, e) + ld_elem<DT>(recv, e));
   }
@@ -51,13 +52,12 @@ hipError_t launch_acc(char* acc, const char* recv, size_t count, hipStream_t st)
   const size_t nvec = count / VE;
   size_t blocks = (nvec + kBlock - 1) / kBlock;
   if (blocks == 0) blocks = 1;  // a lone ragged tail still needs one block
-  if (blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
+  unsigned gx, gz;
+  if (!split_grid_xz(blocks, kBlock, &gx, &gz)) return hipErrorInvalidValue;
   if (is16(acc) && is16(recv))
-    hipLaunchKernelGGL((k_accumulate<DT, true>), dim3((unsigned)blocks), dim3(kBlock), 0, st, acc,
-                       recv, count);
+    hipLaunchKernelGGL((k_accumulate<DT, true>), dim3(gx, 1, gz), dim3(kBlock), 0, st, acc, recv, count);
   else
-    hipLaunchKernelGGL((k_accumulate<DT, false>), dim3((unsigned)blocks), dim3(kBlock), 0, st, acc,
-                       recv, count);
+    hipLaunchKernelGGL((k_accumulate<DT, false>), dim3(gx, 1, gz), dim3(kBlock), 0, st, acc, recv, count);
   return hipGetLastError();
 }
 

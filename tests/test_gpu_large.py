@@ -1,0 +1,226 @@
+"""Buffers beyond 4 GiB: every byte offset the kernels form must be 64-bit.  At these sizes the
+oracle checks sampled windows (it computes them one by one); a property that holds at any size
+-- equality with torch's own element-wise IEEE arithmetic, or chunk-by-chunk byte equality --
+covers every element on the GPU."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2504_18658_amd as pccl
+from util import same_bits, to_np
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda"
+F32, BF16 = torch.float32, torch.bfloat16
+G4 = 1 << 32
+
+
+def _sync():
+    torch.cuda.synchronize()
+
+
+@pytest.fixture(autouse=True)
+def _free_between_tests():
+    yield
+    torch.cuda.empty_cache()
+
+
+def _rand(n, dtype, seed):
+    g = torch.Generator(device=DEV)
+    g.manual_seed(seed)
+    x = torch.empty(n, dtype=dtype, device=DEV)
+    x.uniform_(-1.0, 1.0, generator=g)
+    return x
+
+
+def _windows(n, width=4096):
+    """Head, the elements either side of every 4 GiB byte boundary is covered by the caller's
+    choice of n; here: head, middle, tail."""
+    return [0, n // 2 - width // 2, n - width]
+
+
+def test_local_reduce_fp32_beyond_4gib():
+    n = (1 << 30) + 4099                                   # 4 GiB + 16 KiB of fp32 per source, ragged tail
+    src = _rand(2 * n, F32, 1).view(2, n)
+    dst = torch.empty(n, dtype=F32, device=DEV)
+    pccl.pccl_local_reduce(dst, src)
+    _sync()
+    assert torch.equal(dst.view(torch.int32), (src[0] + src[1]).view(torch.int32))
+    for lo in _windows(n) + [(1 << 30) - 2048]:
+        sl = slice(lo, lo + 4096)
+        assert same_bits(to_np(dst[sl]), oracle.flat_reduce([to_np(src[0][sl]), to_np(src[1][sl])]))
+
+
+def test_local_reduce_bf16_three_sources_beyond_4gib():
+    n = (1 << 31) + 11                                     # 4 GiB of bf16 per source + a ragged tail
+    src = _rand(3 * n, BF16, 2).view(3, n)
+    dst = torch.empty(n, dtype=BF16, device=DEV)
+    pccl.pccl_local_reduce(dst, src)
+    _sync()
+    step = 1 << 28
+    for lo in range(0, n, step):                           # torch's fp32 adds and bf16 cast, piecewise
+        sl = slice(lo, min(n, lo + step))
+        ref = ((src[0][sl].float() + src[1][sl].float()) + src[2][sl].float()).to(BF16)
+        assert torch.equal(dst[sl].view(torch.int16), ref.view(torch.int16)), lo
+    for lo in _windows(n) + [(1 << 31) - 2048]:
+        sl = slice(lo, lo + 4096)
+        assert same_bits(to_np(dst[sl]), oracle.flat_reduce([to_np(src[k][sl]) for k in range(3)]))
+
+
+def test_two_level_lds_kernel_beyond_4gib():
+    n = (1 << 30) + 5
+    nodes, gpus = 2, 2
+    src = _rand(nodes * gpus * n, F32, 3).view(nodes * gpus, n)
+    ptrs = pccl.device_pointer_array([src[k] for k in range(nodes * gpus)])
+    dst = torch.empty(n, dtype=F32, device=DEV)
+    os.environ["PCCL_FORCE_TWO_LEVEL_KERNEL"] = "lds"
+    try:
+        pccl.pccl_local_reduce_ptrs_two_level(dst, ptrs, nodes, gpus, n, F32)
+        _sync()
+    finally:
+        os.environ.pop("PCCL_FORCE_TWO_LEVEL_KERNEL", None)
+    assert torch.equal(dst.view(torch.int32), ((src[0] + src[1]) + (src[2] + src[3])).view(torch.int32))
+    for lo in _windows(n) + [(1 << 30) - 2048]:
+        sl = slice(lo, lo + 4096)
+        want = oracle.two_level_reduce([to_np(src[k][sl]) for k in range(4)], nodes, gpus)
+        assert same_bits(to_np(dst[sl]), want)
+
+
+def test_accumulate_bf16_beyond_4gib():
+    n = (1 << 31) + 9
+    acc = _rand(n, BF16, 4)
+    recv = _rand(n, BF16, 5)
+    before = acc.clone()
+    pccl.pccl_accumulate(acc, recv)
+    _sync()
+    step = 1 << 28
+    for lo in range(0, n, step):
+        sl = slice(lo, min(n, lo + step))
+        assert torch.equal(acc[sl].view(torch.int16), (before[sl] + recv[sl]).view(torch.int16)), lo
+    for lo in _windows(n) + [(1 << 31) - 2048]:
+        sl = slice(lo, lo + 4096)
+        assert same_bits(to_np(acc[sl]), oracle.accumulate(to_np(before[sl]), to_np(recv[sl])))
+
+
+def test_pack_and_unpack_chunks_beyond_4gib():
+    nodes, gpus = 2, 2
+    cb = G4 + 48                                           # bytes per chunk: tiles, offsets and strides > 2^32
+    g = torch.Generator(device=DEV)
+    g.manual_seed(6)
+    src = torch.randint(0, 256, (nodes * gpus * cb,), generator=g, device=DEV, dtype=torch.uint8)
+    dst = torch.empty_like(src)
+    pccl.pccl_hier_pack(dst, src, nodes, gpus)
+    _sync()
+    s, d = src.view(nodes, gpus, cb), dst.view(gpus, nodes, cb)
+    for n in range(nodes):
+        for k in range(gpus):
+            assert torch.equal(d[k, n], s[n, k]), (n, k)   # the definition, chunk by chunk
+    # the oracle on windows: a small message made of the same window of every chunk
+    for off in (0, cb // 2, cb - 4096):                    # the last window straddles the 4 GiB offset
+        mini = np.stack([to_np(s[n, k, off:off + 4096]) for n in range(nodes) for k in range(gpus)])
+        want = oracle.hier_pack(mini.reshape(-1), nodes, gpus).reshape(gpus, nodes, 4096)
+        got = np.stack([to_np(d[k, n, off:off + 4096]) for k in range(gpus) for n in range(nodes)])
+        assert same_bits(got.reshape(gpus, nodes, 4096), want)
+    back = torch.empty_like(src)
+    pccl.pccl_hier_unpack(back, dst, nodes, gpus)
+    _sync()
+    assert torch.equal(back, src)                          # round trip = identity
+
+
+@pytest.fixture
+def tiny_grid_x(monkeypatch):
+    """Lower the x extent of a launch to 4096 work-items so that small problems take the
+    x/z-split path that buffers of tens of GiB take."""
+    monkeypatch.setenv("PCCL_GRID_X_LIMIT", "4096")
+
+
+@pytest.mark.parametrize("dtype", [F32, BF16])
+def test_split_grids_on_small_problems(tiny_grid_x, dtype):
+    from paper_2504_18658_amd import workloads as W
+    from util import Guarded
+    import oracle as O
+    odt = {F32: O.F32, BF16: O.BF16}[dtype]
+    # streaming reduce: 8 sources, 100003 elements -> hundreds of tiles over x and z, ragged tail
+    count = 100003
+    host = W.normal(8 * count, 1, 1.0, "cpu", dtype).view(8, count)
+    dst = Guarded(count, dtype)
+    pccl.pccl_local_reduce(dst.view, host.to(DEV))
+    _sync()
+    assert same_bits(to_np(dst.view), O.flat_reduce([to_np(host[s]) for s in range(8)]))
+    dst.check()
+    # LDS two-level kernel
+    nodes, gpus, cnt = 20, 4, 5000 + 3
+    h2 = W.normal(nodes * gpus * cnt, 2, 1.0, "cpu", dtype).view(nodes * gpus, cnt)
+    d2 = h2.to(DEV)
+    out = Guarded(cnt, dtype)
+    os.environ["PCCL_FORCE_TWO_LEVEL_KERNEL"] = "lds"
+    try:
+        pccl.pccl_local_reduce_ptrs_two_level(out.view, pccl.device_pointer_array([d2[k] for k in range(nodes * gpus)]),
+                                              nodes, gpus, cnt, dtype)
+        _sync()
+    finally:
+        os.environ.pop("PCCL_FORCE_TWO_LEVEL_KERNEL", None)
+    assert same_bits(to_np(out.view), O.two_level_reduce([to_np(h2[k]) for k in range(nodes * gpus)], nodes, gpus, odt))
+    out.check()
+    # accumulate
+    a_h, r_h = W.normal(count, 3, 1.0, "cpu", dtype), W.normal(count, 4, 1.0, "cpu", dtype)
+    acc = Guarded(count, dtype)
+    acc.view.copy_(a_h.to(DEV))
+    pccl.pccl_accumulate(acc.view, r_h.to(DEV))
+    _sync()
+    assert same_bits(to_np(acc.view), O.accumulate(to_np(a_h), to_np(r_h)))
+    acc.check()
+    # reduce-scatter share (rows) and the batched form (three buckets, one empty)
+    n, g, c = 5, 4, 3000 + 5
+    x_h = W.normal(g * n * c, 5, 1.0, "cpu", dtype).view(g, n, c)
+    x = x_h.to(DEV)
+    ws, wp = O.reduce_scatter_local(to_np(x_h))
+    s1, p1 = Guarded(c, dtype), Guarded(n * c, dtype)
+    s2, p2 = Guarded(c, dtype), Guarded(n * c, dtype)
+    empty = torch.empty(g, n, 0, dtype=dtype, device=DEV)
+    table = pccl.BucketTable([(s1.view, p1.view, x), (torch.empty(0, dtype=dtype, device=DEV),
+                                                      torch.empty(0, dtype=dtype, device=DEV), empty),
+                              (s2.view, p2.view, x)])
+    pccl.pccl_reduce_scatter_local_batched(table)
+    _sync()
+    for s_, p_ in ((s1, p1), (s2, p2)):
+        assert same_bits(to_np(s_.view), ws) and same_bits(to_np(p_.view), wp.reshape(-1))
+        s_.check()
+        p_.check()
+    P = n * g
+    msgs_h = W.normal(g * P * c, 6, 1.0, "cpu", dtype).view(g, P * c)
+    pccl.pccl_reduce_scatter_local_unpacked(s1.view, p1.view, msgs=msgs_h.to(DEV), nodes=n, gpus_per_node=g, my_gpu=2)
+    _sync()
+    ws, wp = O.reduce_scatter_local_unpacked([to_np(msgs_h[k]) for k in range(g)], n, g, 2)
+    assert same_bits(to_np(s1.view), ws) and same_bits(to_np(p1.view), wp.reshape(-1))
+    s1.check()
+    p1.check()
+
+
+def test_streaming_reduce_with_more_tiles_than_one_grid_dimension_holds():
+    """8 fp32 sources of 2^31 + 3 elements (8 GiB each): one element per thread, so the launch has
+    more than 2^31 work-items and spreads over x and z without any test knob."""
+    n = (1 << 31) + 3
+    src = torch.empty(8, n, dtype=F32, device=DEV)
+    g = torch.Generator(device=DEV)
+    g.manual_seed(7)
+    step = 1 << 28
+    for k in range(8):
+        for lo in range(0, n, step):
+            src[k, lo:lo + step].uniform_(-1.0, 1.0, generator=g)
+    dst = torch.empty(n, dtype=F32, device=DEV)
+    pccl.pccl_local_reduce(dst, src)
+    _sync()
+    for lo in range(0, n, step):
+        sl = slice(lo, min(n, lo + step))
+        ref = src[0][sl].clone()
+        for k in range(1, 8):
+            ref += src[k][sl]
+        assert torch.equal(dst[sl].view(torch.int32), ref.view(torch.int32)), lo
+    for lo in (0, (1 << 31) - 2048, n - 4096):
+        sl = slice(lo, lo + 4096)
+        assert same_bits(to_np(dst[sl]), oracle.flat_reduce([to_np(src[k][sl]) for k in range(8)]))
