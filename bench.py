@@ -32,9 +32,9 @@ from paper_2504_18658_amd import workloads as W  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
 # HBM bytes per 256 MB k_permute launch from the two rocprofv3 --pmc runs summarised in
-# profiles/bench_all_workloads_hbm_counters.txt: FETCH_SIZE 131084.8 KiB (x 2.000, the factor a
-# plain 256 MiB copy calibrates) + WRITE_SIZE 262209.0 KiB (x 1.000).
-PROFILED_PERMUTE_TRAFFIC_BYTES = int((131084.8 * 2.000 + 262209.0 * 1.000) * 1024)
+# profiles/bench_all_workloads_hbm_counters.txt: FETCH_SIZE 131085.1 KiB (x 2.000, the factor a
+# plain 256 MiB copy calibrates) + WRITE_SIZE 262201.5 KiB (x 1.000).
+PROFILED_PERMUTE_TRAFFIC_BYTES = int((131085.1 * 2.000 + 262201.5 * 1.000) * 1024)
 MB = 1 << 20
 
 
@@ -360,7 +360,7 @@ def main():
         torch.cuda.synchronize()
 
     out = {
-        "metric": "achieved HBM GB/s, local reduce + hier permute (one GPU's share of a two-level all-reduce)",
+        "metric": "achieved HBM GB/s (and % of peak) for local reduce + hier permute, 64\u2013256 MB",
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
