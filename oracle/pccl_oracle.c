@@ -16,8 +16,7 @@
  *   - reduce-scatter = the mirror image: intra-node phase first, inter-node
  *     phase second, with the vector reduction done on the GPU (Section IV-B).
  *   - all-reduce  = two-level reduce-scatter followed by two-level all-gather.
- * What the paper leaves open and this file fixes (each reading is listed in
- * the design document):
+ * What the paper leaves open and this file fixes:
  *   - rank r = n*M + g  (block placement of ranks on nodes);
  *   - summation order: within a node in ascending local id, then across
  *     nodes in ascending node id; the accumulator starts from the first
