@@ -1,0 +1,75 @@
+"""The library only enqueues kernels on the caller's stream (no allocation, no synchronisation),
+so a whole all-reduce share can be captured into a HIP graph.  Every replay is checked against
+the eager result, with eager work and synchronisations between replays."""
+import pytest
+import torch
+
+import oracle
+import paper_2504_18658_amd as pccl
+from paper_2504_18658_amd import workloads as W
+from util import same_bits, to_np
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+def test_captured_all_reduce_share_replays_match_eager_and_oracle():
+    w = W.cfg3(chunk=8192 + 8)
+    w.nodes = 4
+    P, C = w.ranks, w.chunk
+    msg = W.draw(w, P * C, DEV, seed_offset=1)
+    x = W.two_level_input(w, DEV, seed_offset=2)
+    msgs = W.draw(w, w.gpus * P * C, DEV, seed_offset=3).view(w.gpus, P * C)
+    inter = W.draw(w, w.nodes * C, DEV, seed_offset=4).view(w.nodes, C)
+    d_inter = pccl.device_pointer_array([inter[n] for n in range(w.nodes)])
+    gathered = W.draw(w, P * C, DEV, seed_offset=5)
+    srcs = W.draw(w, 64 * 8 * 512, DEV, seed_offset=6).view(64 * 8, 512)
+    ptrs = pccl.device_pointer_array([srcs[k] for k in range(64 * 8)])
+    recv = W.draw(w, 7 * C, DEV, seed_offset=7).view(7, C)
+    ring0 = W.draw(w, 8 * C, DEV, seed_offset=8).view(8, C)
+
+    def buffers():
+        return dict(packed=torch.empty_like(msg), partial=torch.empty(w.nodes * C, dtype=w.dtype, device=DEV),
+                    shard=torch.empty(C, dtype=w.dtype, device=DEV), partial2=torch.empty(w.nodes * C, dtype=w.dtype, device=DEV),
+                    shard2=torch.empty(C, dtype=w.dtype, device=DEV), out=torch.empty_like(gathered),
+                    small=torch.empty(512, dtype=torch.float32, device=DEV), ring=torch.empty_like(ring0))
+
+    def step(b):
+        pccl.pccl_hier_pack(b["packed"], msg, w.nodes, w.gpus)
+        pccl.pccl_reduce_scatter_local(b["shard"], b["partial"], x, d_inter=d_inter, my_node=1, average=True)
+        pccl.pccl_reduce_scatter_local_unpacked(b["shard2"], b["partial2"], msgs=msgs, d_inter=d_inter, nodes=w.nodes,
+                                                gpus_per_node=w.gpus, my_node=2, my_gpu=5)
+        pccl.pccl_allgather_reassemble(b["out"], src=gathered, nodes=w.nodes, gpus_per_node=w.gpus)
+        pccl.pccl_local_reduce_ptrs_two_level(b["small"], ptrs, 64, 8, 512, w.dtype)
+        b["ring"].copy_(ring0)                      # the replay mutates its message in place: reset it first
+        pccl.pccl_ring_reduce_scatter_local(b["ring"], recv, 3)
+
+    eager = buffers()
+    step(eager)
+    torch.cuda.synchronize()
+
+    cap = buffers()
+    g = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step(cap)                                   # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    with torch.cuda.graph(g):
+        step(cap)
+    for replay in range(4):
+        for t in cap.values():
+            t.view(torch.int16 if t.element_size() == 2 else torch.int32).fill_(0x5A5A)   # poison by an eager kernel
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for k in eager:
+            assert same_bits(to_np(cap[k]), to_np(eager[k])), (replay, k)
+        step(buffers())                             # eager work between replays
+        torch.cuda.synchronize()
+    # and the eager result itself is the oracle's
+    ws, wp = oracle.reduce_scatter_local(to_np(x), my_node=1, inter=[to_np(inter[n]) for n in range(w.nodes)], average=True)
+    assert same_bits(to_np(eager["shard"]), ws) and same_bits(to_np(eager["partial"]), wp.reshape(-1))
+    assert same_bits(to_np(eager["packed"]), oracle.hier_pack(to_np(msg), w.nodes, w.gpus))
+    assert same_bits(to_np(eager["ring"]), oracle.ring_rs_local(to_np(ring0), [to_np(recv[s]) for s in range(7)], 3))
