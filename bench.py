@@ -12,7 +12,8 @@ several disjoint buffer sets so that the last-level cache cannot serve a re-run.
 
 Prints ONE JSON line.  `value` = algorithmic bytes of a step / wall time of a step.
 `roofline` is for the dominant kernel (the chunk transpose), timed with events on the launch
-stream inside the timed region.  `cpu_baseline` times the CPU oracle on the same workload.
+stream inside the timed region (on every 8th step: an event pair stalls the stream for about
+3 us, which would otherwise add 13 us to every 220 us step).  `cpu_baseline` times the CPU oracle on the same workload.
 """
 import argparse
 import json
@@ -261,6 +262,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--sets", type=int, default=4, help="disjoint buffer sets rotated over (cold cache)")
     ap.add_argument("--no-kernel-events", action="store_true", help="do not record per-call events")
+    ap.add_argument("--events-every", type=int, default=8,
+                    help="bracket the calls of every n-th timed step with events (an event pair costs the "
+                         "stream about 3 us, 13 us per step when every call of every step is bracketed)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-others", action="store_true", help="skip the other four configurations")
     ap.add_argument("--calibration-copy", action="store_true",
@@ -287,11 +291,14 @@ def main():
     torch.cuda.synchronize()
 
     use_ev = not args.no_kernel_events
-    events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)] if use_ev else None
+    every = max(1, args.events_every)
+    # sampled steps: every `every`-th, shifted by one set per sample so that all buffer sets are sampled
+    sampled = [k for k in range(args.steps) if k % every == (k // every) % min(every, len(sets))] if use_ev else []
+    events = {k: [torch.cuda.Event(enable_timing=True) for _ in range(4)] for k in sampled}
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for k in range(args.steps):
-        sets[k % len(sets)].run(events[k] if use_ev else None)
+        sets[k % len(sets)].run(events.get(k))
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
@@ -302,7 +309,7 @@ def main():
     if use_ev:
         names = ["pccl_hier_pack", "pccl_reduce_scatter_local", "pccl_allgather_reassemble"]
         dur = {n: [] for n in names}
-        for ev in events:
+        for ev in events.values():
             for j, n in enumerate(names):
                 dur[n].append(ev[j].elapsed_time(ev[j + 1]))
         for n in names:
@@ -368,7 +375,7 @@ def main():
         "config": {"workload": w.name + ": pack 256 MB + two-level reduce (8 x 32 MB, 16 x 2 MB) + reassemble 256 MB",
                    "nodes": w.nodes, "gpus_per_node": w.gpus, "message_MB": w.ranks * w.chunk * w.esize // MB,
                    "accumulate": "f32", "algorithmic_bytes_per_step": step_bytes, "buffer_sets": args.sets,
-                   "kernel_events_in_timed_region": use_ev},
+                   "kernel_events_in_timed_region": use_ev, "kernel_events_every_n_steps": every if use_ev else None},
         "roofline": roofline, "cpu_baseline": cpu_baseline, "parity_vs_oracle": parity,
         "calls": calls, "fused_step": fused, "other_workloads": others,
     }
