@@ -96,6 +96,20 @@ pccl_status_t permute_common(void* dst, const void* src, const void* const* slot
   return e == hipErrorInvalidValue ? PCCL_ERR_INVALID : from_hip(e);
 }
 
+// A flat sum (p.nodes == 1, p.gpus sources).  A long chain over short buffers leaves the
+// streaming kernel with too few threads; a flat sum is the two-level sum with one GPU per
+// node, so the LDS-staged kernel takes it and overlaps the loads of many sources.
+hipError_t launch_flat(const ReduceProblem& p, int in_dt, int out_dt, hipStream_t st) {
+  ReduceProblem q = p;
+  q.nodes = p.gpus;
+  q.gpus = 1;
+  q.stride_n = p.stride_g;
+  q.stride_g = 0;
+  if (p.rows == 1 && p.partial == nullptr && pccl::prefer_lds_two_level(q, in_dt))
+    return pccl::launch_reduce_two_level_lds(q, in_dt, out_dt, st);
+  return pccl::launch_reduce(p, in_dt, out_dt, st);
+}
+
 // phase 2 (inter-node) of a two-level reduce-scatter share: shard[e] = sum over n' of
 // inter_n'[e], an N-source flat sum over the partial's rows or over received chunks
 pccl_status_t phase2(void* shard, void* partial, const void* const* d_inter, int nodes, int my_node,
@@ -113,7 +127,7 @@ pccl_status_t phase2(void* shard, void* partial, const void* const* d_inter, int
     p2.override_index = my_node;
     p2.override_ptr = reinterpret_cast<const char*>(partial) + (size_t)my_node * chunk_bytes;
   }
-  const hipError_t e = pccl::launch_reduce(p2, dt, dt, st);
+  const hipError_t e = launch_flat(p2, dt, dt, st);
   return e == hipErrorInvalidValue ? PCCL_ERR_INVALID : from_hip(e);
 }
 
@@ -145,7 +159,7 @@ pccl_status_t pccl_local_reduce(void* dst, const void* src_base, size_t src_stri
   p.count = count;
   p.gpus = nsrc;
   p.divisor = divisor_for(op, (size_t)nsrc);
-  const hipError_t e = pccl::launch_reduce(p, in_dt, out_dt, reinterpret_cast<hipStream_t>(stream));
+  const hipError_t e = launch_flat(p, in_dt, out_dt, reinterpret_cast<hipStream_t>(stream));
   return e == hipErrorInvalidValue ? PCCL_ERR_INVALID : from_hip(e);
 }
 
@@ -168,14 +182,7 @@ pccl_status_t pccl_local_reduce_ptrs(void* dst, const void* const* d_srcs, int n
   p.divisor = divisor_for(op, (size_t)nsrc);
   const int ib = in_dt, ob = out_dt;
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-  // A long flat chain over short buffers: stage the sources through LDS (a flat sum is the
-  // two-level sum with one GPU per node) so that the loads of many sources overlap.
-  ReduceProblem q = p;
-  q.nodes = nsrc;
-  q.gpus = 1;
-  const hipError_t e = pccl::prefer_lds_two_level(q, ib)
-                           ? pccl::launch_reduce_two_level_lds(q, ib, ob, st)
-                           : pccl::launch_reduce(p, ib, ob, st);
+  const hipError_t e = launch_flat(p, ib, ob, st);
   return e == hipErrorInvalidValue ? PCCL_ERR_INVALID : from_hip(e);
 }
 
@@ -270,7 +277,7 @@ pccl_status_t pccl_reduce_scatter_local(void* shard, void* partial, const void* 
   p1.stride_g = gpus_per_node > 1 ? intra_stride_bytes : 0;
   p1.count = piece_count;
   p1.gpus = gpus_per_node;
-  hipError_t e = pccl::launch_reduce(p1, dt, dt, st);
+  hipError_t e = launch_flat(p1, dt, dt, st);
   if (e != hipSuccess) return e == hipErrorInvalidValue ? PCCL_ERR_INVALID : PCCL_ERR_HIP;
 
   return phase2(shard, partial, d_inter, nodes, my_node, chunk_count, chunk_bytes, dt, divisor, st);

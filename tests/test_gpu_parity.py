@@ -358,6 +358,35 @@ def test_reduce_scatter_local_with_received_inter_chunks(dtype):
     shard.check()
 
 
+@pytest.mark.parametrize("dtype", [F32, BF16])
+@pytest.mark.parametrize("nodes,gpus,chunk", [(64, 2, 1000), (256, 8, 96), (300, 1, 515), (40, 32, 64)])
+def test_reduce_scatter_local_many_sources_short_chunks(dtype, nodes, gpus, chunk):
+    """Shapes whose phase 2 (and, with 32 GPUs per node, phase 1) is a long chain over short
+    buffers: the flat sums go through the LDS-staged kernel."""
+    x_h = _draw(gpus * nodes * chunk, dtype, 4242 + nodes).view(gpus, nodes, chunk)
+    inter_h = _draw(nodes * chunk, dtype, 4243 + nodes).view(nodes, chunk)
+    x, inter = x_h.to(DEV), inter_h.to(DEV)
+    my_node = nodes // 3
+    for d_inter in (None, pccl.device_pointer_array([inter[n] for n in range(nodes)])):
+        partial = Guarded(nodes * chunk, dtype)
+        shard = Guarded(chunk, dtype)
+        pccl.pccl_reduce_scatter_local(shard.view, partial.view, x, d_inter=d_inter, my_node=my_node)
+        _sync()
+        want_shard, want_partial = oracle.reduce_scatter_local(
+            to_np(x_h), my_node=my_node, inter=None if d_inter is None else [to_np(inter_h[n]) for n in range(nodes)])
+        assert same_bits(to_np(partial.view), want_partial.reshape(-1)), first_diff(to_np(partial.view), want_partial)
+        assert same_bits(to_np(shard.view), want_shard), first_diff(to_np(shard.view), want_shard)
+        partial.check()
+        shard.check()
+    # the strided flat entry with many short sources
+    src_h = _draw(200 * 333, dtype, 99).view(200, 333)
+    dst = Guarded(333, dtype)
+    pccl.pccl_local_reduce(dst.view, src_h.to(DEV))
+    _sync()
+    assert same_bits(to_np(dst.view), oracle.flat_reduce([to_np(src_h[k]) for k in range(200)]))
+    dst.check()
+
+
 def test_reduce_scatter_local_strided_pieces():
     """Pieces that do not touch each other in memory (row stride larger than a piece)."""
     nodes, gpus, chunk = 4, 8, 512
