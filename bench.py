@@ -268,6 +268,35 @@ def fused_leg(dev, steps, warmup, nsets=4, my_node=5, my_gpu=3):
                 unpacked_reduce_scatter_back_to_back_us=round(rs_ms[3] * 1e3, 2))
 
 
+def size_sweep(dev):
+    """Message sizes of the paper's range (16 MB - 1 GB, Section V-A) through the three kernels:
+    chunk transpose (16 x 8 ranks), 8-source bf16 reduce (phase 1) and the two-source step."""
+    w = W.cfg3()
+    out = []
+    for mb in (16, 32, 64, 128, 256, 512, 1024):
+        m = mb * MB
+        n = m // 2                                              # bf16 elements of the message
+        nsets = max(2, min(8, (1024 * MB) // m + 1))             # rotate over at least ~1 GB of inputs
+        row = {"message_MB": mb, "buffer_sets": nsets}
+        sets = [(torch.empty(n, dtype=w.dtype, device=dev), W.draw(w, n, dev, seed_offset=400 + k)) for k in range(nsets)]
+        t = time_calls([lambda s=s: pccl.pccl_hier_pack(s[0], s[1], w.nodes, w.gpus) for s in sets], trials=2 * nsets)
+        row["hier_pack_us"] = round(t[3] * 1e3, 2)
+        row["hier_pack_GBps"] = round(2 * m / (t[3] * 1e-3) / 1e9, 1)
+        # phase 1 of the share of this message: 8 pieces of m/8 -> m/8
+        t = time_calls([lambda s=s: pccl.pccl_local_reduce(s[0][: n // 8], s[1].view(8, n // 8)) for s in sets],
+                       trials=2 * nsets)
+        row["reduce8_us"] = round(t[3] * 1e3, 2)
+        row["reduce8_GBps"] = round((m + m // 8) / (t[3] * 1e-3) / 1e9, 1)
+        # first halving step on this message: m/2 += m/2
+        t = time_calls([lambda s=s: pccl.pccl_accumulate(s[0][: n // 2], s[1][: n // 2]) for s in sets], trials=2 * nsets)
+        row["accumulate_us"] = round(t[3] * 1e3, 2)
+        row["accumulate_GBps"] = round(3 * (m // 2) / (t[3] * 1e-3) / 1e9, 1)
+        out.append(row)
+        del sets
+        torch.cuda.empty_cache()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -280,6 +309,7 @@ def main():
                          "stream about 3 us, 13 us per step when every call of every step is bracketed)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-others", action="store_true", help="skip the other four configurations")
+    ap.add_argument("--sweep", action="store_true", help="also time the kernels over 16 MB - 1 GB messages")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run plain 256 MB device-to-device copies (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -372,6 +402,7 @@ def main():
         fused["speedup_vs_three_call_step"] = round(ms_per_step / fused["ms_per_step"], 3)
     torch.cuda.empty_cache()
     others = None if args.no_others else other_workloads(dev)
+    sweep = size_sweep(dev) if args.sweep else None
     if args.calibration_copy:
         a = torch.empty(256 * MB, dtype=torch.uint8, device=dev)
         b = torch.ones(256 * MB, dtype=torch.uint8, device=dev)
@@ -390,7 +421,7 @@ def main():
                    "accumulate": "f32", "algorithmic_bytes_per_step": step_bytes, "buffer_sets": args.sets,
                    "kernel_events_in_timed_region": use_ev, "kernel_events_every_n_steps": every if use_ev else None},
         "roofline": roofline, "cpu_baseline": cpu_baseline, "parity_vs_oracle": parity,
-        "calls": calls, "fused_step": fused, "other_workloads": others,
+        "calls": calls, "fused_step": fused, "other_workloads": others, "size_sweep": sweep,
     }
     print(json.dumps(out), flush=True)
 
