@@ -394,6 +394,28 @@ def main():
                             sample="%d whole steps of the same workload (pack, two-level reduce, reassemble), "
                                    "%.1f s, single thread of %d host cores" % (reps, t_cpu, os.cpu_count() or 0),
                             ms_per_step=round(t_cpu / reps * 1e3, 1))
+        # the same oracle with its element loops split over the box's share of host cores (the byte
+        # copies of its permutations stay on one thread); a second reported baseline, about 5 s
+        nthr = min(16, os.cpu_count() or 1)
+        reps2, t2 = 0, 0.0
+        while t2 < 5.0 and reps2 < 50:
+            c0 = time.perf_counter()
+            want2 = s0.oracle_step(host, nthreads=nthr)
+            t2 += time.perf_counter() - c0
+            reps2 += 1
+        parity = parity and all(np.ascontiguousarray(a).tobytes() == np.ascontiguousarray(b).tobytes()
+                                for a, b in zip(want, want2))
+        cpu_baseline["all_threads"] = dict(value=round(step_bytes * reps2 / t2 / 1e9, 3), unit="GB/s", cores=nthr,
+                                           ms_per_step=round(t2 / reps2 * 1e3, 1),
+                                           sample="%d whole steps, %.1f s" % (reps2, t2))
+        # warm numbers, labelled: the same buffer set over and over (the 256 MB last-level cache holds part of it)
+        warm = {}
+        for name, fn in (("pccl_hier_pack", lambda: pccl.pccl_hier_pack(s0.packed, s0.msg, w.nodes, w.gpus)),
+                         ("pccl_reduce_scatter_local", lambda: pccl.pccl_reduce_scatter_local(
+                             s0.shard, s0.partial, s0.x, d_inter=s0.d_inter, my_node=s0.my_node))):
+            t = time_calls([fn], trials=20, warm=5)
+            warm[name] = dict(back_to_back_us=round(t[3] * 1e3, 2), GBps=round(per_call[name] / (t[3] * 1e-3) / 1e9, 1))
+        calls["warm_same_buffers"] = warm
     del sets
     torch.cuda.empty_cache()
 
