@@ -577,3 +577,51 @@ def test_cfg5_zero3_buckets_full_size():
         for sl in (slice(0, head), slice(tail, tail + head)):
             want_shard, _ = oracle.reduce_scatter_local(to_np(x[:, :, sl]))
             assert same_bits(to_np(shard[sl]), want_shard), k
+
+
+# ------------------------------------------------------------------------------- empty inputs
+def test_empty_inputs_launch_nothing_and_touch_nothing():
+    """count == 0 / chunk == 0 succeed without a launch: poisoned outputs stay as they are."""
+    for dtype in (F32, BF16):
+        out = Guarded(16, dtype)
+        before = to_np(out.raw).copy()
+        empty_src = torch.empty(4, 0, dtype=dtype, device=DEV)
+        L = pccl.lib()
+        st = torch.cuda.current_stream().cuda_stream
+        dt = pccl.binding.dtype_code(dtype)
+        p = out.view.data_ptr()
+        q = torch.empty(64, dtype=dtype, device=DEV).data_ptr()
+        assert L.pccl_local_reduce(p, q, 0, 4, 0, dt, dt, 0, st) == pccl.PCCL_OK
+        assert L.pccl_local_reduce_ptrs(p, q, 4, 0, dt, dt, 0, st) == pccl.PCCL_OK
+        assert L.pccl_local_reduce_ptrs_two_level(p, q, 2, 2, 0, dt, dt, 0, st) == pccl.PCCL_OK
+        assert L.pccl_hier_pack(p, q, 2, 2, 0, st) == pccl.PCCL_OK
+        assert L.pccl_hier_unpack(p, q, 2, 2, 0, st) == pccl.PCCL_OK
+        assert L.pccl_allgather_reassemble(p, q, None, 2, 2, 0, st) == pccl.PCCL_OK
+        assert L.pccl_reduce_scatter_local(p, p + 1024, q, 0, None, 2, 2, 0, 0, dt, 0, st) == pccl.PCCL_OK
+        assert L.pccl_reduce_scatter_local_unpacked(p, p + 1024, q, 0, None, None, 2, 2, 0, 1, 0, dt, 0, st) == pccl.PCCL_OK
+        assert L.pccl_reduce_scatter_local_batched(None, None, 0, 2, 2, dt, 0, st) == pccl.PCCL_OK
+        assert L.pccl_accumulate(p, q, 0, dt, 0, st) == pccl.PCCL_OK
+        assert L.pccl_ring_reduce_scatter_local(p, q, 0, 4, 1, 0, dt, 0, st) == pccl.PCCL_OK
+        assert L.pccl_halving_reduce_scatter_local(p, q, 4, 1, 0, dt, 0, st) == pccl.PCCL_OK
+        _sync()
+        assert same_bits(to_np(out.raw), before)
+        del empty_src
+
+
+def test_binding_refuses_host_tensors_and_mismatched_shapes():
+    host = torch.zeros(4, 8)
+    dev = torch.zeros(4, 8, device=DEV)
+    with pytest.raises(ValueError):
+        pccl.pccl_local_reduce(torch.zeros(8, device=DEV), host)
+    with pytest.raises(ValueError):
+        pccl.pccl_local_reduce(torch.zeros(7, device=DEV), dev)
+    with pytest.raises(ValueError):
+        pccl.pccl_hier_pack(torch.zeros(30, device=DEV), torch.zeros(32, device=DEV), 2, 4)
+    with pytest.raises(TypeError):
+        pccl.pccl_local_reduce(torch.zeros(8, device=DEV, dtype=torch.float64), dev.double())
+    with pytest.raises(pccl.PcclError) as e:                       # in-place is refused by the library itself
+        pccl.pccl_local_reduce(dev[0], dev)
+    assert e.value.status == pccl.PCCL_ERR_OVERLAP
+    with pytest.raises(pccl.PcclError) as e:                       # bf16 in, fp16 out: no such pair
+        pccl.pccl_local_reduce(torch.zeros(8, device=DEV, dtype=torch.float16), dev.to(torch.bfloat16))
+    assert e.value.status == pccl.PCCL_ERR_UNSUPPORTED
