@@ -222,6 +222,17 @@ def other_workloads(dev):
     entry("cfg5_rs_batched_40_buckets_8x8_bf16", nbytes,
           *time_calls([lambda: pccl.pccl_reduce_scatter_local_batched(table)], trials=5, warm=2),
           total_bucket_MB=round(sum(sizes) / MB, 1))
+    del table, buckets
+    torch.cuda.empty_cache()
+    # the all-gather side of the same 40 buckets: every bucket's shuffle into rank order, one launch
+    pairs = []
+    for k, b in enumerate(sizes):
+        src = W.random_bits16(b // 2, 500 + k, dev)
+        pairs.append((torch.empty_like(src), src))
+    ptable = pccl.PermuteTable(pairs, w.nodes, w.gpus)
+    entry("cfg5_allgather_reassemble_batched_40_buckets_8x8", 2 * sum(sizes),
+          *time_calls([lambda: pccl.pccl_allgather_reassemble_batched(ptable)], trials=5, warm=2),
+          total_bucket_MB=round(sum(sizes) / MB, 1))
     return res
 
 

@@ -195,6 +195,31 @@ pccl_status_t pccl_reduce_scatter_local_batched(const pccl_bucket_t* d_buckets,
                                                 pccl_dtype_t io_dt, pccl_op_t op,
                                                 pccl_stream_t stream);
 
+/* One bucket of a batched shuffle: dst and src each hold nodes*gpus_per_node chunks of
+ * chunk_bytes bytes and must not overlap.  Device pointers. */
+typedef struct {
+  void* dst;
+  const void* src;
+  size_t chunk_bytes;
+} pccl_permute_bucket_t;
+
+/* nbuckets independent shuffles in ONE launch -- the all-gathers (parameters) and the
+ * reduce-scatter pre-shuffles (gradients) a ZeRO-3 / FSDP step issues by the dozen (Section
+ * II-A).  pccl_allgather_reassemble_batched applies pccl_hier_unpack to every bucket
+ * (hierarchical order -> rank order), pccl_hier_pack_batched applies pccl_hier_pack (rank
+ * order -> hierarchical order).  d_buckets: device array read by the kernel; h_buckets: HOST
+ * copy of the same descriptors for the argument checks and the launch size.  nodes and
+ * gpus_per_node are common to the batch; a bucket with chunk_bytes == 0 is skipped;
+ * nbuckets <= PCCL_MAX_BUCKETS; at most 2^32 - 1 KiB-tiles per call.
+ * Errors: NULLs; nodes/gpus < 1; size overflow; a bucket whose dst overlaps its src. */
+pccl_status_t pccl_allgather_reassemble_batched(const pccl_permute_bucket_t* d_buckets,
+                                                const pccl_permute_bucket_t* h_buckets,
+                                                int nbuckets, int nodes, int gpus_per_node,
+                                                pccl_stream_t stream);
+pccl_status_t pccl_hier_pack_batched(const pccl_permute_bucket_t* d_buckets,
+                                     const pccl_permute_bucket_t* h_buckets, int nbuckets,
+                                     int nodes, int gpus_per_node, pccl_stream_t stream);
+
 /* The vector-reduction kernel in the paper's literal form (Section III-B: a reduce-scatter
  * from point-to-point messages plus a GPU vector reduction; Section IV-B: PCCL_ring and
  * PCCL_rec schedule their local reduction on the GPU): the buffer a step has just received

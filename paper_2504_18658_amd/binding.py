@@ -20,7 +20,8 @@ EXPORTS = (
     "pccl_local_reduce", "pccl_local_reduce_ptrs", "pccl_local_reduce_ptrs_two_level",
     "pccl_hier_pack", "pccl_hier_unpack", "pccl_reduce_scatter_local",
     "pccl_allgather_reassemble", "pccl_reduce_scatter_local_batched", "pccl_accumulate",
-    "pccl_reduce_scatter_local_unpacked", "pccl_ring_reduce_scatter_local", "pccl_halving_reduce_scatter_local", "pccl_model_ring", "pccl_model_rec",
+    "pccl_reduce_scatter_local_unpacked", "pccl_ring_reduce_scatter_local",
+    "pccl_allgather_reassemble_batched", "pccl_hier_pack_batched", "pccl_halving_reduce_scatter_local", "pccl_model_ring", "pccl_model_rec",
     "pccl_choose_algorithm", "pccl_model_two_level", "pccl_status_string",
 )
 PCCL_ALGO_RING, PCCL_ALGO_REC = 0, 1
@@ -36,6 +37,10 @@ class pccl_bucket_t(ctypes.Structure):
     _fields_ = [("shard", ctypes.c_void_p), ("partial", ctypes.c_void_p),
                 ("intra_base", ctypes.c_void_p), ("intra_stride_bytes", ctypes.c_size_t),
                 ("chunk_count", ctypes.c_size_t)]
+
+
+class pccl_permute_bucket_t(ctypes.Structure):
+    _fields_ = [("dst", ctypes.c_void_p), ("src", ctypes.c_void_p), ("chunk_bytes", ctypes.c_size_t)]
 
 
 class PcclError(RuntimeError):
@@ -65,6 +70,8 @@ def lib():
         L.pccl_allgather_reassemble.argtypes = [vp, vp, vp, i, i, sz, vp]
         L.pccl_reduce_scatter_local_batched.argtypes = [vp, vp, i, i, i, i, i, vp]
         L.pccl_accumulate.argtypes = [vp, vp, sz, i, i, vp]
+        L.pccl_allgather_reassemble_batched.argtypes = [vp, vp, i, i, i, vp]
+        L.pccl_hier_pack_batched.argtypes = [vp, vp, i, i, i, vp]
         L.pccl_reduce_scatter_local_unpacked.argtypes = [vp, vp, vp, sz, vp, vp, i, i, i, i, sz, i, i, vp]
         L.pccl_ring_reduce_scatter_local.argtypes = [vp, vp, sz, i, i, sz, i, i, vp]
         L.pccl_halving_reduce_scatter_local.argtypes = [vp, vp, i, i, sz, i, i, vp]
@@ -334,3 +341,39 @@ def pccl_choose_algorithm(p, m_bytes, alpha_ring, beta_ring, alpha_rec, beta_rec
     _check(lib().pccl_choose_algorithm(p, m_bytes, ctypes.byref(model), ctypes.byref(algo), ctypes.byref(tr),
                                        ctypes.byref(tc)), "pccl_choose_algorithm")
     return algo.value, tr.value, tc.value
+
+
+class PermuteTable:
+    """Descriptor table of a batched shuffle: host array + device copy, built once and reused."""
+
+    def __init__(self, pairs, nodes, gpus_per_node):
+        """pairs: list of (dst, src) contiguous tensors, each holding nodes*gpus_per_node equal chunks."""
+        n = len(pairs)
+        self.host = (pccl_permute_bucket_t * max(n, 1))()
+        self.nbuckets, self.nodes, self.gpus = n, nodes, gpus_per_node
+        for k, (dst, src) in enumerate(pairs):
+            cb = _chunk_bytes(src, nodes, gpus_per_node, "PermuteTable")
+            if _chunk_bytes(dst, nodes, gpus_per_node, "PermuteTable") != cb:
+                raise ValueError("PermuteTable: dst and src sizes differ")
+            self.host[k] = pccl_permute_bucket_t(_dev(dst, "dst") if cb else None, _dev(src, "src") if cb else None, cb)
+        raw = bytes(self.host)[: n * ctypes.sizeof(pccl_permute_bucket_t)]
+        dev = pairs[0][0].device if n else "cuda"
+        self.device = torch.frombuffer(bytearray(raw), dtype=torch.uint8).to(dev) if n else None
+        self._keep = pairs  # the table holds raw pointers: keep the tensors alive
+
+
+def _permute_batched(name, table, stream):
+    if table.nbuckets == 0:
+        return
+    _check(getattr(lib(), name)(table.device.data_ptr(), ctypes.addressof(table.host), table.nbuckets, table.nodes,
+                                table.gpus, _stream(stream)), name)
+
+
+def pccl_allgather_reassemble_batched(table, stream=None):
+    """Every bucket of a PermuteTable: hierarchical order -> rank order, one launch."""
+    _permute_batched("pccl_allgather_reassemble_batched", table, stream)
+
+
+def pccl_hier_pack_batched(table, stream=None):
+    """Every bucket of a PermuteTable: rank order -> hierarchical order, one launch."""
+    _permute_batched("pccl_hier_pack_batched", table, stream)

@@ -64,6 +64,12 @@ hipError_t launch_reduce_two_level_lds(const ReduceProblem& p, int in_dt, int ou
 // True when the LDS-staged kernel is the better choice for this shape.
 bool prefer_lds_two_level(const ReduceProblem& p, int in_dt);
 
+// nbuckets chunk transposes (dst chunk c*rows + r = src chunk r*cols + c in every bucket) in
+// one launch; h_buckets is the host copy used to size the grid.
+hipError_t launch_permute_batched(const pccl_permute_bucket_t* d_buckets,
+                                  const pccl_permute_bucket_t* h_buckets, int nbuckets, int rows, int cols,
+                                  hipStream_t st);
+
 // x and z extents for `blocks` thread blocks of `threads` threads each, keeping blocks*threads
 // of the x dimension below 2^32 work-items (kernels index with linear_block_xz()).  False when
 // even 65535 z-slices do not hold them.  PCCL_GRID_X_LIMIT (work-items, for tests) lowers the

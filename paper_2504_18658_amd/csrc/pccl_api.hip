@@ -131,6 +131,30 @@ pccl_status_t phase2(void* shard, void* partial, const void* const* d_inter, int
   return e == hipErrorInvalidValue ? PCCL_ERR_INVALID : from_hip(e);
 }
 
+pccl_status_t permute_batched_common(const pccl_permute_bucket_t* d_buckets,
+                                     const pccl_permute_bucket_t* h_buckets, int nbuckets, int rows,
+                                     int cols, pccl_stream_t stream) {
+  if (nbuckets < 0 || nbuckets > PCCL_MAX_BUCKETS) return PCCL_ERR_INVALID;
+  if (nbuckets > 0 && (d_buckets == nullptr || h_buckets == nullptr)) return PCCL_ERR_NULL;
+  if (rows < 1 || cols < 1) return PCCL_ERR_INVALID;
+  size_t chunks;
+  if (!mul_ok((size_t)rows, (size_t)cols, &chunks) || chunks > 0x7FFFFFFFull) return PCCL_ERR_INVALID;
+  bool any = false;
+  for (int b = 0; b < nbuckets; ++b) {
+    const pccl_permute_bucket_t& k = h_buckets[b];
+    if (k.chunk_bytes == 0) continue;  // an empty bucket is skipped whatever its pointers are
+    if (k.dst == nullptr || k.src == nullptr) return PCCL_ERR_NULL;
+    size_t total;
+    if (!mul_ok(chunks, k.chunk_bytes, &total)) return PCCL_ERR_INVALID;
+    if (overlaps(k.dst, total, k.src, total)) return PCCL_ERR_OVERLAP;
+    any = true;
+  }
+  if (!any) return PCCL_OK;
+  const hipError_t e = pccl::launch_permute_batched(d_buckets, h_buckets, nbuckets, rows, cols,
+                                                    reinterpret_cast<hipStream_t>(stream));
+  return e == hipErrorInvalidValue ? PCCL_ERR_INVALID : from_hip(e);
+}
+
 }  // namespace
 
 extern "C" {
@@ -237,6 +261,21 @@ pccl_status_t pccl_allgather_reassemble(void* dst, const void* src, const void* 
                                         pccl_stream_t stream) {
   return permute_common(dst, d_slots != nullptr ? nullptr : src, d_slots, gpus_per_node, nodes,
                         chunk_bytes, stream);
+}
+
+pccl_status_t pccl_allgather_reassemble_batched(const pccl_permute_bucket_t* d_buckets,
+                                                const pccl_permute_bucket_t* h_buckets,
+                                                int nbuckets, int nodes, int gpus_per_node,
+                                                pccl_stream_t stream) {
+  // every src is [gpu][node]: rows = gpus, cols = nodes
+  return permute_batched_common(d_buckets, h_buckets, nbuckets, gpus_per_node, nodes, stream);
+}
+
+pccl_status_t pccl_hier_pack_batched(const pccl_permute_bucket_t* d_buckets,
+                                     const pccl_permute_bucket_t* h_buckets, int nbuckets,
+                                     int nodes, int gpus_per_node, pccl_stream_t stream) {
+  // every src is [node][gpu]: rows = nodes, cols = gpus
+  return permute_batched_common(d_buckets, h_buckets, nbuckets, nodes, gpus_per_node, stream);
 }
 
 pccl_status_t pccl_reduce_scatter_local(void* shard, void* partial, const void* intra_base,

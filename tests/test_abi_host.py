@@ -275,3 +275,28 @@ def test_unpacked_reduce_scatter_rejects_bad_arguments():
     assert call(shard=8 * A + 16380) == pccl.PCCL_ERR_OVERLAP       # shard reaches the last message word
     assert call(shard=2 * A + 4092) == pccl.PCCL_ERR_OVERLAP        # shard reaches into the partial
     assert call(c=0) == pccl.PCCL_OK
+
+
+@pytest.mark.parametrize("name", ["pccl_allgather_reassemble_batched", "pccl_hier_pack_batched"])
+def test_batched_permute_rejects_bad_arguments(name):
+    f = getattr(pccl.lib(), name)
+    good = (pccl.pccl_permute_bucket_t * 2)(pccl.pccl_permute_bucket_t(A, 8 * A, 4096),
+                                            pccl.pccl_permute_bucket_t(2 * A, 16 * A, 100))
+    h = ctypes.addressof(good)
+    assert f(None, h, 2, 4, 8, None) == pccl.PCCL_ERR_NULL
+    assert f(A, None, 2, 4, 8, None) == pccl.PCCL_ERR_NULL
+    assert f(A, h, -1, 4, 8, None) == pccl.PCCL_ERR_INVALID
+    assert f(A, h, pccl.PCCL_MAX_BUCKETS + 1, 4, 8, None) == pccl.PCCL_ERR_INVALID
+    assert f(A, h, 2, 0, 8, None) == pccl.PCCL_ERR_INVALID
+    assert f(A, h, 2, 4, -2, None) == pccl.PCCL_ERR_INVALID
+    assert f(A, h, 2, 1 << 20, 1 << 20, None) == pccl.PCCL_ERR_INVALID     # rank count out of range
+    assert f(None, None, 0, 4, 8, None) == pccl.PCCL_OK                    # empty batch
+    null_dst = (pccl.pccl_permute_bucket_t * 1)(pccl.pccl_permute_bucket_t(None, 8 * A, 64))
+    assert f(A, ctypes.addressof(null_dst), 1, 4, 8, None) == pccl.PCCL_ERR_NULL
+    over = (pccl.pccl_permute_bucket_t * 1)(pccl.pccl_permute_bucket_t(8 * A + 64, 8 * A, 64))
+    assert f(A, ctypes.addressof(over), 1, 4, 8, None) == pccl.PCCL_ERR_OVERLAP
+    huge = (pccl.pccl_permute_bucket_t * 1)(pccl.pccl_permute_bucket_t(A, 8 * A, 1 << 62))
+    assert f(A, ctypes.addressof(huge), 1, 4, 8, None) == pccl.PCCL_ERR_INVALID  # byte size overflows
+    empty = (pccl.pccl_permute_bucket_t * 2)(pccl.pccl_permute_bucket_t(None, None, 0),
+                                             pccl.pccl_permute_bucket_t(None, None, 0))
+    assert f(A, ctypes.addressof(empty), 2, 4, 8, None) == pccl.PCCL_OK    # only empty buckets: no launch

@@ -625,3 +625,48 @@ def test_binding_refuses_host_tensors_and_mismatched_shapes():
     with pytest.raises(pccl.PcclError) as e:                       # bf16 in, fp16 out: no such pair
         pccl.pccl_local_reduce(torch.zeros(8, device=DEV, dtype=torch.float16), dev.to(torch.bfloat16))
     assert e.value.status == pccl.PCCL_ERR_UNSUPPORTED
+
+
+# ------------------------------------------------------------------------------- batched shuffles
+@pytest.mark.parametrize("nodes,gpus", [(4, 8), (3, 5), (1, 7), (16, 2)])
+def test_batched_shuffles_match_the_oracle_bucket_by_bucket(nodes, gpus):
+    P = nodes * gpus
+    chunk_bytes = [1024, 6, 0, 4096 + 48, 1, 100000, 16, 2050]       # ragged, tiny, empty, several tiles
+    for offset in (0, 1):                                              # 16-byte aligned and not
+        srcs_h = [W.random_bits16((P * cb + 1) // 2 + 8, 50 + k).view(torch.uint8)[offset:offset + P * cb]
+                  for k, cb in enumerate(chunk_bytes)]
+        srcs = [s.to(DEV) for s in srcs_h]
+        for name, fn, ref in (("unpack", pccl.pccl_allgather_reassemble_batched, oracle.hier_unpack),
+                              ("pack", pccl.pccl_hier_pack_batched, oracle.hier_pack)):
+            outs = [Guarded((P * cb + 3) // 4 + 2, F32) for cb in chunk_bytes]
+            dsts = [o.view.view(torch.uint8)[offset:offset + P * cb] for o, cb in zip(outs, chunk_bytes)]
+            table = pccl.PermuteTable(list(zip(dsts, srcs)), nodes, gpus)
+            fn(table)
+            _sync()
+            for k, cb in enumerate(chunk_bytes):
+                if cb:
+                    want = ref(srcs_h[k].numpy(), nodes, gpus)
+                    assert same_bits(to_np(dsts[k]), want), (name, k, cb, first_diff(to_np(dsts[k]), want))
+                outs[k].check()
+
+
+def test_batched_reassembly_of_the_zero3_bucket_list_full_size():
+    """The 40 ZeRO-3-shaped buckets (16-512 MB, 8 x 8 ranks) through one batched all-gather shuffle:
+    chunk by chunk equal to the definition on the GPU, three buckets and the head and tail of every
+    bucket against the oracle."""
+    w = W.cfg5()
+    sizes = w.extra["bucket_bytes"]
+    pairs = []
+    for k, b in enumerate(sizes):
+        src = W.random_bits16(b // 2, 700 + k, DEV)
+        pairs.append((torch.empty_like(src), src))
+    table = pccl.PermuteTable(pairs, w.nodes, w.gpus)
+    pccl.pccl_allgather_reassemble_batched(table)
+    _sync()
+    for k, (dst, src) in enumerate(pairs):
+        cb2 = src.numel() // w.ranks
+        assert torch.equal(dst.view(torch.int16).view(w.nodes, w.gpus, cb2),
+                           src.view(torch.int16).view(w.gpus, w.nodes, cb2).transpose(0, 1)), k
+    for k in sorted(range(len(sizes)), key=lambda j: sizes[j])[:3]:
+        dst, src = pairs[k]
+        assert same_bits(to_np(dst), oracle.hier_unpack(to_np(src), w.nodes, w.gpus)), k
