@@ -11,7 +11,13 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
-constexpr int kBlock = 256;  // threads per block of the streaming kernels (4 wavefronts)
+// Threads per block of the streaming kernels.  Measured on MI355X for the 8-source reduce:
+// two-wavefront blocks win up to ~150 MB moved per launch (13.3 against 15.2 us at 72 MB,
+// 25.4 against 27.6 at 144 MB), four-wavefront blocks from there on (47.6 against 49.3 us at
+// 288 MB, 183 against 190 at 1.1 GB); the host picks by the bytes a launch moves.
+constexpr int kBlock = 256;       // large launches, and the batched kernels
+constexpr int kBlockSmall = 128;  // small launches
+constexpr size_t kSmallLaunchBytes = (size_t)192 << 20;
 
 // A grid dimension holds fewer than 2^32 work-items (blocks x threads), so a launch with more
 // blocks than that spreads them over x and z; this is the block's index in the whole launch.

@@ -108,22 +108,22 @@ __device__ void reduce_elem(const ReduceProblem& p, size_t e) {
 }
 
 // ------------------------------------------------------------------------------------------
-// streaming path.  A thread owns one vector of W 32-bit words per source; a tile is kBlock
+// streaming path.  A thread owns one vector of W 32-bit words per source; a tile is BLOCK
 // consecutive vectors, so every wavefront load is one contiguous 256*W bytes.
 // M > 0: exactly M sources per node, fully unrolled (M loads in flight per lane);
 // M == 0: any number of sources, walked in batches of four.
 // W is picked so that a lane keeps about 32 bytes of loads in flight (M * 4W): measured on
 // MI355X, more bytes per lane at full occupancy lowers the achieved HBM bandwidth.
-template <int IN, int OUT, int M, int W, bool FAST>
+template <int IN, int OUT, int M, int W, bool FAST, int BLOCK>
 __device__ __forceinline__ void reduce_tile(const ReduceProblem& p, size_t tile) {
   constexpr int VE = narrow(IN) ? 2 * W : W;  // elements per vector
   constexpr int ES = narrow(IN) ? 2 : 4;
   constexpr int VB = 4 * W;  // bytes per vector
   const size_t nvec = p.count / VE;
-  const size_t ntiles_vec = (nvec + kBlock - 1) / kBlock;
+  const size_t ntiles_vec = (nvec + BLOCK - 1) / BLOCK;
   const size_t last_tile = ntiles_vec == 0 ? 0 : ntiles_vec - 1;
-  const size_t v = tile * kBlock + threadIdx.x;
-  const size_t tile_off = tile * ((size_t)kBlock * VB);  // wave-uniform byte offset of the tile
+  const size_t v = tile * BLOCK + threadIdx.x;
+  const size_t tile_off = tile * ((size_t)BLOCK * VB);  // wave-uniform byte offset of the tile
   const uint32_t lane_off = threadIdx.x * VB;            // this lane's offset inside the tile
 
   if (v < nvec) {
@@ -216,20 +216,20 @@ inline int pick_m(int gpus) {
   return (gpus == 1 || gpus == 2 || gpus == 4 || gpus == 8 || gpus == 16) ? gpus : 0;
 }
 
-template <int IN, int OUT, int M, bool FAST>
-__global__ __launch_bounds__(kBlock) void k_reduce(ReduceProblem p) {
+template <int IN, int OUT, int M, bool FAST, int BLOCK>
+__global__ __launch_bounds__(BLOCK) void k_reduce(ReduceProblem p) {
   // grid.y = rows: the same reduction over `rows` strided rows of every source
   const size_t row = blockIdx.y;
   p.base += row * p.row_stride_src;
   p.src_offset += row * p.row_stride_src;
   p.dst = reinterpret_cast<char*>(p.dst) + row * p.row_stride_dst;
-  reduce_tile<IN, OUT, M, words_for(M), FAST>(p, linear_block_xz());
+  reduce_tile<IN, OUT, M, words_for(M), FAST, BLOCK>(p, linear_block_xz());
 }
 
-inline size_t tiles_for(size_t count, int m, bool in_narrow) {
+inline size_t tiles_for(size_t count, int m, bool in_narrow, int block = kBlock) {
   const size_t ve = (size_t)words_for(m) * (in_narrow ? 2 : 1);
   const size_t nvec = count / ve;
-  const size_t t = (nvec + kBlock - 1) / kBlock;
+  const size_t t = (nvec + block - 1) / block;
   return t == 0 ? 1 : t;  // a lone ragged tail still needs one block
 }
 
@@ -243,18 +243,28 @@ inline bool fast_eligible(const ReduceProblem& p, bool in_narrow) {
          (p.partial == nullptr || (is16(p.partial) && (p.count * es) % 16 == 0));
 }
 
-template <int IN, int OUT, int M>
-hipError_t launch_m(const ReduceProblem& p, hipStream_t st) {
-  const size_t tiles = tiles_for(p.count, M, narrow(IN));
+template <int IN, int OUT, int M, int BLOCK>
+hipError_t launch_mb(const ReduceProblem& p, hipStream_t st) {
+  const size_t tiles = tiles_for(p.count, M, narrow(IN), BLOCK);
   unsigned gx, gz;
-  if (p.rows < 1 || p.rows > 65535 || !split_grid_xz(tiles, kBlock, &gx, &gz)) return hipErrorInvalidValue;
+  if (p.rows < 1 || p.rows > 65535 || !split_grid_xz(tiles, BLOCK, &gx, &gz)) return hipErrorInvalidValue;
   if (p.rows > 1 && p.partial != nullptr) return hipErrorInvalidValue;
   const dim3 grid(gx, (unsigned)p.rows, gz);  // tiles past the last one find nothing to do
   if (fast_eligible(p, narrow(IN)))
-    hipLaunchKernelGGL((k_reduce<IN, OUT, M, true>), grid, dim3(kBlock), 0, st, p);
+    hipLaunchKernelGGL((k_reduce<IN, OUT, M, true, BLOCK>), grid, dim3(BLOCK), 0, st, p);
   else
-    hipLaunchKernelGGL((k_reduce<IN, OUT, M, false>), grid, dim3(kBlock), 0, st, p);
+    hipLaunchKernelGGL((k_reduce<IN, OUT, M, false, BLOCK>), grid, dim3(BLOCK), 0, st, p);
   return hipGetLastError();
+}
+
+template <int IN, int OUT, int M>
+hipError_t launch_m(const ReduceProblem& p, hipStream_t st) {
+  // bytes the launch reads: small launches take two-wavefront blocks
+  const size_t es = narrow(IN) ? 2 : 4;
+  const size_t sources = (size_t)p.nodes * (size_t)p.gpus;
+  const size_t per_source = p.count * es * (size_t)p.rows;
+  const bool small = per_source < kSmallLaunchBytes / (sources == 0 ? 1 : sources);
+  return small ? launch_mb<IN, OUT, M, kBlockSmall>(p, st) : launch_mb<IN, OUT, M, kBlock>(p, st);
 }
 
 template <int IN, int OUT>
@@ -528,7 +538,7 @@ __global__ __launch_bounds__(kBlock) void k_rs_batched(const pccl_bucket_t* __re
     p.count = b.chunk_count;
     p.gpus = nodes;
   }
-  reduce_tile<DT, DT, M, words_for(M), FAST>(p, block - tiles.first_tile[lo]);
+  reduce_tile<DT, DT, M, words_for(M), FAST, kBlock>(p, block - tiles.first_tile[lo]);
 }
 
 template <int DT, int M, int PHASE>

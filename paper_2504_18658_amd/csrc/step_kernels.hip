@@ -15,14 +15,14 @@ namespace pccl {
 
 namespace {
 
-template <int DT, bool FAST>
-__global__ __launch_bounds__(kBlock) void k_accumulate(char* acc, const char* recv, size_t count) {
+template <int DT, bool FAST, int BLOCK>
+__global__ __launch_bounds__(BLOCK) void k_accumulate(char* acc, const char* recv, size_t count) {
   constexpr int W = 4;
   constexpr int VE = narrow(DT) ? 2 * W : W;
   constexpr int ES = narrow(DT) ? 2 : 4;
   const size_t nvec = count / VE;
   const size_t block = linear_block_xz();
-  const size_t v = block * kBlock + threadIdx.x;
+  const size_t v = block * BLOCK + threadIdx.x;
   if (v < nvec) {
     const size_t off = v * (4 * W);
     uint32_t a[W], r[W], o[W];
@@ -38,7 +38,7 @@ __global__ __launch_bounds__(kBlock) void k_accumulate(char* acc, const char* re
     st_words<W, ES, FAST>(acc, off, o);
   }
   // ragged tail: fewer than VE <= 8 elements, taken by the last block that holds vectors
-  if (block == (nvec == 0 ? 0 : (nvec - 1) / kBlock)) {
+  if (block == (nvec == 0 ? 0 : (nvec - 1) / BLOCK)) {
     const size_t e = nvec * VE + threadIdx.x;
     if (e < count) st_elem<DT>(acc, e, ld_elem<DT>(acc, e) + ld_elem<DT>(recv, e));
   }
@@ -46,19 +46,28 @@ __global__ __launch_bounds__(kBlock) void k_accumulate(char* acc, const char* re
 
 inline bool is16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
-template <int DT>
-hipError_t launch_acc(char* acc, const char* recv, size_t count, hipStream_t st) {
+template <int DT, int BLOCK>
+hipError_t launch_acc_b(char* acc, const char* recv, size_t count, hipStream_t st) {
   constexpr size_t VE = narrow(DT) ? 8 : 4;
   const size_t nvec = count / VE;
-  size_t blocks = (nvec + kBlock - 1) / kBlock;
+  size_t blocks = (nvec + BLOCK - 1) / BLOCK;
   if (blocks == 0) blocks = 1;  // a lone ragged tail still needs one block
   unsigned gx, gz;
-  if (!split_grid_xz(blocks, kBlock, &gx, &gz)) return hipErrorInvalidValue;
+  if (!split_grid_xz(blocks, BLOCK, &gx, &gz)) return hipErrorInvalidValue;
   if (is16(acc) && is16(recv))
-    hipLaunchKernelGGL((k_accumulate<DT, true>), dim3(gx, 1, gz), dim3(kBlock), 0, st, acc, recv, count);
+    hipLaunchKernelGGL((k_accumulate<DT, true, BLOCK>), dim3(gx, 1, gz), dim3(BLOCK), 0, st, acc, recv, count);
   else
-    hipLaunchKernelGGL((k_accumulate<DT, false>), dim3(gx, 1, gz), dim3(kBlock), 0, st, acc, recv, count);
+    hipLaunchKernelGGL((k_accumulate<DT, false, BLOCK>), dim3(gx, 1, gz), dim3(BLOCK), 0, st, acc, recv, count);
   return hipGetLastError();
+}
+
+// Two streams only: here the two-wavefront block is the better one for large buffers (244
+// against 252 us at 512 MB += 512 MB) and the four-wavefront block for small ones.
+template <int DT>
+hipError_t launch_acc(char* acc, const char* recv, size_t count, hipStream_t st) {
+  const size_t bytes = count * (narrow(DT) ? 2 : 4);
+  return bytes < ((size_t)32 << 20) ? launch_acc_b<DT, kBlock>(acc, recv, count, st)
+                                    : launch_acc_b<DT, kBlockSmall>(acc, recv, count, st);
 }
 
 }  // namespace
