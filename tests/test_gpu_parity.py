@@ -670,3 +670,40 @@ def test_batched_reassembly_of_the_zero3_bucket_list_full_size():
     for k in sorted(range(len(sizes)), key=lambda j: sizes[j])[:3]:
         dst, src = pairs[k]
         assert same_bits(to_np(dst), oracle.hier_unpack(to_np(src), w.nodes, w.gpus)), k
+
+
+@pytest.mark.parametrize("dst_off", [0, 16, 48, 112, 512, 1008, 1023, 1024 + 16, 7])
+@pytest.mark.parametrize("src_off", [0, 16, 100])
+def test_shuffle_tiles_cut_at_destination_boundaries(dst_off, src_off):
+    """Tiles are cut at 1 KB boundaries of the destination address: every combination of
+    destination misalignment, source misalignment and chunk size around the tile size must
+    still move every byte exactly once (single, pointer-array and batched forms)."""
+    nodes, gpus = 2, 3
+    P = nodes * gpus
+    sizes = [1, 16, 1000, 1024, 1040, 2048, 3000, 5000, 1024 - 16]
+    pairs, wants, outs = [], [], []
+    for k, cb in enumerate(sizes):
+        src_h = W.random_bits16((P * cb + 1) // 2 + 64, 900 + k).view(torch.uint8)[src_off:src_off + P * cb]
+        src = src_h.to(DEV)                       # a fresh allocation: shift it to the wanted misalignment
+        raw = torch.empty(P * cb + 256, dtype=torch.uint8, device=DEV)
+        src = raw[src_off:src_off + P * cb].copy_(src)
+        out = Guarded((P * cb + dst_off) // 4 + 8, F32)
+        dst = out.view.view(torch.uint8)[dst_off:dst_off + P * cb]
+        want = oracle.hier_unpack(src_h.numpy(), nodes, gpus)
+        pccl.pccl_hier_unpack(dst, src, nodes, gpus)
+        _sync()
+        assert same_bits(to_np(dst), want), (cb, first_diff(to_np(dst), want))
+        out.check()
+        dst.zero_()
+        slots = pccl.device_pointer_array([src[j * cb:(j + 1) * cb] for j in range(P)])
+        pccl.pccl_allgather_reassemble(dst, d_slots=slots, nodes=nodes, gpus_per_node=gpus)
+        _sync()
+        assert same_bits(to_np(dst), want), ("slots", cb)
+        out.check()
+        dst.zero_()
+        pairs.append((dst, src)); wants.append(want); outs.append(out)
+    pccl.pccl_allgather_reassemble_batched(pccl.PermuteTable(pairs, nodes, gpus))
+    _sync()
+    for (dst, _), want, out, cb in zip(pairs, wants, outs, sizes):
+        assert same_bits(to_np(dst), want), ("batched", cb)
+        out.check()
