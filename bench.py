@@ -184,6 +184,29 @@ def other_workloads(dev):
               *time_calls([lambda s=s: pccl.pccl_reduce_scatter_local(s[0], s[1], s[2], d_inter=s[3], my_node=5,
                                                                       average=avg) for s in sets]))
         del sets
+    # a DDP gradient bucket (Section II-A: 48-80 MB of fp32 gradients per all-reduce): one rank's share of
+    # a two-level all-reduce of a 64 MB fp32 bucket at 128 nodes x 8 GPUs (64 KB chunks)
+    n_nodes, n_gpus, c = 128, 8, 16384
+    P = n_nodes * n_gpus
+    sets = []
+    for k in range(8):
+        msg = W.normal(P * c, 600 + k, 1e-3, dev)
+        x = W.normal(n_gpus * n_nodes * c, 610 + k, 1e-3, dev).view(n_gpus, n_nodes, c)
+        inter = W.normal(n_nodes * c, 620 + k, 1e-3, dev).view(n_nodes, c)
+        sets.append(dict(msg=msg, packed=torch.empty_like(msg), x=x, inter=inter,
+                         d_inter=pccl.device_pointer_array([inter[j] for j in range(n_nodes)]),
+                         partial=torch.empty(n_nodes * c, device=dev), shard=torch.empty(c, device=dev),
+                         gathered=W.normal(P * c, 630 + k, 1e-3, dev), out=torch.empty(P * c, device=dev)))
+
+    def ddp_share(s):
+        pccl.pccl_hier_pack(s["packed"], s["msg"], n_nodes, n_gpus)
+        pccl.pccl_reduce_scatter_local(s["shard"], s["partial"], s["x"], d_inter=s["d_inter"], my_node=77, average=True)
+        pccl.pccl_allgather_reassemble(s["out"], src=s["gathered"], nodes=n_nodes, gpus_per_node=n_gpus)
+
+    ddp_bytes = 2 * P * c * 4 + (n_gpus + 1) * n_nodes * c * 4 + (n_nodes + 1) * c * 4 + 2 * P * c * 4
+    entry("ddp_bucket_64MB_f32_allreduce_share_128x8_average", ddp_bytes,
+          *time_calls([lambda s=s: ddp_share(s) for s in sets], trials=16, warm=8), launches_per_call=4)
+    del sets
     # the paper's literal two-source step (acc += recv) and one rank's replay of its inter-node algorithms
     w = W.cfg3()
     n = 64 * MB                                                     # 128 MB of bf16
