@@ -29,6 +29,19 @@
  *   Errors     A status code is returned; nothing throws or aborts.  All argument checks
  *              run on the host before the first HIP call, so a rejected call has no side
  *              effect.  A failed launch is reported as PCCL_ERR_HIP.
+ *   Checked    Raw pointers cannot be checked for free, and a kernel given a host pointer
+ *              or a range longer than its allocation takes a GPU memory fault.  With the
+ *              environment variable PCCL_CHECK_POINTERS=1 every call, once its arguments
+ *              have passed the checks above, asks the HIP runtime whether each range the
+ *              host can see lies inside ONE allocation that kernels can address (device,
+ *              managed or pinned host memory) and returns PCCL_ERR_ADDRESS instead of
+ *              launching when one does not; the device-resident pointer arrays and
+ *              descriptor tables are checked as ranges only.  PCCL_CHECK_POINTERS=2 also
+ *              copies those arrays back on `stream`, WAITS for the stream, checks every
+ *              pointer in them and compares a descriptor table with its host mirror
+ *              (PCCL_ERR_INVALID when they differ): not for use under graph capture.  About
+ *              a microsecond per range; off when unset or 0.  Memory handed out by a
+ *              caching sub-allocator is checked against the block it was carved from.
  *   Empty      count == 0 / chunk_bytes == 0 / chunk_count == 0 / nbuckets == 0 succeed
  *              and launch nothing.
  *   Alignment  Any element-aligned pointer is accepted.  Pointers, strides and chunk sizes
@@ -66,7 +79,8 @@ typedef enum {
   PCCL_ERR_INVALID = 2,     /* a count, stride, index or size is out of range or overflows */
   PCCL_ERR_UNSUPPORTED = 3, /* unknown dtype, dtype pair or op */
   PCCL_ERR_OVERLAP = 4,     /* an output range overlaps an input range */
-  PCCL_ERR_HIP = 5          /* the HIP runtime refused a launch */
+  PCCL_ERR_HIP = 5,         /* the HIP runtime refused a launch */
+  PCCL_ERR_ADDRESS = 6      /* checked mode: a range is not inside one reachable allocation */
 } pccl_status_t;
 
 /* fp32, bf16 and fp16 (IEEE binary16) elements.  Where an entry point takes an input and an
@@ -292,6 +306,11 @@ double pccl_model_two_level(int nodes, int gpus_per_node, double m_bytes, pccl_a
                             double alpha_inter_s, double beta_inter_s_per_byte,
                             double alpha_intra_s, double beta_intra_s_per_byte,
                             double local_bytes, double hbm_bytes_per_s);
+
+/* The test behind PCCL_CHECK_POINTERS, callable on its own (it launches nothing): PCCL_OK when
+ * [ptr, ptr + bytes) lies inside one allocation that kernels of the current device can address
+ * or bytes == 0, PCCL_ERR_NULL for NULL with bytes > 0, else PCCL_ERR_ADDRESS. */
+pccl_status_t pccl_check_device_range(const void* ptr, size_t bytes);
 
 /* Static, human-readable name of a status code (never NULL). */
 const char* pccl_status_string(pccl_status_t status);

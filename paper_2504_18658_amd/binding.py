@@ -11,7 +11,7 @@ import torch
 
 from . import build as _build
 
-PCCL_OK, PCCL_ERR_NULL, PCCL_ERR_INVALID, PCCL_ERR_UNSUPPORTED, PCCL_ERR_OVERLAP, PCCL_ERR_HIP = range(6)
+PCCL_OK, PCCL_ERR_NULL, PCCL_ERR_INVALID, PCCL_ERR_UNSUPPORTED, PCCL_ERR_OVERLAP, PCCL_ERR_HIP, PCCL_ERR_ADDRESS = range(7)
 PCCL_F32, PCCL_BF16, PCCL_F16 = 0, 1, 2
 PCCL_SUM, PCCL_AVG = 0, 1
 PCCL_MAX_BUCKETS = 512
@@ -22,7 +22,7 @@ EXPORTS = (
     "pccl_allgather_reassemble", "pccl_reduce_scatter_local_batched", "pccl_accumulate",
     "pccl_reduce_scatter_local_unpacked", "pccl_ring_reduce_scatter_local",
     "pccl_allgather_reassemble_batched", "pccl_hier_pack_batched", "pccl_halving_reduce_scatter_local", "pccl_model_ring", "pccl_model_rec",
-    "pccl_choose_algorithm", "pccl_model_two_level", "pccl_status_string",
+    "pccl_choose_algorithm", "pccl_model_two_level", "pccl_status_string", "pccl_check_device_range",
 )
 PCCL_ALGO_RING, PCCL_ALGO_REC = 0, 1
 _NO_STATUS = ("pccl_status_string", "pccl_model_ring", "pccl_model_rec", "pccl_model_two_level")
@@ -85,6 +85,7 @@ def lib():
         for name in EXPORTS:
             if name not in _NO_STATUS:
                 getattr(L, name).restype = i
+        L.pccl_check_device_range.argtypes = [vp, ctypes.c_size_t]
         L.pccl_status_string.argtypes = [i]
         L.pccl_status_string.restype = ctypes.c_char_p
         _lib = L
@@ -93,6 +94,15 @@ def lib():
 
 def status_string(status):
     return lib().pccl_status_string(int(status)).decode()
+
+
+def pccl_check_device_range(ptr, nbytes=None):
+    """Status of the library's reachability test for a tensor (its own extent) or for a raw
+    address and byte count; launches nothing."""
+    if isinstance(ptr, torch.Tensor):
+        nbytes = ptr.numel() * ptr.element_size() if nbytes is None else nbytes
+        ptr = ptr.data_ptr()
+    return lib().pccl_check_device_range(ctypes.c_void_p(ptr), int(nbytes))
 
 
 def _check(status, where):

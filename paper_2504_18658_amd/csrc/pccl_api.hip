@@ -1,9 +1,12 @@
 // C ABI of libpccl_local.so: argument checks on the host, then kernel launches on the
 // caller's stream.  Every check runs before the first HIP call, so a rejected call has no
-// side effect and the error paths can be exercised on a machine without a GPU.
+// side effect and the error paths can be exercised on a machine without a GPU.  With
+// PCCL_CHECK_POINTERS set, a call that passed those checks then asks the runtime whether every
+// range lies inside memory a kernel can reach, and launches only if so.
 #include <cstdlib>
 
 #include "../../include/pccl_local.h"
+#include "address_check.h"
 #include "kernels.h"
 
 namespace {
@@ -29,6 +32,27 @@ inline bool overlaps(const void* a, size_t la, const void* b, size_t lb) {
 }
 
 inline pccl_status_t from_hip(hipError_t e) { return e == hipSuccess ? PCCL_OK : PCCL_ERR_HIP; }
+
+// Opt-in address checks of one call: the first failure is kept.
+struct AddressChecks {
+  int level;
+  hipStream_t st;
+  pccl_status_t status;
+  explicit AddressChecks(pccl_stream_t stream)
+      : level(pccl::address_check_level()), st(reinterpret_cast<hipStream_t>(stream)), status(PCCL_OK) {}
+  bool on() const { return level > 0; }
+  void range(const void* p, size_t bytes) {
+    if (level > 0 && status == PCCL_OK) status = pccl::check_range(p, bytes);
+  }
+  void pointers(const void* const* d_table, size_t n, size_t offset, size_t bytes_each, long long skip = -1) {
+    if (level > 0 && status == PCCL_OK)
+      status = pccl::check_pointer_table(d_table, n, offset, bytes_each, skip, level, st);
+  }
+  void descriptors(const void* d_table, const void* h_table, size_t bytes) {
+    if (level > 0 && status == PCCL_OK)
+      status = pccl::check_descriptor_table(d_table, h_table, bytes, level, st);
+  }
+};
 
 ReduceProblem blank_problem() {
   ReduceProblem p;
@@ -85,6 +109,15 @@ pccl_status_t permute_common(void* dst, const void* src, const void* const* slot
   if (!mul_ok(chunks, chunk_bytes, &total)) return PCCL_ERR_INVALID;
   if (slots == nullptr && overlaps(dst, total, src, total)) return PCCL_ERR_OVERLAP;
   if (chunk_bytes == 0) return PCCL_OK;
+  AddressChecks ck(stream);
+  if (ck.on()) {
+    ck.range(dst, total);
+    if (slots == nullptr)
+      ck.range(src, total);
+    else
+      ck.pointers(slots, chunks, 0, chunk_bytes);
+    if (ck.status != PCCL_OK) return ck.status;
+  }
   PermuteProblem p;
   p.dst = reinterpret_cast<char*>(dst);
   p.src = reinterpret_cast<const char*>(src);
@@ -150,6 +183,15 @@ pccl_status_t permute_batched_common(const pccl_permute_bucket_t* d_buckets,
     any = true;
   }
   if (!any) return PCCL_OK;
+  AddressChecks ck(stream);
+  if (ck.on()) {
+    ck.descriptors(d_buckets, h_buckets, (size_t)nbuckets * sizeof(pccl_permute_bucket_t));
+    for (int b = 0; b < nbuckets; ++b) {
+      ck.range(h_buckets[b].dst, chunks * h_buckets[b].chunk_bytes);
+      ck.range(h_buckets[b].src, chunks * h_buckets[b].chunk_bytes);
+    }
+    if (ck.status != PCCL_OK) return ck.status;
+  }
   const hipError_t e = pccl::launch_permute_batched(d_buckets, h_buckets, nbuckets, rows, cols,
                                                     reinterpret_cast<hipStream_t>(stream));
   return e == hipErrorInvalidValue ? PCCL_ERR_INVALID : from_hip(e);
@@ -176,6 +218,12 @@ pccl_status_t pccl_local_reduce(void* dst, const void* src_base, size_t src_stri
     return PCCL_ERR_INVALID;
   if (overlaps(dst, out_bytes, src_base, span)) return PCCL_ERR_OVERLAP;
   if (count == 0) return PCCL_OK;
+  AddressChecks ck(stream);
+  if (ck.on()) {
+    ck.range(dst, out_bytes);
+    ck.range(src_base, span);
+    if (ck.status != PCCL_OK) return ck.status;
+  }
   ReduceProblem p = blank_problem();
   p.dst = dst;
   p.base = reinterpret_cast<const char*>(src_base);
@@ -198,6 +246,12 @@ pccl_status_t pccl_local_reduce_ptrs(void* dst, const void* const* d_srcs, int n
     return PCCL_ERR_INVALID;
   if (!elem_aligned(dst, esize(out_dt))) return PCCL_ERR_INVALID;
   if (count == 0) return PCCL_OK;
+  AddressChecks ck(stream);
+  if (ck.on()) {
+    ck.range(dst, count * esize(out_dt));
+    ck.pointers(d_srcs, (size_t)nsrc, 0, count * esize(in_dt));
+    if (ck.status != PCCL_OK) return ck.status;
+  }
   ReduceProblem p = blank_problem();
   p.dst = dst;
   p.ptrs = d_srcs;
@@ -225,6 +279,12 @@ pccl_status_t pccl_local_reduce_ptrs_two_level(void* dst, const void* const* d_s
     return PCCL_ERR_INVALID;
   if (!elem_aligned(dst, esize(out_dt))) return PCCL_ERR_INVALID;
   if (count == 0) return PCCL_OK;
+  AddressChecks ck(stream);
+  if (ck.on()) {
+    ck.range(dst, count * esize(out_dt));
+    ck.pointers(d_srcs, ranks, 0, count * esize(in_dt));
+    if (ck.status != PCCL_OK) return ck.status;
+  }
   ReduceProblem p = blank_problem();
   p.dst = dst;
   p.ptrs = d_srcs;
@@ -304,6 +364,14 @@ pccl_status_t pccl_reduce_scatter_local(void* shard, void* partial, const void* 
       overlaps(shard, chunk_bytes, partial, piece_bytes))
     return PCCL_ERR_OVERLAP;
   if (chunk_count == 0) return PCCL_OK;
+  AddressChecks ck(stream);
+  if (ck.on()) {
+    ck.range(shard, chunk_bytes);
+    ck.range(partial, piece_bytes);
+    ck.range(intra_base, span);
+    if (d_inter != nullptr) ck.pointers(d_inter, (size_t)nodes, 0, chunk_bytes, my_node);
+    if (ck.status != PCCL_OK) return ck.status;
+  }
   const int dt = io_dt;
   const float divisor = divisor_for(op, (size_t)nodes * (size_t)gpus_per_node);
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
@@ -357,6 +425,17 @@ pccl_status_t pccl_reduce_scatter_local_unpacked(void* shard, void* partial, con
       return PCCL_ERR_OVERLAP;
   }
   if (chunk_count == 0) return PCCL_OK;
+  AddressChecks ck(stream);
+  if (ck.on()) {
+    ck.range(shard, chunk_bytes);
+    ck.range(partial, piece_bytes);
+    if (d_msgs == nullptr)
+      ck.range(msgs_base, span);
+    else
+      ck.pointers(d_msgs, (size_t)gpus_per_node, 0, msg_bytes);
+    if (d_inter != nullptr) ck.pointers(d_inter, (size_t)nodes, 0, chunk_bytes, my_node);
+    if (ck.status != PCCL_OK) return ck.status;
+  }
   const int dt = io_dt;
   const float divisor = divisor_for(op, (size_t)nodes * (size_t)gpus_per_node);
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
@@ -420,6 +499,19 @@ pccl_status_t pccl_reduce_scatter_local_batched(const pccl_bucket_t* d_buckets,
     any = true;
   }
   if (!any) return PCCL_OK;
+  AddressChecks ck(stream);
+  if (ck.on()) {
+    ck.descriptors(d_buckets, h_buckets, (size_t)nbuckets * sizeof(pccl_bucket_t));
+    for (int b = 0; b < nbuckets; ++b) {
+      const pccl_bucket_t& k = h_buckets[b];
+      if (k.chunk_count == 0) continue;
+      const size_t piece_bytes = (size_t)nodes * k.chunk_count * es;
+      ck.range(k.shard, k.chunk_count * es);
+      ck.range(k.partial, piece_bytes);
+      ck.range(k.intra_base, (size_t)(gpus_per_node - 1) * (gpus_per_node > 1 ? k.intra_stride_bytes : 0) + piece_bytes);
+    }
+    if (ck.status != PCCL_OK) return ck.status;
+  }
   const hipError_t e =
       pccl::launch_rs_batched(d_buckets, h_buckets, nbuckets, nodes, gpus_per_node, io_dt,
                               divisor_for(op, (size_t)nodes * (size_t)gpus_per_node),
@@ -437,6 +529,12 @@ pccl_status_t pccl_accumulate(void* acc, const void* recv, size_t count, pccl_dt
   if (!mul_ok(count, es, &bytes)) return PCCL_ERR_INVALID;
   if (!elem_aligned(acc, es) || !elem_aligned(recv, es)) return PCCL_ERR_INVALID;
   if (overlaps(acc, bytes, recv, bytes)) return PCCL_ERR_OVERLAP;
+  AddressChecks ck(stream);
+  if (ck.on()) {
+    ck.range(acc, bytes);
+    ck.range(recv, bytes);
+    if (ck.status != PCCL_OK) return ck.status;
+  }
   const hipError_t e = pccl::launch_accumulate(acc, recv, count, io_dt,
                                                reinterpret_cast<hipStream_t>(stream));
   return e == hipErrorInvalidValue ? PCCL_ERR_INVALID : from_hip(e);
@@ -463,6 +561,12 @@ pccl_status_t pccl_ring_reduce_scatter_local(void* msg, const void* recv_base,
     return PCCL_ERR_INVALID;
   if (steps > 0 && overlaps(msg, msg_bytes, recv_base, span)) return PCCL_ERR_OVERLAP;
   if (chunk_count == 0) return PCCL_OK;
+  AddressChecks ck(stream);
+  if (ck.on()) {
+    ck.range(msg, msg_bytes);
+    if (steps > 0) ck.range(recv_base, span);
+    if (ck.status != PCCL_OK) return ck.status;
+  }
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   for (int s = 0; s < steps; ++s) {
     // rank r forwards chunk r-1 first; what arrives at step s is chunk r-2-s, further reduced
@@ -491,6 +595,12 @@ pccl_status_t pccl_halving_reduce_scatter_local(void* msg, const void* recv, int
   if (!elem_aligned(msg, es) || !elem_aligned(recv, es)) return PCCL_ERR_INVALID;
   if (nranks > 1 && overlaps(msg, msg_bytes, recv, msg_bytes - chunk_bytes)) return PCCL_ERR_OVERLAP;
   if (chunk_count == 0) return PCCL_OK;
+  AddressChecks ck(stream);
+  if (ck.on()) {
+    ck.range(msg, msg_bytes);
+    ck.range(recv, msg_bytes - chunk_bytes);
+    if (ck.status != PCCL_OK) return ck.status;
+  }
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   size_t lo = 0, len = (size_t)nranks, recv_off = 0;  // active chunk range, received chunks so far
   for (int dist = nranks >> 1; dist >= 1; dist >>= 1) {
@@ -506,6 +616,10 @@ pccl_status_t pccl_halving_reduce_scatter_local(void* msg, const void* recv, int
   return PCCL_OK;
 }
 
+pccl_status_t pccl_check_device_range(const void* ptr, size_t bytes) {
+  return pccl::check_range(ptr, bytes);
+}
+
 const char* pccl_status_string(pccl_status_t status) {
   switch (status) {
     case PCCL_OK: return "PCCL_OK";
@@ -514,6 +628,8 @@ const char* pccl_status_string(pccl_status_t status) {
     case PCCL_ERR_UNSUPPORTED: return "PCCL_ERR_UNSUPPORTED: unknown dtype, dtype pair or reduction op";
     case PCCL_ERR_OVERLAP: return "PCCL_ERR_OVERLAP: an output range overlaps an input range";
     case PCCL_ERR_HIP: return "PCCL_ERR_HIP: the HIP runtime refused a kernel launch";
+    case PCCL_ERR_ADDRESS:
+      return "PCCL_ERR_ADDRESS: a range is not inside one allocation kernels can reach (checked mode)";
   }
   return "PCCL: unknown status";
 }

@@ -300,3 +300,21 @@ def test_batched_permute_rejects_bad_arguments(name):
     empty = (pccl.pccl_permute_bucket_t * 2)(pccl.pccl_permute_bucket_t(None, None, 0),
                                              pccl.pccl_permute_bucket_t(None, None, 0))
     assert f(A, ctypes.addressof(empty), 2, 4, 8, None) == pccl.PCCL_OK    # only empty buckets: no launch
+
+
+def test_checked_mode_refuses_addresses_no_kernel_can_reach(monkeypatch):
+    """With PCCL_CHECK_POINTERS set, made-up addresses are refused before any launch."""
+    L = binding.lib()
+    assert L.pccl_check_device_range(None, 0) == pccl.PCCL_OK
+    assert L.pccl_check_device_range(None, 16) == pccl.PCCL_ERR_NULL
+    assert L.pccl_check_device_range(0x10000, 16) == pccl.PCCL_ERR_ADDRESS
+    monkeypatch.setenv("PCCL_CHECK_POINTERS", "1")
+    a, b = 0x10000000, 0x20000000
+    assert L.pccl_local_reduce(a, b, 4096, 2, 1024, pccl.PCCL_F32, pccl.PCCL_F32, pccl.PCCL_SUM, None) == pccl.PCCL_ERR_ADDRESS
+    assert L.pccl_accumulate(a, b, 1024, pccl.PCCL_BF16, pccl.PCCL_SUM, None) == pccl.PCCL_ERR_ADDRESS
+    assert L.pccl_hier_pack(a, b, 4, 2, 256, None) == pccl.PCCL_ERR_ADDRESS
+    assert L.pccl_local_reduce_ptrs(a, b, 4, 1024, pccl.PCCL_F32, pccl.PCCL_F32, pccl.PCCL_SUM, None) == pccl.PCCL_ERR_ADDRESS
+    # argument errors still come first, and empty problems still succeed
+    assert L.pccl_local_reduce(a, b, 4096, 0, 1024, pccl.PCCL_F32, pccl.PCCL_F32, pccl.PCCL_SUM, None) == pccl.PCCL_ERR_INVALID
+    assert L.pccl_local_reduce(a, b, 4096, 2, 0, pccl.PCCL_F32, pccl.PCCL_F32, pccl.PCCL_SUM, None) == pccl.PCCL_OK
+    assert "ADDRESS" in pccl.status_string(pccl.PCCL_ERR_ADDRESS)
