@@ -63,6 +63,11 @@ hipError_t launch_reduce_two_level_lds(const ReduceProblem& p, int in_dt, int ou
                                        hipStream_t st);
 // True when the LDS-staged kernel is the better choice for this shape.
 bool prefer_lds_two_level(const ReduceProblem& p, int in_dt);
+// A flat sum written as p.nodes sources (p.gpus == 1, one row, no partial kept) through the
+// LDS-staged flat kernel: every load of an element slice in flight at once.
+hipError_t launch_reduce_flat_lds(const ReduceProblem& p, int in_dt, int out_dt, hipStream_t st);
+// True when that kernel is the better choice for a flat sum of p.nodes sources.
+bool prefer_flat_lds(const ReduceProblem& p, int in_dt);
 
 // nbuckets chunk transposes (dst chunk c*rows + r = src chunk r*cols + c in every bucket) in
 // one launch; h_buckets is the host copy used to size the grid.

@@ -129,17 +129,22 @@ pccl_status_t permute_common(void* dst, const void* src, const void* const* slot
   return e == hipErrorInvalidValue ? PCCL_ERR_INVALID : from_hip(e);
 }
 
-// A flat sum (p.nodes == 1, p.gpus sources).  A long chain over short buffers leaves the
-// streaming kernel with too few threads; a flat sum is the two-level sum with one GPU per
-// node, so the LDS-staged kernel takes it and overlaps the loads of many sources.
+// A flat sum (p.nodes == 1, p.gpus sources).  Beyond 16 sources the streaming kernel walks
+// them batch after batch with too few loads in flight for short sources; the LDS-staged flat
+// kernel then keeps every load of an element slice in flight at once.
 hipError_t launch_flat(const ReduceProblem& p, int in_dt, int out_dt, hipStream_t st) {
   ReduceProblem q = p;
   q.nodes = p.gpus;
   q.gpus = 1;
   q.stride_n = p.stride_g;
   q.stride_g = 0;
-  if (p.rows == 1 && p.partial == nullptr && pccl::prefer_lds_two_level(q, in_dt))
-    return pccl::launch_reduce_two_level_lds(q, in_dt, out_dt, st);
+  if (p.rows == 1 && p.partial == nullptr) {
+    int forced = 0;  // PCCL_FORCE_FLAT_KERNEL=stream|two-level|flat (A/B runs under the profiler)
+    if (const char* v = std::getenv("PCCL_FORCE_FLAT_KERNEL")) forced = v[0] == 's' ? 1 : v[0] == 't' ? 2 : v[0] == 'f' ? 3 : 0;
+    if (forced == 3 || (forced == 0 && pccl::prefer_flat_lds(q, in_dt)))
+      return pccl::launch_reduce_flat_lds(q, in_dt, out_dt, st);
+    if (forced == 2) return pccl::launch_reduce_two_level_lds(q, in_dt, out_dt, st);
+  }
   return pccl::launch_reduce(p, in_dt, out_dt, st);
 }
 

@@ -10,6 +10,8 @@
 //                       the per-node sums of one element slice are staged in LDS and a
 //                       final pass adds them in node order.
 // Both are HBM-bound: (sources - 1) adds per element against >= 2 bytes per operand.
+#include <cstdlib>
+
 #include "device_utils.h"
 #include "kernels.h"
 
@@ -513,6 +515,151 @@ hipError_t launch_lds_io(const ReduceProblem& p, hipStream_t st) {
 }
 
 // ------------------------------------------------------------------------------------------
+// LDS-staged FLAT sum of many sources (phase 2 at large node counts: N sources of a few
+// hundred KB each).  The streaming kernel has too few threads for such a shape and each walks
+// N sources one batch after another; here every load of a slice is in flight at once.
+//   block  = WAVES wavefronts, owns one slice of 64 consecutive 32-bit words (64 fp32 or 128
+//            16-bit elements) of every source;
+//   tile   = TN = WAVES * 8 consecutive sources: wave w loads its 8 sources' words (8 loads in
+//            flight per lane, each wavefront load one contiguous 256 bytes) and parks the RAW
+//            words in LDS -- in a flat sum the addend is the source value itself, so nothing
+//            is computed before the ordered pass;
+//   then wavefront 0 adds the parked words in ascending source order (two chains per lane
+//   for 16-bit elements), one tile behind the loads (the parking area is double-buffered).
+// The accumulator starts from source 0 and every add is sequential in source order, so the
+// result is bit-identical to the streaming kernel's.
+constexpr int kFlatNpt = 8;
+
+template <int IN, int OUT, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void k_flat_lds(ReduceProblem p) {
+  constexpr int EPL = narrow(IN) ? 2 : 1;
+  constexpr int TN = WAVES * kFlatNpt;
+  __shared__ uint32_t parked[2][TN * 64];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const size_t nwords = (p.count + EPL - 1) / EPL;  // a ragged last word counts
+  const size_t w0 = linear_block_xz() * 64;
+  if (w0 >= nwords) return;  // the x*z rectangle is rounded up: whole blocks past the end leave
+  const size_t le = (w0 + lane) * EPL;  // this lane's first element
+  const bool slice_full = (w0 + 64) * EPL <= p.count;  // block-uniform
+  const int nsrc = p.nodes;
+  const int ntiles = (nsrc + TN - 1) / TN;
+
+  // lane l < 8 of wave w holds the address of source tile*TN + w*8 + l
+  auto fetch = [&](int tile) -> uint64_t {
+    const int n = tile * TN + wave * kFlatNpt + lane;
+    return lds_lane_src(p, n, 0, 1, lane < kFlatNpt && n < nsrc);
+  };
+  // acc (+)= the tn parked words of this lane, ascending source order
+  float acc[EPL];
+  auto ordered = [&](const uint32_t* buf, int tn, bool first) {
+    int j = 0;
+    if (first) {
+      const uint32_t w = buf[lane];
+      if constexpr (narrow(IN)) {
+        acc[0] = lo16<IN>(w);
+        acc[1] = hi16<IN>(w);
+      } else {
+        acc[0] = __uint_as_float(w);
+      }
+      j = 1;
+    }
+#pragma unroll 8
+    for (; j < tn; ++j) {
+      const uint32_t w = buf[j * 64 + lane];
+      if constexpr (narrow(IN)) {
+        acc[0] = acc[0] + lo16<IN>(w);
+        acc[1] = acc[1] + hi16<IN>(w);
+      } else {
+        acc[0] = acc[0] + __uint_as_float(w);
+      }
+    }
+  };
+
+  uint64_t cur = fetch(0);
+  for (int k = 0; k < ntiles; ++k) {
+    const uint64_t nxt = k + 1 < ntiles ? fetch(k + 1) : 0;
+    const int nvalid = min(kFlatNpt, max(0, nsrc - (k * TN + wave * kFlatNpt)));  // wave-uniform
+    uint32_t raw[kFlatNpt];
+    if (nvalid == kFlatNpt && slice_full && !__any((int)(cur & 3))) {
+      // the whole trip without a check: 8 loads issue back to back
+#pragma unroll
+      for (int q = 0; q < kFlatNpt; ++q) raw[q] = ld_stream<uint32_t>(lane_pointer(cur, q) + 4 * (w0 + lane));
+    } else {
+#pragma unroll
+      for (int q = 0; q < kFlatNpt; ++q)
+        if (q < nvalid) {
+          const char* sp = lane_pointer(cur, q);
+          if constexpr (narrow(IN)) {
+            if (le + 1 < p.count && aligned_to(sp, 4)) {
+              raw[q] = ld_stream<uint32_t>(sp + 2 * le);
+            } else {
+              const uint32_t a = le < p.count ? ld_stream<uint16_t>(sp + 2 * le) : 0u;
+              const uint32_t b = le + 1 < p.count ? ld_stream<uint16_t>(sp + 2 * le + 2) : 0u;
+              raw[q] = a | (b << 16);
+            }
+          } else {
+            raw[q] = le < p.count ? ld_stream<uint32_t>(sp + 4 * le) : 0u;
+          }
+        }
+    }
+    // ordered sum of the previous tile while this tile's loads are in flight
+    if (wave == 0 && k > 0) ordered(parked[(k - 1) & 1], TN, k == 1);
+    uint32_t* buf = parked[k & 1];
+#pragma unroll
+    for (int q = 0; q < kFlatNpt; ++q)
+      if (q < nvalid) buf[(wave * kFlatNpt + q) * 64 + lane] = raw[q];
+    cur = nxt;
+    __syncthreads();
+  }
+  if (wave == 0) {
+    const int last = ntiles - 1;
+    ordered(parked[last & 1], nsrc - last * TN, last == 0);
+    if (p.divisor != 0.0f) {
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) acc[e] = acc[e] / p.divisor;
+    }
+    char* dst = reinterpret_cast<char*>(p.dst);
+    if constexpr (narrow(OUT) && narrow(IN)) {
+      if (slice_full && aligned_to(dst, 4)) {
+        st_stream<uint32_t>(dst + 2 * le, pack16<OUT>(acc[0], acc[1]));
+        return;
+      }
+    }
+#pragma unroll
+    for (int e = 0; e < EPL; ++e)
+      if (le + e < p.count) st_elem<OUT>(dst, le + e, acc[e]);
+  }
+}
+
+template <int IN, int OUT>
+hipError_t launch_flat_lds_io(const ReduceProblem& p, hipStream_t st) {
+  constexpr int EPL = narrow(IN) ? 2 : 1;
+  const size_t nwords = (p.count + EPL - 1) / EPL;
+  const size_t blocks = (nwords + 63) / 64;
+  if (p.gpus != 1 || p.rows != 1 || p.partial != nullptr) return hipErrorInvalidValue;
+  unsigned gx, gz;
+  // Block shape, measured over 2-512 MB of sources and 24-256 of them: four wavefronts (more
+  // blocks per CU, so that one block's ordered pass hides behind the others' loads) unless the
+  // sources are many and short, where sixteen put a whole slice's loads in flight at once.
+  const size_t src_bytes = p.count * (narrow(IN) ? 2 : 4);
+  int waves = (p.nodes <= 32 || src_bytes >= ((size_t)256 << 10)) ? 4 : (p.nodes <= 64 ? 8 : 16);
+  if (const char* v = std::getenv("PCCL_FLAT_WAVES")) {
+    const int w = std::atoi(v);
+    if (w == 4 || w == 8 || w == 16) waves = w;
+  }
+  if (!split_grid_xz(blocks, (unsigned)waves * 64, &gx, &gz)) return hipErrorInvalidValue;
+  const dim3 grid(gx, 1, gz), block((unsigned)waves * 64);
+  if (waves == 4)
+    hipLaunchKernelGGL((k_flat_lds<IN, OUT, 4>), grid, block, 0, st, p);
+  else if (waves == 8)
+    hipLaunchKernelGGL((k_flat_lds<IN, OUT, 8>), grid, block, 0, st, p);
+  else
+    hipLaunchKernelGGL((k_flat_lds<IN, OUT, 16>), grid, block, 0, st, p);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
 // batched two-level reduce-scatter share: a flat tile space over all buckets, one launch
 // per phase.  Each block finds its bucket by bisection in the tile prefix (kernel argument).
 template <int DT, int M, int PHASE, bool FAST>
@@ -632,6 +779,21 @@ hipError_t launch_reduce(const ReduceProblem& p, int in_dt, int out_dt, hipStrea
 hipError_t launch_reduce_two_level_lds(const ReduceProblem& p, int in_dt, int out_dt,
                                        hipStream_t st) {
   PCCL_DISPATCH_IO(launch_lds_io, in_dt, out_dt, p, st);
+}
+
+hipError_t launch_reduce_flat_lds(const ReduceProblem& p, int in_dt, int out_dt, hipStream_t st) {
+  PCCL_DISPATCH_IO(launch_flat_lds_io, in_dt, out_dt, p, st);
+}
+
+bool prefer_flat_lds(const ReduceProblem& p, int in_dt) {
+  // Up to 16 sources the streaming kernel keeps every load of a lane in flight (fully
+  // unrolled); beyond, it walks the sources in batches of four and needs long sources to hide
+  // that: measured equal to the LDS kernel from about 4 MB per source (24-31 sources) or
+  // 16 MB (more), 2-4 times slower at 64-512 KB per source.
+  const size_t src_bytes = p.count * (narrow(in_dt) ? 2 : 4);
+  if (p.gpus != 1 || p.nodes <= 16) return false;
+  if (src_bytes >= ((size_t)16 << 20)) return false;
+  return !(src_bytes >= ((size_t)4 << 20) && p.nodes < 32);
 }
 
 bool prefer_lds_two_level(const ReduceProblem& p, int in_dt) {
