@@ -68,12 +68,13 @@ inline size_t tiles_per_chunk_for(const void* dst, size_t chunk_bytes) {
 // resident blocks walk the destination contiguously and read from as many places as they span
 // source rows; with CFAST they walk the source contiguously and write to `cols` places.
 template <bool GRID3, bool CFAST>
-__global__ __launch_bounds__(kPermBlock) void k_permute(PermuteProblem p, uint32_t tiles_per_chunk) {
+__global__ __launch_bounds__(kPermBlock) void k_permute(PermuteProblem p, uint32_t tiles_per_chunk, uint32_t skew) {
   uint32_t tile, r, c;
   if (GRID3) {
     tile = blockIdx.x;
     r = CFAST ? blockIdx.z : blockIdx.y;
     c = CFAST ? blockIdx.y : blockIdx.z;
+    if (skew) tile = (uint32_t)(((uint64_t)tile + (uint64_t)(r + c) * skew) % tiles_per_chunk);
   } else {
     const uint32_t chunk = blockIdx.x / tiles_per_chunk;  // dst chunk = c*rows + r
     tile = blockIdx.x - chunk * tiles_per_chunk;
@@ -163,16 +164,22 @@ hipError_t launch_permute(const PermuteProblem& p, hipStream_t st) {
   if (p.rows <= 65535 && p.cols <= 65535) {
     bool cfast = column_fast_order(p);
     if (const char* v = std::getenv("PCCL_PERMUTE_ORDER")) cfast = v[0] == 's';  // "src" / "dst"
+    // Chunk (r, c) starts (r + c) * skew tiles into itself, modulo its tile count: the resident
+    // blocks otherwise sit at the same offset of several chunks a power of two apart.  Measured
+    // with 131 tiles: 1-7 % faster for chunks of 512 KB-1 MB (256 MB as 64x8: 85.8 -> 79.5 us,
+    // 128 MB as 32x8: 43.7 -> 40.9 us), no change from 2 MB up, slower below 256 KB.
+    uint32_t skew = p.chunk_bytes >= ((size_t)512 << 10) ? 131u : 0u;
+    if (const char* v = std::getenv("PCCL_PERMUTE_SKEW")) skew = (uint32_t)std::atoi(v);
     if (cfast)
       hipLaunchKernelGGL((k_permute<true, true>), dim3((unsigned)tiles_per_chunk, (unsigned)p.cols, (unsigned)p.rows),
-                         dim3(kPermBlock), 0, st, p, (uint32_t)tiles_per_chunk);
+                         dim3(kPermBlock), 0, st, p, (uint32_t)tiles_per_chunk, skew);
     else
       hipLaunchKernelGGL((k_permute<true, false>), dim3((unsigned)tiles_per_chunk, (unsigned)p.rows, (unsigned)p.cols),
-                         dim3(kPermBlock), 0, st, p, (uint32_t)tiles_per_chunk);
+                         dim3(kPermBlock), 0, st, p, (uint32_t)tiles_per_chunk, skew);
   } else {
     if (tiles_per_chunk * chunks > kPermMaxTilesX) return hipErrorInvalidValue;
     hipLaunchKernelGGL((k_permute<false, false>), dim3((unsigned)(tiles_per_chunk * chunks)), dim3(kPermBlock), 0,
-                       st, p, (uint32_t)tiles_per_chunk);
+                       st, p, (uint32_t)tiles_per_chunk, 0u);
   }
   return hipGetLastError();
 }

@@ -19,13 +19,20 @@ SHAPES = [(12, 3), (3, 12), (5, 5), (1, 7), (7, 1)]
 CHUNKS = [1000, 48 * KB + 16, 64 * KB, 200 * KB + 2, 512 * KB, 640 * KB + 48]
 
 
+@pytest.mark.parametrize("skew", [None, "0", "7", "131"])
 @pytest.mark.parametrize("order", ["dst", "src", None])
 @pytest.mark.parametrize("nodes,gpus", SHAPES)
-def test_pack_unpack_reassemble_in_either_block_order(monkeypatch, order, nodes, gpus):
+def test_pack_unpack_reassemble_in_either_block_order(monkeypatch, order, skew, nodes, gpus):
+    """`skew` rotates the tiles of chunk (r, c) by (r + c) * skew: None leaves the library's own
+    choice (on from 512 KB chunks), a number forces it for every chunk size below."""
     if order is None:
         monkeypatch.delenv("PCCL_PERMUTE_ORDER", raising=False)
     else:
         monkeypatch.setenv("PCCL_PERMUTE_ORDER", order)
+    if skew is None:
+        monkeypatch.delenv("PCCL_PERMUTE_SKEW", raising=False)
+    else:
+        monkeypatch.setenv("PCCL_PERMUTE_SKEW", skew)
     gen = torch.Generator()
     gen.manual_seed(nodes * 100 + gpus)
     P = nodes * gpus
