@@ -207,6 +207,39 @@ def other_workloads(dev):
     entry("ddp_bucket_64MB_f32_allreduce_share_128x8_average", ddp_bytes,
           *time_calls([lambda s=s: ddp_share(s) for s in sets], trials=16, warm=8), launches_per_call=4)
     del sets
+    # the headline message at the paper's scale (Section V-A runs up to 2048 GCDs): one rank's share
+    # of a two-level all-reduce of 256 MB of bf16 at 128 nodes x 8 GPUs (256 KB chunks), with the
+    # pre-shuffle and straight from the node-mates' rank-order messages
+    n_nodes, n_gpus = 128, 8
+    P = n_nodes * n_gpus
+    c = (256 << 20) // P // 2
+    sets = []
+    for k in range(3):
+        msgs = W.uniform_pm1(n_gpus * P * c, 700 + k, dev, torch.bfloat16).view(n_gpus, P * c)          # 8 x 256 MB
+        inter = W.uniform_pm1(n_nodes * c, 710 + k, dev, torch.bfloat16).view(n_nodes, c)
+        sets.append(dict(msgs=msgs, packed=torch.empty(P * c, dtype=torch.bfloat16, device=dev),
+                         x=msgs.view(-1)[: n_gpus * n_nodes * c].view(n_gpus, n_nodes, c), inter=inter,
+                         d_inter=pccl.device_pointer_array([inter[j] for j in range(n_nodes)]),
+                         partial=torch.empty(n_nodes * c, dtype=torch.bfloat16, device=dev),
+                         shard=torch.empty(c, dtype=torch.bfloat16, device=dev),
+                         out=torch.empty(P * c, dtype=torch.bfloat16, device=dev)))
+
+    def big_share(s):
+        pccl.pccl_hier_pack(s["packed"], s["msgs"][0], n_nodes, n_gpus)
+        pccl.pccl_reduce_scatter_local(s["shard"], s["partial"], s["x"], d_inter=s["d_inter"], my_node=77)
+        pccl.pccl_allgather_reassemble(s["out"], src=s["msgs"][1], nodes=n_nodes, gpus_per_node=n_gpus)
+
+    def big_share_unpacked(s):
+        pccl.pccl_reduce_scatter_local_unpacked(s["shard"], s["partial"], msgs=s["msgs"], d_inter=s["d_inter"],
+                                                nodes=n_nodes, gpus_per_node=n_gpus, my_node=77, my_gpu=3)
+        pccl.pccl_allgather_reassemble(s["out"], src=s["msgs"][1], nodes=n_nodes, gpus_per_node=n_gpus)
+
+    share_bytes = (n_gpus + 1) * n_nodes * c * 2 + (n_nodes + 1) * c * 2
+    entry("allreduce_share_256MB_bf16_128x8", 4 * P * c * 2 + share_bytes,
+          *time_calls([lambda s=s: big_share(s) for s in sets], trials=12, warm=6), launches_per_call=4)
+    entry("allreduce_share_256MB_bf16_128x8_no_pack", 2 * P * c * 2 + share_bytes,
+          *time_calls([lambda s=s: big_share_unpacked(s) for s in sets], trials=12, warm=6), launches_per_call=3)
+    del sets
     # the paper's literal two-source step (acc += recv) and one rank's replay of its inter-node algorithms
     w = W.cfg3()
     n = 64 * MB                                                     # 128 MB of bf16
