@@ -631,7 +631,7 @@ def test_binding_refuses_host_tensors_and_mismatched_shapes():
 @pytest.mark.parametrize("nodes,gpus", [(4, 8), (3, 5), (1, 7), (16, 2)])
 def test_batched_shuffles_match_the_oracle_bucket_by_bucket(nodes, gpus):
     P = nodes * gpus
-    chunk_bytes = [1024, 6, 0, 4096 + 48, 1, 100000, 16, 2050]       # ragged, tiny, empty, several tiles
+    chunk_bytes = [1024, 6, 0, 4096 + 48, 1, 100000, 16, 2050, 640 * 1024 + 48]   # ragged, tiny, empty, several tiles, rotated tiles
     for offset in (0, 1):                                              # 16-byte aligned and not
         srcs_h = [W.random_bits16((P * cb + 1) // 2 + 8, 50 + k).view(torch.uint8)[offset:offset + P * cb]
                   for k, cb in enumerate(chunk_bytes)]
