@@ -364,6 +364,47 @@ def size_sweep(dev):
     return out
 
 
+def scale_sweep(dev):
+    """Message size x node count (8 GPUs per node), the two axes of the paper's heat maps
+    (Section IV-B, Section V-A: 16 MB - 1 GB, up to 2048 GCDs), through the four calls of an
+    all-reduce share: bf16, back-to-back launches over rotating buffer sets."""
+    gpus, dt = 8, torch.bfloat16
+    out = []
+    for mb in (16, 64, 256, 1024):
+        m = mb * MB
+        n = m // 2
+        nsets = 2 if mb >= 256 else 4
+        sets = []
+        for k in range(nsets):
+            msgs = W.uniform_pm1(gpus * n, 800 + k, dev, dt).view(gpus, n)
+            sets.append(dict(msgs=msgs, packed=torch.empty(n, dtype=dt, device=dev), out=torch.empty(n, dtype=dt, device=dev),
+                             partial=torch.empty(n // gpus, dtype=dt, device=dev), shard=torch.empty(n // (4 * gpus), dtype=dt, device=dev)))
+        for nodes in (4, 16, 64, 256):
+            c = n // (nodes * gpus)
+            share_bytes = (gpus + 1) * nodes * c * 2 + (nodes + 1) * c * 2
+            row = {"message_MB": mb, "nodes": nodes, "chunk_KB": c * 2 // 1024}
+
+            def put(name, nbytes, t):
+                row[name + "_us"] = round(t[3] * 1e3, 2)
+                row[name + "_GBps"] = round(nbytes / (t[3] * 1e-3) / 1e9, 1)
+
+            put("hier_pack", 2 * m, time_calls(
+                [lambda s=s: pccl.pccl_hier_pack(s["packed"], s["msgs"][0], nodes, gpus) for s in sets], trials=4 * nsets))
+            put("reduce_scatter_local", share_bytes, time_calls(
+                [lambda s=s: pccl.pccl_reduce_scatter_local(s["shard"][:c], s["partial"], s["msgs"][0].view(gpus, nodes, c))
+                 for s in sets], trials=4 * nsets))
+            put("reduce_scatter_local_unpacked", share_bytes, time_calls(
+                [lambda s=s: pccl.pccl_reduce_scatter_local_unpacked(s["shard"][:c], s["partial"], msgs=s["msgs"], nodes=nodes,
+                                                                     gpus_per_node=gpus, my_gpu=3) for s in sets], trials=4 * nsets))
+            put("allgather_reassemble", 2 * m, time_calls(
+                [lambda s=s: pccl.pccl_allgather_reassemble(s["out"], src=s["msgs"][1], nodes=nodes, gpus_per_node=gpus)
+                 for s in sets], trials=4 * nsets))
+            out.append(row)
+        del sets
+        torch.cuda.empty_cache()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -376,7 +417,7 @@ def main():
                          "stream about 3 us, 13 us per step when every call of every step is bracketed)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-others", action="store_true", help="skip the other four configurations")
-    ap.add_argument("--sweep", action="store_true", help="also time the kernels over 16 MB - 1 GB messages")
+    ap.add_argument("--sweep", action="store_true", help="also time the kernels over 16 MB - 1 GB messages and 4 - 256 nodes")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run plain 256 MB device-to-device copies (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -492,6 +533,7 @@ def main():
     torch.cuda.empty_cache()
     others = None if args.no_others else other_workloads(dev)
     sweep = size_sweep(dev) if args.sweep else None
+    scale = scale_sweep(dev) if args.sweep else None
     if args.calibration_copy:
         a = torch.empty(256 * MB, dtype=torch.uint8, device=dev)
         b = torch.ones(256 * MB, dtype=torch.uint8, device=dev)
@@ -510,7 +552,7 @@ def main():
                    "accumulate": "f32", "algorithmic_bytes_per_step": step_bytes, "buffer_sets": args.sets,
                    "kernel_events_in_timed_region": use_ev, "kernel_events_every_n_steps": every if use_ev else None},
         "roofline": roofline, "cpu_baseline": cpu_baseline, "parity_vs_oracle": parity,
-        "calls": calls, "fused_step": fused, "other_workloads": others, "size_sweep": sweep,
+        "calls": calls, "fused_step": fused, "other_workloads": others, "size_sweep": sweep, "scale_sweep": scale,
     }
     print(json.dumps(out), flush=True)
 
