@@ -130,10 +130,16 @@ def _stream(stream):
     return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
 
 
+# torch reports address 0 for a tensor without elements; the C ABI wants every pointer non-NULL,
+# also for an empty range (which it never dereferences), so such a tensor travels as this address
+_EMPTY_RANGE = 0x100
+
+
 def _dev(t, what):
     if not t.is_cuda:
         raise ValueError("pccl: %s must live in GPU memory" % what)
-    return t.data_ptr()
+    p = t.data_ptr()
+    return _EMPTY_RANGE if p == 0 and t.numel() == 0 else p
 
 
 def _rows(t, what):
