@@ -284,7 +284,9 @@ hipError_t launch_m(const ReduceProblem& p, hipStream_t st) {
   const size_t per_source = p.count * es * (size_t)p.rows;
   // rows: two-wavefront blocks at any size (measured with the row rotation above: 46-48 us
   // against 48-56 us with four-wavefront blocks)
-  const bool small = p.rows > 1 || per_source < kSmallLaunchBytes / (sources == 0 ? 1 : sources);
+  // one or two sources: two-wavefront blocks at any size too (256 MB as 2 x 128 MB: 62.0 us
+  // against 64.4 us)
+  const bool small = p.rows > 1 || (M > 0 && M <= 2) || per_source < kSmallLaunchBytes / (sources == 0 ? 1 : sources);
   return small ? launch_mb<IN, OUT, M, kBlockSmall>(p, st) : launch_mb<IN, OUT, M, kBlock>(p, st);
 }
 
