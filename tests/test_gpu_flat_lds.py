@@ -92,3 +92,18 @@ def test_phase_two_of_a_share_with_received_chunks(nodes):
     assert same_bits(to_np(shard.view), ws) and same_bits(to_np(partial.view), wp.reshape(-1))
     shard.check()
     partial.check()
+
+
+@pytest.mark.parametrize("nsrc", [40, 200])
+def test_launch_split_over_x_and_z(monkeypatch, nsrc):
+    """A tiny x extent makes a small problem take the x/z-split launch that only buffers of tens of
+    GiB would otherwise take: blocks past the last slice must leave, every slice must be summed once."""
+    monkeypatch.setenv("PCCL_GRID_X_LIMIT", "4096")
+    count = 100003
+    host = W.normal(nsrc * count, 31, 1.0, "cpu", BF16).view(nsrc, count)
+    dst, view = _out(count, BF16)
+    pccl.pccl_local_reduce(view, host.to(DEV))
+    torch.cuda.synchronize()
+    want = oracle.flat_reduce([_np(host[s]) for s in range(nsrc)], ODT[BF16])
+    assert same_bits(_np(view), want), first_diff(_np(view), want)
+    dst.check()
