@@ -70,6 +70,18 @@ inline size_t tiles_per_chunk_for(const void* dst, size_t chunk_bytes) {
   return (m + chunk_bytes + kPermTile - 1) / kPermTile;
 }
 
+// Which chunk index the resident blocks sweep first.  Measured on MI355X for N x 8 and 8 x N
+// chunk matrices of 32-256 MB (both orders within 0.3 % run to run): with chunks of 64-256 KB
+// the order whose fast index is the SHORT side of the matrix is 2-10 % faster (the resident
+// blocks then touch one contiguous span on one side and only `short side` spans on the
+// other, instead of one span per chunk); below 64 KB the long side first is 4-5 % faster;
+// from 512 KB up the two are within 2 % and the destination-contiguous order is kept.
+__host__ __device__ inline bool column_fast_order(size_t chunk_bytes, int rows, int cols) {
+  if (chunk_bytes >= ((size_t)512 << 10)) return false;
+  if (chunk_bytes >= ((size_t)64 << 10)) return cols < rows;
+  return cols > rows;
+}
+
 // GRID3: blockIdx = (tile, r, c), or (tile, c, r) with CFAST; otherwise a flat grid,
 // chunk-major in destination order.  Blocks start in x, y, z order, so without CFAST the
 // resident blocks walk the destination contiguously and read from as many places as they span
@@ -95,8 +107,8 @@ __global__ __launch_bounds__(kPermBlock) void k_permute(PermuteProblem p, uint32
 }
 
 // Many independent chunk transposes (one per bucket, common rows x cols) in one launch: a flat
-// tile space over all buckets, chunk-major in destination order inside a bucket; the tile
-// prefix travels as a kernel argument and a block bisects it.
+// tile space over all buckets, chunk-major inside a bucket; the tile prefix travels as a kernel
+// argument and a block bisects it.
 __global__ __launch_bounds__(kPermBlock) void k_permute_batched(
     const pccl_permute_bucket_t* __restrict__ buckets, BatchTiles tiles, int nbuckets, int rows, int cols) {
   const size_t block = linear_block_xz();
@@ -113,28 +125,21 @@ __global__ __launch_bounds__(kPermBlock) void k_permute_batched(
   const uint32_t t = (uint32_t)(block - tiles.first_tile[lo]);
   // tiles in this bucket = chunks * tiles_per_chunk, so the latter follows from the prefix
   const uint32_t tiles_per_chunk = (tiles.first_tile[lo + 1] - tiles.first_tile[lo]) / (uint32_t)(rows * cols);
-  const uint32_t chunk = t / tiles_per_chunk;  // dst chunk = c*rows + r
-  const uint32_t tile = t - chunk * tiles_per_chunk;
-  const uint32_t c = chunk / (uint32_t)rows, r = chunk - c * (uint32_t)rows;
+  // chunks in destination order (k = c*rows + r) or, by the rule above, in source order
+  // (k = r*cols + c)
+  const uint32_t k = t / tiles_per_chunk;
+  const uint32_t tile = t - k * tiles_per_chunk;
+  uint32_t r, c;
+  if (column_fast_order(b.chunk_bytes, rows, cols)) {
+    r = k / (uint32_t)cols;
+    c = k - r * (uint32_t)cols;
+  } else {
+    c = k / (uint32_t)rows;
+    r = k - c * (uint32_t)rows;
+  }
   const char* sp = reinterpret_cast<const char*>(b.src) + ((size_t)r * cols + c) * b.chunk_bytes;
-  char* dp = reinterpret_cast<char*>(b.dst) + (size_t)chunk * b.chunk_bytes;
+  char* dp = reinterpret_cast<char*>(b.dst) + ((size_t)c * rows + r) * b.chunk_bytes;
   copy_chunk_tile(sp, dp, b.chunk_bytes, tile);
-}
-
-}  // namespace
-
-namespace {
-
-// Which chunk index the resident blocks sweep first.  Measured on MI355X for N x 8 and 8 x N
-// chunk matrices of 32-256 MB (both orders within 0.3 % run to run): with chunks of 64-256 KB
-// the order whose fast index is the SHORT side of the matrix is 2-10 % faster (the resident
-// blocks then touch one contiguous span on one side and only `short side` spans on the
-// other, instead of one span per chunk); below 64 KB the long side first is 4-5 % faster;
-// from 512 KB up the two are within 2 % and the destination-contiguous order is kept.
-bool column_fast_order(const PermuteProblem& p) {
-  if (p.chunk_bytes >= ((size_t)512 << 10)) return false;
-  if (p.chunk_bytes >= ((size_t)64 << 10)) return p.cols < p.rows;
-  return p.cols > p.rows;
 }
 
 }  // namespace
@@ -169,7 +174,7 @@ hipError_t launch_permute(const PermuteProblem& p, hipStream_t st) {
   if (tiles_per_chunk == 0 || chunks == 0) return hipSuccess;
   if (tiles_per_chunk > kPermMaxTilesX || chunks > 0x7FFFFFFFull) return hipErrorInvalidValue;
   if (p.rows <= 65535 && p.cols <= 65535) {
-    bool cfast = column_fast_order(p);
+    bool cfast = column_fast_order(p.chunk_bytes, p.rows, p.cols);
     if (const char* v = std::getenv("PCCL_PERMUTE_ORDER")) cfast = v[0] == 's';  // "src" / "dst"
     // Chunk (r, c) starts (r + c) * skew tiles into itself, modulo its tile count: the resident
     // blocks otherwise sit at the same offset of several chunks a power of two apart.  Measured
