@@ -498,6 +498,8 @@ template <int IN, int OUT, int M>
 hipError_t launch_lds_m(const ReduceProblem& p, hipStream_t st) {
   constexpr int E = narrow(IN) ? 128 : 64;
   const size_t blocks = (p.count + E - 1) / E;
+  // node and source indices are formed in 32 bits, tile padding included
+  if (p.nodes > (1 << 30) || (size_t)p.nodes * (size_t)p.gpus > ((size_t)1 << 30)) return hipErrorInvalidValue;
   unsigned gx, gz;
   if (!split_grid_xz(blocks, kLdsBlock, &gx, &gz)) return hipErrorInvalidValue;
   hipLaunchKernelGGL((k_reduce2l_lds<IN, OUT, M>), dim3(gx, 1, gz), dim3(kLdsBlock), 0, st, p);
@@ -640,6 +642,7 @@ hipError_t launch_flat_lds_io(const ReduceProblem& p, hipStream_t st) {
   const size_t nwords = (p.count + EPL - 1) / EPL;
   const size_t blocks = (nwords + 63) / 64;
   if (p.gpus != 1 || p.rows != 1 || p.partial != nullptr) return hipErrorInvalidValue;
+  if (p.nodes > (1 << 30)) return hipErrorInvalidValue;  // source indices are formed in 32 bits, tile padding included
   unsigned gx, gz;
   // Block shape, measured over 2-512 MB of sources and 24-256 of them: four wavefronts (more
   // blocks per CU, so that one block's ordered pass hides behind the others' loads) unless the
