@@ -107,3 +107,27 @@ def test_launch_split_over_x_and_z(monkeypatch, nsrc):
     want = oracle.flat_reduce([_np(host[s]) for s in range(nsrc)], ODT[BF16])
     assert same_bits(_np(view), want), first_diff(_np(view), want)
     dst.check()
+
+
+@pytest.mark.parametrize("dtype", [F32, BF16, F16])
+def test_special_values(dtype):
+    """Subnormals are kept, -0 survives when every source holds it, infinities propagate, NaN stays NaN."""
+    nsrc = 40
+    col = {F32: [1e-45, -0.0, float("inf"), 3e-39, float("nan"), -1e-40, 3.0e38, 1.0],
+           BF16: [1e-40, -0.0, float("inf"), 3e-39, float("nan"), -1e-40, 3.0e38, 1.0],
+           F16: [6e-8, -0.0, float("inf"), 3e-6, float("nan"), -6e-8, 6.0e4, 1.0]}[dtype]
+    host = torch.tensor(col, dtype=torch.float32).to(dtype).repeat(nsrc, 40)        # 320 elements per source
+    host[1::2, 2::8] = 1.0                                                           # inf + finite stays inf
+    host[3, 7::8] = float("-inf")                                                    # finite ... + -inf
+    dst, view = _out(host.shape[1], dtype)
+    pccl.pccl_local_reduce(view, host.to(DEV))
+    torch.cuda.synchronize()
+    want = oracle.flat_reduce([_np(host[s]) for s in range(nsrc)], ODT[dtype])
+    got = _np(view)
+    wf = want.astype(np.float32) if dtype == F16 else (want if dtype == F32 else (want.astype(np.uint32) << 16).view(np.float32))
+    gf = got.astype(np.float32) if dtype == F16 else (got if dtype == F32 else (got.astype(np.uint32) << 16).view(np.float32))
+    nan = np.isnan(wf)
+    assert nan.any() and np.isinf(wf).any() and np.array_equal(np.isnan(gf), nan)
+    assert same_bits(got[~nan], want[~nan]), first_diff(got[~nan], want[~nan])
+    assert np.signbit(gf[1]) and gf[1] == 0.0                                        # -0 + -0 + ... = -0
+    dst.check()
