@@ -280,6 +280,20 @@ def other_workloads(dev):
           total_bucket_MB=round(sum(sizes) / MB, 1))
     del table, buckets
     torch.cuda.empty_cache()
+    # the same 40 buckets straight from the eight node-mates' rank-order messages (no pre-shuffle of any
+    # bucket): 8 x 5 GB of messages resident, same algorithmic bytes
+    buckets = []
+    for k, b in enumerate(sizes):
+        chunk = b // (w.ranks * w.esize)
+        msgs = W.normal(w.gpus * w.ranks * chunk, 300 + k, 1e-3, dev, w.dtype).view(w.gpus, w.ranks * chunk)
+        buckets.append((torch.empty(chunk, dtype=w.dtype, device=dev),
+                        torch.empty(w.nodes * chunk, dtype=w.dtype, device=dev), msgs))
+    table = pccl.BucketTable(buckets, nodes=w.nodes)
+    entry("cfg5_rs_unpacked_batched_40_buckets_8x8_bf16", nbytes,
+          *time_calls([lambda: pccl.pccl_reduce_scatter_local_unpacked_batched(table, 3)], trials=5, warm=2),
+          total_bucket_MB=round(sum(sizes) / MB, 1))
+    del table, buckets
+    torch.cuda.empty_cache()
     # the all-gather side of the same 40 buckets: every bucket's shuffle into rank order, one launch
     pairs = []
     for k, b in enumerate(sizes):

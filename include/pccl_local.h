@@ -211,6 +211,20 @@ pccl_status_t pccl_reduce_scatter_local_batched(const pccl_bucket_t* d_buckets,
                                                 pccl_dtype_t io_dt, pccl_op_t op,
                                                 pccl_stream_t stream);
 
+/* The batched share straight from rank-order messages (the batched form of
+ * pccl_reduce_scatter_local_unpacked with d_msgs == NULL and d_inter == NULL): in every bucket
+ * intra_base is the first of gpus_per_node rank-order MESSAGES of
+ * nodes*gpus_per_node*chunk_count elements, intra_stride_bytes apart, and phase 1 reads chunk
+ * (n, my_gpu) of each.  No pre-shuffle of any bucket is needed; results are bit-identical to
+ * pccl_hier_pack_batched followed by pccl_reduce_scatter_local_batched.
+ * Errors: as there, with the stride checked against a message; my_gpu outside
+ * [0, gpus_per_node). */
+pccl_status_t pccl_reduce_scatter_local_unpacked_batched(const pccl_bucket_t* d_buckets,
+                                                         const pccl_bucket_t* h_buckets,
+                                                         int nbuckets, int nodes, int gpus_per_node,
+                                                         int my_gpu, pccl_dtype_t io_dt, pccl_op_t op,
+                                                         pccl_stream_t stream);
+
 /* One bucket of a batched shuffle: dst and src each hold nodes*gpus_per_node chunks of
  * chunk_bytes bytes and must not overlap.  Device pointers. */
 typedef struct {

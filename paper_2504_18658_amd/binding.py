@@ -23,6 +23,7 @@ EXPORTS = (
     "pccl_reduce_scatter_local_unpacked", "pccl_ring_reduce_scatter_local",
     "pccl_allgather_reassemble_batched", "pccl_hier_pack_batched", "pccl_halving_reduce_scatter_local", "pccl_model_ring", "pccl_model_rec",
     "pccl_choose_algorithm", "pccl_model_two_level", "pccl_status_string", "pccl_check_device_range",
+    "pccl_reduce_scatter_local_unpacked_batched",
 )
 PCCL_ALGO_RING, PCCL_ALGO_REC = 0, 1
 _NO_STATUS = ("pccl_status_string", "pccl_model_ring", "pccl_model_rec", "pccl_model_two_level")
@@ -69,6 +70,7 @@ def lib():
         L.pccl_reduce_scatter_local.argtypes = [vp, vp, vp, sz, vp, i, i, i, sz, i, i, vp]
         L.pccl_allgather_reassemble.argtypes = [vp, vp, vp, i, i, sz, vp]
         L.pccl_reduce_scatter_local_batched.argtypes = [vp, vp, i, i, i, i, i, vp]
+        L.pccl_reduce_scatter_local_unpacked_batched.argtypes = [vp, vp, i, i, i, i, i, i, vp]
         L.pccl_accumulate.argtypes = [vp, vp, sz, i, i, vp]
         L.pccl_allgather_reassemble_batched.argtypes = [vp, vp, i, i, i, vp]
         L.pccl_hier_pack_batched.argtypes = [vp, vp, i, i, i, vp]
@@ -252,16 +254,24 @@ def pccl_allgather_reassemble(dst, src=None, d_slots=None, nodes=1, gpus_per_nod
 class BucketTable:
     """Descriptor table of a batch: a host array and its device copy, built once and reused."""
 
-    def __init__(self, buckets):
-        """buckets: list of (shard, partial, intra) tensors shaped as for pccl_reduce_scatter_local."""
+    def __init__(self, buckets, nodes=None):
+        """buckets: list of (shard, partial, intra) tensors shaped as for pccl_reduce_scatter_local;
+        with `nodes` given, the third tensor of a bucket is instead [gpus][nodes*gpus*chunk]: the
+        node-mates' rank-order messages (for pccl_reduce_scatter_local_unpacked_batched)."""
         n = len(buckets)
         self.host = (pccl_bucket_t * max(n, 1))()
         self.nbuckets = n
         self.nodes = self.gpus = None
         self.dtype = None
+        self.from_messages = nodes is not None
         for k, (shard, partial, intra) in enumerate(buckets):
-            base, stride, gpus, _ = _rows(intra, "intra")
-            nodes, chunk = intra.shape[1], intra.shape[2]
+            base, stride, gpus, row = _rows(intra, "intra")
+            if self.from_messages:
+                if intra.dim() != 2 or row % (nodes * gpus) != 0:
+                    raise ValueError("BucketTable: messages must be [gpus][nodes*gpus*chunk]")
+                chunk = row // (nodes * gpus)
+            else:
+                nodes, chunk = intra.shape[1], intra.shape[2]
             if self.nodes is None:
                 self.nodes, self.gpus, self.dtype = nodes, gpus, intra.dtype
             if (nodes, gpus, intra.dtype) != (self.nodes, self.gpus, self.dtype):
@@ -273,10 +283,23 @@ class BucketTable:
         self._keep = buckets  # the table holds raw pointers: keep the tensors alive
 
 
+def pccl_reduce_scatter_local_unpacked_batched(table, my_gpu, stream=None, average=False):
+    """All buckets of a BucketTable built from rank-order messages (nodes=...): no pre-shuffle pass."""
+    if table.nbuckets == 0:
+        return
+    if not table.from_messages:
+        raise ValueError("pccl_reduce_scatter_local_unpacked_batched: build the table with nodes=...")
+    _check(lib().pccl_reduce_scatter_local_unpacked_batched(
+        table.device.data_ptr(), ctypes.addressof(table.host), table.nbuckets, table.nodes, table.gpus, my_gpu,
+        dtype_code(table.dtype), _op(average), _stream(stream)), "pccl_reduce_scatter_local_unpacked_batched")
+
+
 def pccl_reduce_scatter_local_batched(table, stream=None, average=False):
     """All buckets of a BucketTable: phase 1 in one launch, phase 2 in one launch."""
     if table.nbuckets == 0:
         return
+    if table.from_messages:
+        raise ValueError("pccl_reduce_scatter_local_batched: this table holds rank-order messages")
     _check(lib().pccl_reduce_scatter_local_batched(
         table.device.data_ptr(), ctypes.addressof(table.host), table.nbuckets, table.nodes, table.gpus,
         dtype_code(table.dtype), _op(average), _stream(stream)), "pccl_reduce_scatter_local_batched")

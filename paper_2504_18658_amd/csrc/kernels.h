@@ -87,9 +87,11 @@ hipError_t launch_permute(const PermuteProblem& p, hipStream_t st);
 hipError_t launch_accumulate(void* acc, const void* recv, size_t count, int dt, hipStream_t st);
 
 // Batched two-level reduce-scatter share; h_buckets is the host copy used to size the grid.
-// Phase 2 divides by `divisor` when it is not 0 (op = average).
+// Phase 2 divides by `divisor` when it is not 0 (op = average).  my_gpu < 0: a bucket's
+// intra_base holds pre-shuffled pieces; my_gpu >= 0: it holds `gpus` rank-order messages
+// intra_stride_bytes apart and phase 1 reads chunk (n, my_gpu) of each.
 hipError_t launch_rs_batched(const pccl_bucket_t* d_buckets, const pccl_bucket_t* h_buckets,
                              int nbuckets, int nodes, int gpus, int dt, float divisor,
-                             hipStream_t st);
+                             hipStream_t st, int my_gpu = -1);
 
 }  // namespace pccl

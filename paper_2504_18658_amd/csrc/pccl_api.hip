@@ -466,35 +466,37 @@ pccl_status_t pccl_reduce_scatter_local_unpacked(void* shard, void* partial, con
   return phase2(shard, partial, d_inter, nodes, my_node, chunk_count, chunk_bytes, dt, divisor, st);
 }
 
-pccl_status_t pccl_reduce_scatter_local_batched(const pccl_bucket_t* d_buckets,
-                                                const pccl_bucket_t* h_buckets, int nbuckets,
-                                                int nodes, int gpus_per_node,
-                                                pccl_dtype_t io_dt, pccl_op_t op,
-                                                pccl_stream_t stream) {
+// Both batched shares.  my_gpu < 0: intra_base holds gpus_per_node pre-shuffled pieces of
+// nodes*chunk_count elements; my_gpu >= 0: it holds gpus_per_node rank-order messages of
+// nodes*gpus_per_node*chunk_count elements.
+static pccl_status_t rs_batched_common(const pccl_bucket_t* d_buckets, const pccl_bucket_t* h_buckets,
+                                       int nbuckets, int nodes, int gpus_per_node, int my_gpu,
+                                       pccl_dtype_t io_dt, pccl_op_t op, pccl_stream_t stream) {
   if (nbuckets < 0 || nbuckets > PCCL_MAX_BUCKETS) return PCCL_ERR_INVALID;
   if (nbuckets > 0 && (d_buckets == nullptr || h_buckets == nullptr)) return PCCL_ERR_NULL;
   if (pccl_status_t s = check_common(io_dt, io_dt, op)) return s;
-  if (nodes < 1 || gpus_per_node < 1) return PCCL_ERR_INVALID;
+  if (nodes < 1 || gpus_per_node < 1 || my_gpu >= gpus_per_node) return PCCL_ERR_INVALID;
   if (!divisor_ok(op, (size_t)nodes * (size_t)gpus_per_node)) return PCCL_ERR_INVALID;
   const size_t es = esize(io_dt);
+  const size_t per_source_chunks = my_gpu < 0 ? 1 : (size_t)gpus_per_node;  // chunks per node in a source
   bool any = false;
   for (int b = 0; b < nbuckets; ++b) {
     const pccl_bucket_t& k = h_buckets[b];
     if (k.chunk_count == 0) continue;  // an empty bucket is skipped whatever its pointers are
     if (k.shard == nullptr || k.partial == nullptr || k.intra_base == nullptr)
       return PCCL_ERR_NULL;
-    size_t piece_count, piece_bytes, span;
+    size_t piece_count, piece_bytes, source_bytes, span;
     if (!mul_ok((size_t)nodes, k.chunk_count, &piece_count) ||
-        !mul_ok(piece_count, es, &piece_bytes))
+        !mul_ok(piece_count, es, &piece_bytes) || !mul_ok(piece_bytes, per_source_chunks, &source_bytes))
       return PCCL_ERR_INVALID;
     if (!elem_aligned(k.shard, es) || !elem_aligned(k.partial, es) ||
         !elem_aligned(k.intra_base, es))
       return PCCL_ERR_INVALID;
-    if (gpus_per_node > 1 && (k.intra_stride_bytes < piece_bytes || k.intra_stride_bytes % es != 0))
+    if (gpus_per_node > 1 && (k.intra_stride_bytes < source_bytes || k.intra_stride_bytes % es != 0))
       return PCCL_ERR_INVALID;
     if (!mul_ok((size_t)(gpus_per_node - 1), gpus_per_node > 1 ? k.intra_stride_bytes : 0,
                 &span) ||
-        !add_ok(span, piece_bytes, &span))
+        !add_ok(span, source_bytes, &span))
       return PCCL_ERR_INVALID;
     const size_t chunk_bytes = k.chunk_count * es;
     if (overlaps(k.partial, piece_bytes, k.intra_base, span) ||
@@ -513,15 +515,33 @@ pccl_status_t pccl_reduce_scatter_local_batched(const pccl_bucket_t* d_buckets,
       const size_t piece_bytes = (size_t)nodes * k.chunk_count * es;
       ck.range(k.shard, k.chunk_count * es);
       ck.range(k.partial, piece_bytes);
-      ck.range(k.intra_base, (size_t)(gpus_per_node - 1) * (gpus_per_node > 1 ? k.intra_stride_bytes : 0) + piece_bytes);
+      ck.range(k.intra_base, (size_t)(gpus_per_node - 1) * (gpus_per_node > 1 ? k.intra_stride_bytes : 0) +
+                                 piece_bytes * per_source_chunks);
     }
     if (ck.status != PCCL_OK) return ck.status;
   }
   const hipError_t e =
       pccl::launch_rs_batched(d_buckets, h_buckets, nbuckets, nodes, gpus_per_node, io_dt,
                               divisor_for(op, (size_t)nodes * (size_t)gpus_per_node),
-                              reinterpret_cast<hipStream_t>(stream));
+                              reinterpret_cast<hipStream_t>(stream), my_gpu);
   return e == hipErrorInvalidValue ? PCCL_ERR_INVALID : from_hip(e);
+}
+
+pccl_status_t pccl_reduce_scatter_local_batched(const pccl_bucket_t* d_buckets,
+                                                const pccl_bucket_t* h_buckets, int nbuckets,
+                                                int nodes, int gpus_per_node,
+                                                pccl_dtype_t io_dt, pccl_op_t op,
+                                                pccl_stream_t stream) {
+  return rs_batched_common(d_buckets, h_buckets, nbuckets, nodes, gpus_per_node, -1, io_dt, op, stream);
+}
+
+pccl_status_t pccl_reduce_scatter_local_unpacked_batched(const pccl_bucket_t* d_buckets,
+                                                         const pccl_bucket_t* h_buckets, int nbuckets,
+                                                         int nodes, int gpus_per_node, int my_gpu,
+                                                         pccl_dtype_t io_dt, pccl_op_t op,
+                                                         pccl_stream_t stream) {
+  if (my_gpu < 0) return PCCL_ERR_INVALID;
+  return rs_batched_common(d_buckets, h_buckets, nbuckets, nodes, gpus_per_node, my_gpu, io_dt, op, stream);
 }
 
 pccl_status_t pccl_accumulate(void* acc, const void* recv, size_t count, pccl_dtype_t io_dt,

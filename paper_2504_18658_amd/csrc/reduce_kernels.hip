@@ -116,17 +116,22 @@ __device__ void reduce_elem(const ReduceProblem& p, size_t e) {
 // M == 0: any number of sources, walked in batches of four.
 // W is picked so that a lane keeps about 32 bytes of loads in flight (M * 4W): measured on
 // MI355X, more bytes per lane at full occupancy lowers the achieved HBM bandwidth.
+// `shift` (< BLOCK, in vectors) moves the tile grid: thread t of tile k owns vector
+// k*BLOCK + t - shift, so that the first `shift` threads of tile 0 idle and one more tile may
+// be needed; the caller picks it so that wavefront loads start on cache-line boundaries.
 template <int IN, int OUT, int M, int W, bool FAST, int BLOCK>
-__device__ __forceinline__ void reduce_tile(const ReduceProblem& p, size_t tile) {
+__device__ __forceinline__ void reduce_tile(const ReduceProblem& p, size_t tile, size_t shift = 0) {
   constexpr int VE = narrow(IN) ? 2 * W : W;  // elements per vector
   constexpr int ES = narrow(IN) ? 2 : 4;
   constexpr int VB = 4 * W;  // bytes per vector
   const size_t nvec = p.count / VE;
-  const size_t ntiles_vec = (nvec + BLOCK - 1) / BLOCK;
+  const size_t ntiles_vec = (nvec + shift + BLOCK - 1) / BLOCK;
   const size_t last_tile = ntiles_vec == 0 ? 0 : ntiles_vec - 1;
-  const size_t v = tile * BLOCK + threadIdx.x;
-  const size_t tile_off = tile * ((size_t)BLOCK * VB);  // wave-uniform byte offset of the tile
-  const uint32_t lane_off = threadIdx.x * VB;            // this lane's offset inside the tile
+  // both wrap below zero for the idle head of tile 0: v then fails v < nvec, and tile_off is
+  // only ever added to a lane offset that brings the sum back to v * VB
+  const size_t v = tile * BLOCK + threadIdx.x - shift;
+  const size_t tile_off = (tile * BLOCK - shift) * (size_t)VB;  // wave-uniform byte offset of the tile
+  const uint32_t lane_off = threadIdx.x * VB;                    // this lane's offset inside the tile
 
   if (v < nvec) {
     float acc[VE];
@@ -218,6 +223,18 @@ inline int pick_m(int gpus) {
   return (gpus == 1 || gpus == 2 || gpus == 4 || gpus == 8 || gpus == 16) ? gpus : 0;
 }
 
+// Vectors by which a row's tile grid is moved so that every wavefront load but the row's
+// first starts on a 128-byte line of the first source (the others share its alignment when
+// they are a multiple of 128 bytes apart, as whole messages are).  Rows start wherever the
+// chunk size puts them; with chunk sizes that are multiples of 16 bytes only, line-straddling
+// loads cost the 8-source row reduce 22 % (16 x 8 ranks, 2 MB + 16 B chunks: 69.6 us against
+// 55.0 us for 2 MB chunks).
+template <int VB>
+__device__ __forceinline__ size_t line_shift(const void* row_start) {
+  const uintptr_t a = reinterpret_cast<uintptr_t>(row_start);
+  return (a % VB == 0) ? (a & 127) / VB : 0;
+}
+
 // Rows (grid.y > 1: the same reduction over `rows` strided rows of every source) start their
 // tiles kRowSkewTiles further along than the row before, modulo the tiles of a row.  Rows
 // are a power-of-two number of bytes apart in every source, and the blocks resident at one
@@ -230,19 +247,22 @@ constexpr size_t kRowSkewTiles = 131;
 template <int IN, int OUT, int M, bool FAST, int BLOCK>
 __global__ __launch_bounds__(BLOCK) void k_reduce(ReduceProblem p) {
   size_t tile = linear_block_xz();
+  size_t shift = 0;
   if (gridDim.y > 1) {
     constexpr size_t VE = (size_t)words_for(M) * (narrow(IN) ? 2 : 1);
     const size_t nvec = p.count / VE;
     size_t ntiles = (nvec + BLOCK - 1) / BLOCK;
     if (ntiles == 0) ntiles = 1;       // a lone ragged tail
+    ntiles += 1;                       // room for the line shift below
     if (tile >= ntiles) return;        // the x*z rectangle is rounded up
     const size_t row = blockIdx.y;
     tile = (tile + row * kRowSkewTiles) % ntiles;
     p.base += row * p.row_stride_src;
     p.src_offset += row * p.row_stride_src;
     p.dst = reinterpret_cast<char*>(p.dst) + row * p.row_stride_dst;
+    shift = line_shift<4 * words_for(M)>(src_ptr<FAST>(p, 0, 0));
   }
-  reduce_tile<IN, OUT, M, words_for(M), FAST, BLOCK>(p, tile);
+  reduce_tile<IN, OUT, M, words_for(M), FAST, BLOCK>(p, tile, shift);
 }
 
 inline size_t tiles_for(size_t count, int m, bool in_narrow, int block = kBlock) {
@@ -264,7 +284,8 @@ inline bool fast_eligible(const ReduceProblem& p, bool in_narrow) {
 
 template <int IN, int OUT, int M, int BLOCK>
 hipError_t launch_mb(const ReduceProblem& p, hipStream_t st) {
-  const size_t tiles = tiles_for(p.count, M, narrow(IN), BLOCK);
+  // rows: one more tile per row, for the line shift
+  const size_t tiles = tiles_for(p.count, M, narrow(IN), BLOCK) + (p.rows > 1 ? 1 : 0);
   unsigned gx, gz;
   if (p.rows < 1 || p.rows > 65535 || !split_grid_xz(tiles, BLOCK, &gx, &gz)) return hipErrorInvalidValue;
   if (p.rows > 1 && p.partial != nullptr) return hipErrorInvalidValue;
@@ -532,18 +553,36 @@ hipError_t launch_lds_io(const ReduceProblem& p, hipStream_t st) {
 //   for 16-bit elements), one tile behind the loads (the parking area is double-buffered).
 // The accumulator starts from source 0 and every add is sequential in source order, so the
 // result is bit-identical to the streaming kernel's.
+// A slice is only 256 bytes of each source, so when sources do not start on a cache line every
+// line a block touches at the edge of its slice is also needed by the block of the next slice.
+// Two measures keep that second access out of HBM: neighbouring slices run on the same XCD
+// (kFlatXcdMajor), and the loads are ordinary cached ones rather than streaming ones
+// (kFlatCachedLoads).  32 MB of bf16 in 32 / 64 / 128 / 256 sources whose size is 16 bytes
+// off a multiple of 128: 13.0 / 16.9 / 21.3 / 21.5 us without, 9.0 / 9.8 / 13.1 / 14.7 us
+// with both; sources on line boundaries: 9.1 / 9.4 / 9.0 / 10.5 against 8.2 / 8.3 / 8.4 /
+// 10.7 us.  Either measure alone gains about half of that.
 constexpr int kFlatNpt = 8;
+constexpr int kFlatXcdMajor = 1;
+constexpr int kFlatCachedLoads = 2;
 
 template <int IN, int OUT, int WAVES>
-__global__ __launch_bounds__(WAVES * 64) void k_flat_lds(ReduceProblem p) {
+__global__ __launch_bounds__(WAVES * 64) void k_flat_lds(ReduceProblem p, int mode) {
   constexpr int EPL = narrow(IN) ? 2 : 1;
   constexpr int TN = WAVES * kFlatNpt;
   __shared__ uint32_t parked[2][TN * 64];
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const size_t nwords = (p.count + EPL - 1) / EPL;  // a ragged last word counts
-  const size_t w0 = linear_block_xz() * 64;
-  if (w0 >= nwords) return;  // the x*z rectangle is rounded up: whole blocks past the end leave
+  size_t slice = linear_block_xz();
+  if (mode & kFlatXcdMajor) {
+    // workgroups are dealt to the 8 XCDs round-robin: give XCD x the contiguous range of
+    // slices [x*per, (x+1)*per), so that neighbouring slices share an L2
+    const size_t per = ((nwords + 63) / 64 + 7) / 8;
+    if (slice >= 8 * per) return;  // the x*z rectangle is rounded up
+    slice = (slice & 7) * per + (slice >> 3);
+  }
+  const size_t w0 = slice * 64;
+  if (w0 >= nwords) return;  // the launch is rounded up: whole blocks past the end leave
   const size_t le = (w0 + lane) * EPL;  // this lane's first element
   const bool slice_full = (w0 + 64) * EPL <= p.count;  // block-uniform
   const int nsrc = p.nodes;
@@ -588,7 +627,10 @@ __global__ __launch_bounds__(WAVES * 64) void k_flat_lds(ReduceProblem p) {
     if (nvalid == kFlatNpt && slice_full && !__any((int)(cur & 3))) {
       // the whole trip without a check: 8 loads issue back to back
 #pragma unroll
-      for (int q = 0; q < kFlatNpt; ++q) raw[q] = ld_stream<uint32_t>(lane_pointer(cur, q) + 4 * (w0 + lane));
+      for (int q = 0; q < kFlatNpt; ++q) {
+        const char* a = lane_pointer(cur, q) + 4 * (w0 + lane);
+        raw[q] = (mode & kFlatCachedLoads) ? *((const PCCL_GLOBAL uint32_t*)a) : ld_stream<uint32_t>(a);
+      }
     } else {
 #pragma unroll
       for (int q = 0; q < kFlatNpt; ++q)
@@ -653,14 +695,17 @@ hipError_t launch_flat_lds_io(const ReduceProblem& p, hipStream_t st) {
     const int w = std::atoi(v);
     if (w == 4 || w == 8 || w == 16) waves = w;
   }
-  if (!split_grid_xz(blocks, (unsigned)waves * 64, &gx, &gz)) return hipErrorInvalidValue;
+  int mode = kFlatXcdMajor | kFlatCachedLoads;
+  if (const char* v = std::getenv("PCCL_FLAT_MODE")) mode = std::atoi(v) & 3;  // for A/B runs
+  const size_t launch_blocks = (mode & kFlatXcdMajor) ? (blocks + 7) / 8 * 8 : blocks;
+  if (!split_grid_xz(launch_blocks, (unsigned)waves * 64, &gx, &gz)) return hipErrorInvalidValue;
   const dim3 grid(gx, 1, gz), block((unsigned)waves * 64);
   if (waves == 4)
-    hipLaunchKernelGGL((k_flat_lds<IN, OUT, 4>), grid, block, 0, st, p);
+    hipLaunchKernelGGL((k_flat_lds<IN, OUT, 4>), grid, block, 0, st, p, mode);
   else if (waves == 8)
-    hipLaunchKernelGGL((k_flat_lds<IN, OUT, 8>), grid, block, 0, st, p);
+    hipLaunchKernelGGL((k_flat_lds<IN, OUT, 8>), grid, block, 0, st, p, mode);
   else
-    hipLaunchKernelGGL((k_flat_lds<IN, OUT, 16>), grid, block, 0, st, p);
+    hipLaunchKernelGGL((k_flat_lds<IN, OUT, 16>), grid, block, 0, st, p, mode);
   return hipGetLastError();
 }
 
@@ -746,6 +791,97 @@ hipError_t launch_batched_phase(const pccl_bucket_t* d_buckets, const pccl_bucke
   return hipGetLastError();
 }
 
+// Phase 1 of the batched share straight from rank-order messages: bucket b reads chunk
+// (n, my_gpu) of each of its `gpus` messages (intra_base = the first message, messages
+// intra_stride_bytes apart) and writes row n of its partial.  The tile space of a bucket is
+// nodes x tiles-of-a-row; rows start their tiles kRowSkewTiles apart as in k_reduce.
+template <int DT, int M, bool FAST>
+__global__ __launch_bounds__(kBlockSmall) void k_rs_batched_rows(const pccl_bucket_t* __restrict__ buckets,
+                                                                 BatchTiles tiles, int nbuckets, int nodes,
+                                                                 int gpus, int my_gpu) {
+  constexpr int ES = narrow(DT) ? 2 : 4;
+  const size_t block = linear_block_xz();
+  if (block >= tiles.first_tile[nbuckets]) return;  // the x*z rectangle is rounded up
+  int lo = 0, hi = nbuckets;
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (tiles.first_tile[mid] <= block)
+      lo = mid;
+    else
+      hi = mid;
+  }
+  const pccl_bucket_t b = buckets[lo];
+  const uint32_t t = (uint32_t)(block - tiles.first_tile[lo]);
+  const uint32_t row_tiles = (tiles.first_tile[lo + 1] - tiles.first_tile[lo]) / (uint32_t)nodes;
+  const uint32_t row = t / row_tiles;
+  const uint32_t tile = (uint32_t)(((uint64_t)(t - row * row_tiles) + (uint64_t)row * kRowSkewTiles) % row_tiles);
+  const size_t chunk_bytes = b.chunk_count * ES;
+  ReduceProblem p;
+  p.ptrs = nullptr;
+  p.override_ptr = nullptr;
+  p.override_index = -1;
+  p.partial = nullptr;
+  p.round_partial = 0;
+  p.nodes = 1;
+  p.stride_n = 0;
+  p.src_offset = 0;
+  p.row_stride_src = 0;
+  p.row_stride_dst = 0;
+  p.rows = 1;
+  p.divisor = 0.0f;
+  p.dst = reinterpret_cast<char*>(b.partial) + (size_t)row * chunk_bytes;
+  p.base = reinterpret_cast<const char*>(b.intra_base) + ((size_t)row * gpus + my_gpu) * chunk_bytes;
+  p.stride_g = b.intra_stride_bytes;
+  p.count = b.chunk_count;
+  p.gpus = gpus;
+  reduce_tile<DT, DT, M, words_for(M), FAST, kBlockSmall>(p, tile, line_shift<4 * words_for(M)>(p.base));
+}
+
+template <int DT, int M>
+hipError_t launch_batched_rows(const pccl_bucket_t* d_buckets, const pccl_bucket_t* h_buckets, int nbuckets,
+                               int nodes, int gpus, int my_gpu, hipStream_t st) {
+  BatchTiles tiles;
+  size_t total = 0;
+  for (int b = 0; b < nbuckets; ++b) {
+    tiles.first_tile[b] = (uint32_t)total;
+    if (h_buckets[b].chunk_count != 0)
+      total += (size_t)nodes * (tiles_for(h_buckets[b].chunk_count, M, narrow(DT), kBlockSmall) + 1);  // + line shift
+    if (total > 0xFFFFFFFFull) return hipErrorInvalidValue;  // the prefix holds 32-bit tile indices
+  }
+  for (int b = nbuckets; b <= kMaxBuckets; ++b) tiles.first_tile[b] = (uint32_t)total;
+  if (total == 0) return hipSuccess;
+  bool fast = true;
+  const size_t es = narrow(DT) ? 2 : 4;
+  for (int b = 0; b < nbuckets; ++b) {
+    const pccl_bucket_t& k = h_buckets[b];
+    if (k.chunk_count == 0) continue;
+    fast = fast && is16(k.partial) && is16(k.intra_base) && k.intra_stride_bytes % 16 == 0 &&
+           (k.chunk_count * es) % 16 == 0;
+  }
+  unsigned gx, gz;
+  if (!split_grid_xz(total, kBlockSmall, &gx, &gz)) return hipErrorInvalidValue;
+  if (fast)
+    hipLaunchKernelGGL((k_rs_batched_rows<DT, M, true>), dim3(gx, 1, gz), dim3(kBlockSmall), 0, st, d_buckets,
+                       tiles, nbuckets, nodes, gpus, my_gpu);
+  else
+    hipLaunchKernelGGL((k_rs_batched_rows<DT, M, false>), dim3(gx, 1, gz), dim3(kBlockSmall), 0, st, d_buckets,
+                       tiles, nbuckets, nodes, gpus, my_gpu);
+  return hipGetLastError();
+}
+
+template <int DT>
+hipError_t launch_batched_rows_io(const pccl_bucket_t* d, const pccl_bucket_t* h, int nb, int nodes, int gpus,
+                                  int my_gpu, hipStream_t st) {
+  switch (pick_m(gpus)) {
+    case 1: return launch_batched_rows<DT, 1>(d, h, nb, nodes, gpus, my_gpu, st);
+    case 2: return launch_batched_rows<DT, 2>(d, h, nb, nodes, gpus, my_gpu, st);
+    case 4: return launch_batched_rows<DT, 4>(d, h, nb, nodes, gpus, my_gpu, st);
+    case 8: return launch_batched_rows<DT, 8>(d, h, nb, nodes, gpus, my_gpu, st);
+    case 16: return launch_batched_rows<DT, 16>(d, h, nb, nodes, gpus, my_gpu, st);
+    default: return launch_batched_rows<DT, 0>(d, h, nb, nodes, gpus, my_gpu, st);
+  }
+}
+
 template <int DT, int PHASE>
 hipError_t launch_batched_io(const pccl_bucket_t* d, const pccl_bucket_t* h, int nb, int nodes,
                              int gpus, float divisor, hipStream_t st) {
@@ -812,11 +948,17 @@ bool prefer_lds_two_level(const ReduceProblem& p, int in_dt) {
 
 hipError_t launch_rs_batched(const pccl_bucket_t* d_buckets, const pccl_bucket_t* h_buckets,
                              int nbuckets, int nodes, int gpus, int dt, float divisor,
-                             hipStream_t st) {
+                             hipStream_t st, int my_gpu) {
   hipError_t e = hipErrorInvalidValue;
-  if (dt == kF32) e = launch_batched_io<kF32, 1>(d_buckets, h_buckets, nbuckets, nodes, gpus, 0.0f, st);
-  if (dt == kBF16) e = launch_batched_io<kBF16, 1>(d_buckets, h_buckets, nbuckets, nodes, gpus, 0.0f, st);
-  if (dt == kF16) e = launch_batched_io<kF16, 1>(d_buckets, h_buckets, nbuckets, nodes, gpus, 0.0f, st);
+  if (my_gpu >= 0) {  // phase 1 straight from rank-order messages
+    if (dt == kF32) e = launch_batched_rows_io<kF32>(d_buckets, h_buckets, nbuckets, nodes, gpus, my_gpu, st);
+    if (dt == kBF16) e = launch_batched_rows_io<kBF16>(d_buckets, h_buckets, nbuckets, nodes, gpus, my_gpu, st);
+    if (dt == kF16) e = launch_batched_rows_io<kF16>(d_buckets, h_buckets, nbuckets, nodes, gpus, my_gpu, st);
+  } else {
+    if (dt == kF32) e = launch_batched_io<kF32, 1>(d_buckets, h_buckets, nbuckets, nodes, gpus, 0.0f, st);
+    if (dt == kBF16) e = launch_batched_io<kBF16, 1>(d_buckets, h_buckets, nbuckets, nodes, gpus, 0.0f, st);
+    if (dt == kF16) e = launch_batched_io<kF16, 1>(d_buckets, h_buckets, nbuckets, nodes, gpus, 0.0f, st);
+  }
   if (e != hipSuccess) return e;
   if (dt == kF32) return launch_batched_io<kF32, 2>(d_buckets, h_buckets, nbuckets, nodes, gpus, divisor, st);
   if (dt == kBF16) return launch_batched_io<kBF16, 2>(d_buckets, h_buckets, nbuckets, nodes, gpus, divisor, st);

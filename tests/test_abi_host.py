@@ -318,3 +318,28 @@ def test_checked_mode_refuses_addresses_no_kernel_can_reach(monkeypatch):
     assert L.pccl_local_reduce(a, b, 4096, 0, 1024, pccl.PCCL_F32, pccl.PCCL_F32, pccl.PCCL_SUM, None) == pccl.PCCL_ERR_INVALID
     assert L.pccl_local_reduce(a, b, 4096, 2, 0, pccl.PCCL_F32, pccl.PCCL_F32, pccl.PCCL_SUM, None) == pccl.PCCL_OK
     assert "ADDRESS" in pccl.status_string(pccl.PCCL_ERR_ADDRESS)
+
+
+def test_unpacked_batched_rejects_bad_arguments():
+    f = pccl.lib().pccl_reduce_scatter_local_unpacked_batched
+    # 4 nodes x 8 GPUs, bf16, chunk 1024 elements: a message is 4*8*1024*2 = 65536 bytes
+    good = (pccl.pccl_bucket_t * 1)(pccl.pccl_bucket_t(A, 2 * A, 8 * A, 1 << 16, 1024))
+    h = ctypes.addressof(good)
+    assert f(None, h, 1, 4, 8, 3, 1, 0, None) == pccl.PCCL_ERR_NULL
+    assert f(A, None, 1, 4, 8, 3, 1, 0, None) == pccl.PCCL_ERR_NULL
+    assert f(A, h, 1, 4, 8, -1, 1, 0, None) == pccl.PCCL_ERR_INVALID            # my_gpu out of range
+    assert f(A, h, 1, 4, 8, 8, 1, 0, None) == pccl.PCCL_ERR_INVALID
+    assert f(A, h, 1, 0, 8, 3, 1, 0, None) == pccl.PCCL_ERR_INVALID
+    assert f(A, h, 1, 4, 8, 3, 7, 0, None) == pccl.PCCL_ERR_UNSUPPORTED
+    assert f(A, h, pccl.PCCL_MAX_BUCKETS + 1, 4, 8, 3, 1, 0, None) == pccl.PCCL_ERR_INVALID
+    assert f(None, None, 0, 4, 8, 3, 1, 0, None) == pccl.PCCL_OK
+    # a stride that fits a pre-shuffled piece (4*1024*2 bytes) but not a whole message
+    bad = (pccl.pccl_bucket_t * 1)(pccl.pccl_bucket_t(A, 2 * A, 8 * A, 1 << 13, 1024))
+    assert f(A, ctypes.addressof(bad), 1, 4, 8, 3, 1, 0, None) == pccl.PCCL_ERR_INVALID
+    # the partial inside the span of the eight messages
+    bad = (pccl.pccl_bucket_t * 1)(pccl.pccl_bucket_t(A, 8 * A + (5 << 16), 8 * A, 1 << 16, 1024))
+    assert f(A, ctypes.addressof(bad), 1, 4, 8, 3, 1, 0, None) == pccl.PCCL_ERR_OVERLAP
+    bad = (pccl.pccl_bucket_t * 1)(pccl.pccl_bucket_t(None, 2 * A, 8 * A, 1 << 16, 1024))
+    assert f(A, ctypes.addressof(bad), 1, 4, 8, 3, 1, 0, None) == pccl.PCCL_ERR_NULL
+    empty = (pccl.pccl_bucket_t * 1)(pccl.pccl_bucket_t(None, None, None, 0, 0))
+    assert f(A, ctypes.addressof(empty), 1, 4, 8, 3, 1, 0, None) == pccl.PCCL_OK

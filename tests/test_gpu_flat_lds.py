@@ -131,3 +131,21 @@ def test_special_values(dtype):
     assert same_bits(got[~nan], want[~nan]), first_diff(got[~nan], want[~nan])
     assert np.signbit(gf[1]) and gf[1] == 0.0                                        # -0 + -0 + ... = -0
     dst.check()
+
+
+@pytest.mark.parametrize("mode", ["0", "1", "2", "3"])
+@pytest.mark.parametrize("tiny_grid", [False, True])
+def test_slice_order_and_load_kind(monkeypatch, mode, tiny_grid):
+    """Slices dealt linearly or XCD-major (bit 0), streaming or cached loads (bit 1): the same sums;
+    with a tiny x extent the XCD-major launch is also rounded up over x and z."""
+    monkeypatch.setenv("PCCL_FLAT_MODE", mode)
+    if tiny_grid:
+        monkeypatch.setenv("PCCL_GRID_X_LIMIT", "4096")
+    for nsrc, count, dtype in ((40, 100003, BF16), (130, 1000, F32), (17, 64 * 9 + 1, BF16), (300, 127, F16)):
+        host = W.normal(nsrc * (count + 1), 41, 1.0, "cpu", dtype)[: nsrc * count].view(nsrc, count)
+        dst, view = _out(count, dtype)
+        pccl.pccl_local_reduce(view, host.to(DEV))
+        torch.cuda.synchronize()
+        want = oracle.flat_reduce([_np(host[s]) for s in range(nsrc)], ODT[dtype])
+        assert same_bits(_np(view), want), (nsrc, count, first_diff(_np(view), want))
+        dst.check()

@@ -707,3 +707,63 @@ def test_shuffle_tiles_cut_at_destination_boundaries(dst_off, src_off):
     for (dst, _), want, out, cb in zip(pairs, wants, outs, sizes):
         assert same_bits(to_np(dst), want), ("batched", cb)
         out.check()
+
+
+# ------------------------------------------------------------------------------- batched share from messages
+@pytest.mark.parametrize("dtype", [BF16, F32])
+@pytest.mark.parametrize("nodes,gpus,my_gpu", [(4, 8, 3), (5, 3, 0), (1, 4, 3), (40, 2, 1), (3, 1, 0)])
+def test_batched_share_from_rank_order_messages(dtype, nodes, gpus, my_gpu):
+    """Buckets of different sizes (one empty, ragged and misaligned ones) through
+    pccl_reduce_scatter_local_unpacked_batched: equal to the unbatched oracle bucket by bucket."""
+    P = nodes * gpus
+    chunks = [1000, 0, 7, 4096 + 3, 129, 20000]
+    for average in (False, True):
+        buckets, wants, guards = [], [], []
+        for k, c in enumerate(chunks):
+            msgs_h = W.normal(gpus * P * c + gpus, 80 + k, 1.0, "cpu", dtype)[: gpus * P * c].view(gpus, P * c)
+            shard, partial = Guarded(c, dtype), Guarded(nodes * c, dtype, offset_elems=k % 2)
+            buckets.append((shard.view, partial.view, msgs_h.to(DEV)))
+            guards += [shard, partial]
+            wants.append(oracle.reduce_scatter_local_unpacked([to_np(msgs_h[g]) for g in range(gpus)], nodes, gpus, my_gpu,
+                                                              average=average) if c else None)
+        table = pccl.BucketTable(buckets, nodes=nodes)
+        pccl.pccl_reduce_scatter_local_unpacked_batched(table, my_gpu, average=average)
+        _sync()
+        for k, c in enumerate(chunks):
+            if c:
+                ws, wp = wants[k]
+                assert same_bits(to_np(buckets[k][0]), ws), (k, c, average, first_diff(to_np(buckets[k][0]), ws))
+                assert same_bits(to_np(buckets[k][1]), wp.reshape(-1)), (k, c, average)
+        for g in guards:
+            g.check()
+
+
+def test_batched_share_from_messages_equals_pack_then_batched_share_at_size():
+    """Ten ZeRO-3-shaped buckets (8 x 8 ranks, sizes of the 40-bucket list scaled by 1/4): the share
+    straight from the messages equals pre-shuffling every message and taking the packed share,
+    bit for bit on the GPU; the smallest bucket is also checked against the oracle."""
+    w = W.cfg5(scale=0.25, nbuckets=10)
+    sizes = w.extra["bucket_bytes"]
+    nodes, gpus, my_gpu = w.nodes, w.gpus, 5
+    P = nodes * gpus
+    direct, packed, keep = [], [], []
+    for k, b in enumerate(sizes):
+        c = b // 2 // P
+        msgs = W.normal(gpus * P * c, 90 + k, 1e-3, DEV, BF16).view(gpus, P * c)
+        pieces = torch.empty(gpus, nodes * c, dtype=BF16, device=DEV)
+        for g in range(gpus):                                   # piece g of the pre-shuffled message g2 = [my_gpu]
+            tmp = torch.empty(P * c, dtype=BF16, device=DEV)
+            pccl.pccl_hier_pack(tmp, msgs[g], nodes, gpus)
+            pieces[g].copy_(tmp.view(gpus, nodes * c)[my_gpu])
+        direct.append((torch.empty(c, dtype=BF16, device=DEV), torch.empty(nodes * c, dtype=BF16, device=DEV), msgs))
+        packed.append((torch.empty(c, dtype=BF16, device=DEV), torch.empty(nodes * c, dtype=BF16, device=DEV),
+                       pieces.view(gpus, nodes, c)))
+    pccl.pccl_reduce_scatter_local_unpacked_batched(pccl.BucketTable(direct, nodes=nodes), my_gpu)
+    pccl.pccl_reduce_scatter_local_batched(pccl.BucketTable(packed))
+    _sync()
+    for k in range(len(sizes)):
+        assert torch.equal(direct[k][0].view(torch.int16), packed[k][0].view(torch.int16)), k
+        assert torch.equal(direct[k][1].view(torch.int16), packed[k][1].view(torch.int16)), k
+    k = min(range(len(sizes)), key=lambda j: sizes[j])
+    ws, wp = oracle.reduce_scatter_local_unpacked([to_np(direct[k][2][g]) for g in range(gpus)], nodes, gpus, my_gpu)
+    assert same_bits(to_np(direct[k][0]), ws) and same_bits(to_np(direct[k][1]), wp.reshape(-1))
