@@ -119,18 +119,22 @@ __device__ void reduce_elem(const ReduceProblem& p, size_t e) {
 // `shift` (< BLOCK, in vectors) moves the tile grid: thread t of tile k owns vector
 // k*BLOCK + t - shift, so that the first `shift` threads of tile 0 idle and one more tile may
 // be needed; the caller picks it so that wavefront loads start on cache-line boundaries.
+// `head` (0 or 1 element; only without a kept partial) starts the vectors one element into the
+// buffers, for 16-bit sources that begin in the middle of a 32-bit word; that element joins
+// the ragged tail.
 template <int IN, int OUT, int M, int W, bool FAST, int BLOCK>
-__device__ __forceinline__ void reduce_tile(const ReduceProblem& p, size_t tile, size_t shift = 0) {
+__device__ __forceinline__ void reduce_tile(const ReduceProblem& p, size_t tile, size_t shift = 0,
+                                            size_t head = 0) {
   constexpr int VE = narrow(IN) ? 2 * W : W;  // elements per vector
   constexpr int ES = narrow(IN) ? 2 : 4;
   constexpr int VB = 4 * W;  // bytes per vector
-  const size_t nvec = p.count / VE;
+  const size_t nvec = (p.count - (head < p.count ? head : p.count)) / VE;
   const size_t ntiles_vec = (nvec + shift + BLOCK - 1) / BLOCK;
   const size_t last_tile = ntiles_vec == 0 ? 0 : ntiles_vec - 1;
   // both wrap below zero for the idle head of tile 0: v then fails v < nvec, and tile_off is
   // only ever added to a lane offset that brings the sum back to v * VB
   const size_t v = tile * BLOCK + threadIdx.x - shift;
-  const size_t tile_off = (tile * BLOCK - shift) * (size_t)VB;  // wave-uniform byte offset of the tile
+  const size_t tile_off = (tile * BLOCK - shift) * (size_t)VB + head * ES;  // wave-uniform byte offset of the tile
   const uint32_t lane_off = threadIdx.x * VB;                    // this lane's offset inside the tile
 
   if (v < nvec) {
@@ -207,12 +211,13 @@ __device__ __forceinline__ void reduce_tile(const ReduceProblem& p, size_t tile,
 #pragma unroll
       for (int k = 0; k < VE; ++k) acc[k] = acc[k] / p.divisor;
     }
-    store_vals<OUT, VE, FAST>(reinterpret_cast<char*>(p.dst), v * VE, acc);
+    // the head offset goes into the base, whose alignment the store checks
+    store_vals<OUT, VE, FAST>(reinterpret_cast<char*>(p.dst) + head * (narrow(OUT) ? 2 : 4), v * VE, acc);
   }
 
-  // ragged tail (count not a multiple of the vector width): fewer than VE <= 8 elements
+  // the head element and the ragged tail (what the vectors leave): at most VE <= 8 elements
   if (tile == last_tile) {
-    const size_t e = nvec * VE + threadIdx.x;
+    const size_t e = threadIdx.x < head ? threadIdx.x : nvec * VE + threadIdx.x;
     if (e < p.count) reduce_elem<IN, OUT>(p, e);
   }
 }
@@ -234,6 +239,13 @@ __device__ __forceinline__ size_t line_shift(const void* row_start) {
   const uintptr_t a = reinterpret_cast<uintptr_t>(row_start);
   return (a % VB == 0) ? (a & 127) / VB : 0;
 }
+// 1 when a row of 16-bit elements starts in the middle of a 32-bit word: the vectors then start
+// at its second element (odd chunk element counts put every other row there; measured 78-90 us
+// against 56-58 us for the 8-message share when such rows take the element-wise loads).
+template <int IN>
+__device__ __forceinline__ size_t word_head(const void* row_start) {
+  return narrow(IN) ? (reinterpret_cast<uintptr_t>(row_start) >> 1) & 1 : 0;
+}
 
 // Rows (grid.y > 1: the same reduction over `rows` strided rows of every source) start their
 // tiles kRowSkewTiles further along than the row before, modulo the tiles of a row.  Rows
@@ -247,7 +259,7 @@ constexpr size_t kRowSkewTiles = 131;
 template <int IN, int OUT, int M, bool FAST, int BLOCK>
 __global__ __launch_bounds__(BLOCK) void k_reduce(ReduceProblem p) {
   size_t tile = linear_block_xz();
-  size_t shift = 0;
+  size_t shift = 0, head = 0;
   if (gridDim.y > 1) {
     constexpr size_t VE = (size_t)words_for(M) * (narrow(IN) ? 2 : 1);
     const size_t nvec = p.count / VE;
@@ -260,9 +272,11 @@ __global__ __launch_bounds__(BLOCK) void k_reduce(ReduceProblem p) {
     p.base += row * p.row_stride_src;
     p.src_offset += row * p.row_stride_src;
     p.dst = reinterpret_cast<char*>(p.dst) + row * p.row_stride_dst;
-    shift = line_shift<4 * words_for(M)>(src_ptr<FAST>(p, 0, 0));
+    const char* row_start = src_ptr<FAST>(p, 0, 0);
+    head = word_head<IN>(row_start);
+    shift = line_shift<4 * words_for(M)>(row_start + 2 * head);
   }
-  reduce_tile<IN, OUT, M, words_for(M), FAST, BLOCK>(p, tile, shift);
+  reduce_tile<IN, OUT, M, words_for(M), FAST, BLOCK>(p, tile, shift, head);
 }
 
 inline size_t tiles_for(size_t count, int m, bool in_narrow, int block = kBlock) {
@@ -834,7 +848,8 @@ __global__ __launch_bounds__(kBlockSmall) void k_rs_batched_rows(const pccl_buck
   p.stride_g = b.intra_stride_bytes;
   p.count = b.chunk_count;
   p.gpus = gpus;
-  reduce_tile<DT, DT, M, words_for(M), FAST, kBlockSmall>(p, tile, line_shift<4 * words_for(M)>(p.base));
+  const size_t head = word_head<DT>(p.base);
+  reduce_tile<DT, DT, M, words_for(M), FAST, kBlockSmall>(p, tile, line_shift<4 * words_for(M)>(p.base + 2 * head), head);
 }
 
 template <int DT, int M>
