@@ -2,14 +2,18 @@
 // Sections III-B and IV-B, generalised from "received + local" to N x M sources summed in
 // the fixed intra-node-then-inter-node order of Section IV-A).
 //
-// Two kernel families:
+// Kernel families:
 //   k_reduce            streaming: one thread owns a 4..16-byte vector position and walks
 //                       the sources in order; bandwidth comes from the M independent
-//                       loads per lane and from occupancy.
+//                       loads per lane and from occupancy.  With grid.y > 1 the same over
+//                       strided rows (the share straight from rank-order messages).
 //   k_reduce2l_lds      many small chunks (2048 ranks x 64 KB): a wavefront owns a node,
 //                       the per-node sums of one element slice are staged in LDS and a
 //                       final pass adds them in node order.
-// Both are HBM-bound: (sources - 1) adds per element against >= 2 bytes per operand.
+//   k_flat_lds          flat sum of more than 16 short sources (phase 2 at large node
+//                       counts): raw words staged in LDS, ordered pass one tile behind.
+//   k_rs_batched[_rows] the streaming tile body over a flat tile space of many buckets.
+// All are HBM-bound: (sources - 1) adds per element against >= 2 bytes per operand.
 #include <cstdlib>
 
 #include "device_utils.h"
