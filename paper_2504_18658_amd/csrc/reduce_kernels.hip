@@ -573,18 +573,15 @@ hipError_t launch_lds_io(const ReduceProblem& p, hipStream_t st) {
 // result is bit-identical to the streaming kernel's.
 // A slice is only 256 bytes of each source, so when sources do not start on a cache line every
 // line a block touches at the edge of its slice is also needed by the block of the next slice.
-// Two measures keep that second access out of HBM: neighbouring slices run on the same XCD
-// (kFlatXcdMajor), and the loads are ordinary cached ones rather than streaming ones
-// (kFlatCachedLoads).  32 MB of bf16 in 32 / 64 / 128 / 256 sources whose size is 16 bytes
+// Two measures (template LOCAL) keep that second access out of HBM: neighbouring slices run
+// on the same XCD, and the loads are ordinary cached ones rather than streaming ones.  32 MB of bf16 in 32 / 64 / 128 / 256 sources whose size is 16 bytes
 // off a multiple of 128: 13.0 / 16.9 / 21.3 / 21.5 us without, 9.0 / 9.8 / 13.1 / 14.7 us
 // with both; sources on line boundaries: 9.1 / 9.4 / 9.0 / 10.5 against 8.2 / 8.3 / 8.4 /
 // 10.7 us.  Either measure alone gains about half of that.
 constexpr int kFlatNpt = 8;
-constexpr int kFlatXcdMajor = 1;
-constexpr int kFlatCachedLoads = 2;
 
-template <int IN, int OUT, int WAVES>
-__global__ __launch_bounds__(WAVES * 64) void k_flat_lds(ReduceProblem p, int mode) {
+template <int IN, int OUT, int WAVES, bool LOCAL>
+__global__ __launch_bounds__(WAVES * 64) void k_flat_lds(ReduceProblem p) {
   constexpr int EPL = narrow(IN) ? 2 : 1;
   constexpr int TN = WAVES * kFlatNpt;
   __shared__ uint32_t parked[2][TN * 64];
@@ -592,7 +589,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_flat_lds(ReduceProblem p, int mo
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const size_t nwords = (p.count + EPL - 1) / EPL;  // a ragged last word counts
   size_t slice = linear_block_xz();
-  if (mode & kFlatXcdMajor) {
+  if (LOCAL) {
     // workgroups are dealt to the 8 XCDs round-robin: give XCD x the contiguous range of
     // slices [x*per, (x+1)*per), so that neighbouring slices share an L2
     const size_t per = ((nwords + 63) / 64 + 7) / 8;
@@ -647,7 +644,10 @@ __global__ __launch_bounds__(WAVES * 64) void k_flat_lds(ReduceProblem p, int mo
 #pragma unroll
       for (int q = 0; q < kFlatNpt; ++q) {
         const char* a = lane_pointer(cur, q) + 4 * (w0 + lane);
-        raw[q] = (mode & kFlatCachedLoads) ? *((const PCCL_GLOBAL uint32_t*)a) : ld_stream<uint32_t>(a);
+        if constexpr (LOCAL)
+          raw[q] = *((const PCCL_GLOBAL uint32_t*)a);
+        else
+          raw[q] = ld_stream<uint32_t>(a);
       }
     } else {
 #pragma unroll
@@ -713,17 +713,23 @@ hipError_t launch_flat_lds_io(const ReduceProblem& p, hipStream_t st) {
     const int w = std::atoi(v);
     if (w == 4 || w == 8 || w == 16) waves = w;
   }
-  int mode = kFlatXcdMajor | kFlatCachedLoads;
-  if (const char* v = std::getenv("PCCL_FLAT_MODE")) mode = std::atoi(v) & 3;  // for A/B runs
-  const size_t launch_blocks = (mode & kFlatXcdMajor) ? (blocks + 7) / 8 * 8 : blocks;
+  bool local = true;
+  if (const char* v = std::getenv("PCCL_FLAT_LOCAL")) local = v[0] != '0';  // for A/B runs
+  const size_t launch_blocks = local ? (blocks + 7) / 8 * 8 : blocks;
   if (!split_grid_xz(launch_blocks, (unsigned)waves * 64, &gx, &gz)) return hipErrorInvalidValue;
   const dim3 grid(gx, 1, gz), block((unsigned)waves * 64);
-  if (waves == 4)
-    hipLaunchKernelGGL((k_flat_lds<IN, OUT, 4>), grid, block, 0, st, p, mode);
+  if (waves == 4 && local)
+    hipLaunchKernelGGL((k_flat_lds<IN, OUT, 4, true>), grid, block, 0, st, p);
+  else if (waves == 4)
+    hipLaunchKernelGGL((k_flat_lds<IN, OUT, 4, false>), grid, block, 0, st, p);
+  else if (waves == 8 && local)
+    hipLaunchKernelGGL((k_flat_lds<IN, OUT, 8, true>), grid, block, 0, st, p);
   else if (waves == 8)
-    hipLaunchKernelGGL((k_flat_lds<IN, OUT, 8>), grid, block, 0, st, p, mode);
+    hipLaunchKernelGGL((k_flat_lds<IN, OUT, 8, false>), grid, block, 0, st, p);
+  else if (local)
+    hipLaunchKernelGGL((k_flat_lds<IN, OUT, 16, true>), grid, block, 0, st, p);
   else
-    hipLaunchKernelGGL((k_flat_lds<IN, OUT, 16>), grid, block, 0, st, p, mode);
+    hipLaunchKernelGGL((k_flat_lds<IN, OUT, 16, false>), grid, block, 0, st, p);
   return hipGetLastError();
 }
 
