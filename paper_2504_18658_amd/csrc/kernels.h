@@ -36,6 +36,7 @@ struct ReduceProblem {
   int override_index;  // -1: none
   int round_partial;
   int rows;
+  int row_pad;  // rows > 1: one more tile per row, so that a row's tile grid can be shifted onto cache lines
   float divisor;
 };
 

@@ -72,6 +72,7 @@ ReduceProblem blank_problem() {
   p.override_index = -1;
   p.round_partial = 0;
   p.rows = 1;
+  p.row_pad = 0;
   p.divisor = 0.0f;
   return p;
 }
@@ -457,9 +458,12 @@ pccl_status_t pccl_reduce_scatter_local_unpacked(void* shard, void* partial, con
   if (d_msgs == nullptr) {
     p1.base = reinterpret_cast<const char*>(msgs_base) + (size_t)my_gpu * chunk_bytes;
     p1.stride_g = gpus_per_node > 1 ? msg_stride_bytes : 0;
+    // every row of the first message starts on a cache line when the message and the chunk do
+    p1.row_pad = (reinterpret_cast<uintptr_t>(msgs_base) % 128 != 0 || chunk_bytes % 128 != 0) ? 1 : 0;
   } else {
     p1.ptrs = d_msgs;
     p1.src_offset = (size_t)my_gpu * chunk_bytes;
+    p1.row_pad = 1;  // the messages' addresses are on the device
   }
   const hipError_t e = pccl::launch_reduce(p1, dt, dt, st);
   if (e != hipSuccess) return e == hipErrorInvalidValue ? PCCL_ERR_INVALID : PCCL_ERR_HIP;

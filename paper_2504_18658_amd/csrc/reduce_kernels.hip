@@ -269,16 +269,18 @@ __global__ __launch_bounds__(BLOCK) void k_reduce(ReduceProblem p) {
     const size_t nvec = p.count / VE;
     size_t ntiles = (nvec + BLOCK - 1) / BLOCK;
     if (ntiles == 0) ntiles = 1;       // a lone ragged tail
-    ntiles += 1;                       // room for the line shift below
+    ntiles += p.row_pad;               // room for the line shift below
     if (tile >= ntiles) return;        // the x*z rectangle is rounded up
     const size_t row = blockIdx.y;
     tile = (tile + row * kRowSkewTiles) % ntiles;
     p.base += row * p.row_stride_src;
     p.src_offset += row * p.row_stride_src;
     p.dst = reinterpret_cast<char*>(p.dst) + row * p.row_stride_dst;
-    const char* row_start = src_ptr<FAST>(p, 0, 0);
-    head = word_head<IN>(row_start);
-    shift = line_shift<4 * words_for(M)>(row_start + 2 * head);
+    if (p.row_pad) {
+      const char* row_start = src_ptr<FAST>(p, 0, 0);
+      head = word_head<IN>(row_start);
+      shift = line_shift<4 * words_for(M)>(row_start + 2 * head);
+    }
   }
   reduce_tile<IN, OUT, M, words_for(M), FAST, BLOCK>(p, tile, shift, head);
 }
@@ -302,8 +304,8 @@ inline bool fast_eligible(const ReduceProblem& p, bool in_narrow) {
 
 template <int IN, int OUT, int M, int BLOCK>
 hipError_t launch_mb(const ReduceProblem& p, hipStream_t st) {
-  // rows: one more tile per row, for the line shift
-  const size_t tiles = tiles_for(p.count, M, narrow(IN), BLOCK) + (p.rows > 1 ? 1 : 0);
+  // rows that may start off a cache line: one more tile per row, for the line shift
+  const size_t tiles = tiles_for(p.count, M, narrow(IN), BLOCK) + (p.rows > 1 ? p.row_pad : 0);
   unsigned gx, gz;
   if (p.rows < 1 || p.rows > 65535 || !split_grid_xz(tiles, BLOCK, &gx, &gz)) return hipErrorInvalidValue;
   if (p.rows > 1 && p.partial != nullptr) return hipErrorInvalidValue;
@@ -764,6 +766,7 @@ __global__ __launch_bounds__(kBlock) void k_rs_batched(const pccl_bucket_t* __re
   p.row_stride_src = 0;
   p.row_stride_dst = 0;
   p.rows = 1;
+  p.row_pad = 0;
   p.divisor = PHASE == 2 ? divisor : 0.0f;
   if (PHASE == 1) {  // partial[n][e] = sum over g' of piece_g'[n][e]
     p.dst = b.partial;
@@ -852,6 +855,7 @@ __global__ __launch_bounds__(kBlockSmall) void k_rs_batched_rows(const pccl_buck
   p.row_stride_src = 0;
   p.row_stride_dst = 0;
   p.rows = 1;
+  p.row_pad = 0;
   p.divisor = 0.0f;
   p.dst = reinterpret_cast<char*>(b.partial) + (size_t)row * chunk_bytes;
   p.base = reinterpret_cast<const char*>(b.intra_base) + ((size_t)row * gpus + my_gpu) * chunk_bytes;
