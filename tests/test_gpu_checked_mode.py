@@ -109,6 +109,13 @@ def test_valid_calls_are_unchanged_in_checked_mode(monkeypatch, level):
     assert same_bits(to_np(s1), ws) and same_bits(to_np(p1), wp.reshape(-1))
     assert same_bits(to_np(back), oracle.hier_pack(to_np(msgs_h[1]), n, g).view(np.uint16))
 
+    s3, p3 = torch.empty(c, dtype=BF16, device=DEV), torch.empty(n * c, dtype=BF16, device=DEV)
+    mtable = pccl.BucketTable([(s3, p3, msgs)], nodes=n)
+    pccl.pccl_reduce_scatter_local_unpacked_batched(mtable, 1)
+    _sync()
+    ws, wp = oracle.reduce_scatter_local_unpacked([to_np(msgs_h[k]) for k in range(g)], n, g, 1)
+    assert same_bits(to_np(s3), ws) and same_bits(to_np(p3), wp.reshape(-1))
+
     ring_h = W.normal(4 * c, 9, 1.0, "cpu", BF16).view(4, c)
     recv_h = W.normal(3 * c, 10, 1.0, "cpu", BF16).view(3, c)
     ring = ring_h.to(DEV)
