@@ -576,10 +576,11 @@ hipError_t launch_lds_io(const ReduceProblem& p, hipStream_t st) {
 // A slice is only 256 bytes of each source, so when sources do not start on a cache line every
 // line a block touches at the edge of its slice is also needed by the block of the next slice.
 // Two measures (template LOCAL) keep that second access out of HBM: neighbouring slices run
-// on the same XCD, and the loads are ordinary cached ones rather than streaming ones.  32 MB of bf16 in 32 / 64 / 128 / 256 sources whose size is 16 bytes
-// off a multiple of 128: 13.0 / 16.9 / 21.3 / 21.5 us without, 9.0 / 9.8 / 13.1 / 14.7 us
-// with both; sources on line boundaries: 9.1 / 9.4 / 9.0 / 10.5 against 8.2 / 8.3 / 8.4 /
-// 10.7 us.  Either measure alone gains about half of that.
+// on the same XCD, and the loads are ordinary cached ones rather than streaming ones.
+// Measured over 40 rotating 32 MB sets of bf16 (far more than the last-level cache holds), in
+// 32 / 64 / 128 / 256 sources whose size is 16 bytes off a multiple of 128: 13.1 / 17.3 /
+// 21.6 / 21.5 us without, 10.0 / 10.3 / 13.7 / 15.4 us with; sources on line boundaries run
+// the same either way (9.1-9.5 / 9.0-9.5 / 8.9 / 10.7-11.4 us).
 constexpr int kFlatNpt = 8;
 
 template <int IN, int OUT, int WAVES, bool LOCAL>
