@@ -767,3 +767,44 @@ def test_batched_share_from_messages_equals_pack_then_batched_share_at_size():
     k = min(range(len(sizes)), key=lambda j: sizes[j])
     ws, wp = oracle.reduce_scatter_local_unpacked([to_np(direct[k][2][g]) for g in range(gpus)], nodes, gpus, my_gpu)
     assert same_bits(to_np(direct[k][0]), ws) and same_bits(to_np(direct[k][1]), wp.reshape(-1))
+
+
+def test_share_at_128_nodes_in_the_benchmarked_launch_configuration():
+    """The 128 x 8 rank, 256 MB bf16 all-reduce share that bench.py times, at full size: the
+    pre-shuffle of 256 KB chunks, phase 1 from pre-shuffled pieces and straight from the eight
+    rank-order messages (128 rows), phase 2 over 128 received chunks, the reassembly."""
+    nodes, gpus, my_node, my_gpu = 128, 8, 77, 3
+    P = nodes * gpus
+    c = (256 << 20) // P // 2
+    msgs = W.uniform_pm1(gpus * P * c, 700, DEV, BF16).view(gpus, P * c)
+    inter = W.uniform_pm1(nodes * c, 710, DEV, BF16).view(nodes, c)
+    d_inter = pccl.device_pointer_array([inter[j] for j in range(nodes)])
+    want_inter = [to_np(inter[j]) for j in range(nodes)]
+    packed, out = Guarded(P * c, BF16), Guarded(P * c, BF16)
+    pccl.pccl_hier_pack(packed.view, msgs[0], nodes, gpus)
+    pccl.pccl_allgather_reassemble(out.view, src=msgs[1], nodes=nodes, gpus_per_node=gpus)
+    _sync()
+    assert same_bits(to_np(packed.view), oracle.hier_pack(to_np(msgs[0]), nodes, gpus))
+    assert same_bits(to_np(out.view), oracle.hier_unpack(to_np(msgs[1]), nodes, gpus))
+    packed.check()
+    out.check()
+    # from pre-shuffled pieces: the first message's bytes stand for [gpu][node][chunk]
+    x = msgs[0].view(gpus, nodes, c)
+    partial, shard = Guarded(nodes * c, BF16), Guarded(c, BF16)
+    pccl.pccl_reduce_scatter_local(shard.view, partial.view, x, d_inter=d_inter, my_node=my_node)
+    _sync()
+    ws, wp = oracle.reduce_scatter_local(to_np(x), my_node=my_node, inter=want_inter, nthreads=16)
+    assert same_bits(to_np(partial.view), wp.reshape(-1)) and same_bits(to_np(shard.view), ws)
+    partial.check()
+    shard.check()
+    # straight from the messages
+    partial2, shard2 = Guarded(nodes * c, BF16), Guarded(c, BF16)
+    pccl.pccl_reduce_scatter_local_unpacked(shard2.view, partial2.view, msgs=msgs, d_inter=d_inter, nodes=nodes,
+                                            gpus_per_node=gpus, my_node=my_node, my_gpu=my_gpu)
+    _sync()
+    ws, wp = oracle.reduce_scatter_local_unpacked([to_np(msgs[g]) for g in range(gpus)], nodes, gpus, my_gpu,
+                                                  my_node=my_node, inter=want_inter, nthreads=16)
+    assert same_bits(to_np(partial2.view), wp.reshape(-1)), first_diff(to_np(partial2.view), wp.reshape(-1))
+    assert same_bits(to_np(shard2.view), ws)
+    partial2.check()
+    shard2.check()
