@@ -19,13 +19,19 @@ namespace {
 
 constexpr int kPermBlock = 64;                        // one wavefront
 constexpr size_t kPermTile = (size_t)kPermBlock * 16;  // bytes per block
-// Chunk (r, c) starts (r + c) * kSkewTiles tiles into itself when chunks are this long and a
-// multiple of kSkewRound (the rotation undoes a resonance between chunks a round number of
-// bytes apart; with chunk sizes that are multiples of 16 bytes only -- the 40-bucket batch --
-// it costs 5 %).
+// Chunk (r, c) starts (r + c) * kSkewTiles tiles into itself when chunks are a multiple of
+// kSkewRound (the rotation undoes a resonance between chunks a round number of bytes apart;
+// with chunk sizes that are multiples of 16 bytes only -- the 40-bucket batch -- it costs 5 %)
+// and of a size where it was measured to pay: from 512 KB up (1-7 %), and at 64 KB-128 KB
+// (the 2048 x 64 KB reassembly: 46.1 -> 43.0 us), not at 128-256 KB and not below 64 KB
+// (up to 18 % slower).  How strong the resonance is depends on the physical placement the
+// process got, so these are averages over runs from two different host programs.
 constexpr uint32_t kSkewTiles = 131;
-constexpr size_t kSkewMinChunk = (size_t)512 << 10;
 constexpr size_t kSkewRound = (size_t)64 << 10;
+inline bool skew_pays(size_t chunk_bytes) {
+  if (chunk_bytes % kSkewRound != 0) return false;
+  return chunk_bytes >= ((size_t)512 << 10) || chunk_bytes < ((size_t)128 << 10);
+}
 
 // `len` <= kPermTile bytes by one wavefront: a 128-bit load and store per lane when both sides
 // are 16-byte aligned, narrower accesses otherwise, single bytes for what is left.
@@ -179,8 +185,8 @@ hipError_t launch_permute(const PermuteProblem& p, hipStream_t st) {
     // Chunk (r, c) starts (r + c) * skew tiles into itself, modulo its tile count: the resident
     // blocks otherwise sit at the same offset of several chunks a power of two apart.  Measured
     // with 131 tiles: 1-7 % faster for chunks of 512 KB-1 MB (256 MB as 64x8: 85.8 -> 79.5 us,
-    // 128 MB as 32x8: 43.7 -> 40.9 us), no change from 2 MB up, slower below 256 KB.
-    uint32_t skew = (p.chunk_bytes >= kSkewMinChunk && p.chunk_bytes % kSkewRound == 0) ? kSkewTiles : 0u;
+    // 128 MB as 32x8: 43.7 -> 40.9 us), no change from 2 MB up; see skew_pays() for the rest.
+    uint32_t skew = skew_pays(p.chunk_bytes) ? kSkewTiles : 0u;
     if (const char* v = std::getenv("PCCL_PERMUTE_SKEW")) skew = (uint32_t)std::atoi(v);
     if (cfast)
       hipLaunchKernelGGL((k_permute<true, true>), dim3((unsigned)tiles_per_chunk, (unsigned)p.cols, (unsigned)p.rows),
