@@ -652,6 +652,40 @@ __global__ __launch_bounds__(WAVES * 64) void k_flat_lds(ReduceProblem p) {
         else
           raw[q] = ld_stream<uint32_t>(a);
       }
+    } else if (narrow(IN) && nvalid == kFlatNpt && slice_full && !__any((int)(cur & 1))) {
+      // Some source starts in the middle of a 32-bit word (an odd number of 16-bit elements
+      // per chunk puts every other chunk there).  Every lane loads the ALIGNED word that
+      // holds its first element; for a mid-word source the lane's second element is the low
+      // half of the next lane's word (lane 63 fetches that word itself).  Every word read
+      // holds at least one element of the slice, and no access is narrower than 32 bits.
+      uint32_t lo_word[kFlatNpt], next_word[kFlatNpt];
+#pragma unroll
+      for (int q = 0; q < kFlatNpt; ++q) {
+        const uintptr_t sp = reinterpret_cast<uintptr_t>(lane_pointer(cur, q));
+        const char* a = reinterpret_cast<const char*>(sp & ~(uintptr_t)3) + 4 * (w0 + lane);
+        if constexpr (LOCAL)
+          lo_word[q] = *((const PCCL_GLOBAL uint32_t*)a);
+        else
+          lo_word[q] = ld_stream<uint32_t>(a);
+      }
+#pragma unroll
+      for (int q = 0; q < kFlatNpt; ++q) {
+        const uintptr_t sp = reinterpret_cast<uintptr_t>(lane_pointer(cur, q));
+        next_word[q] = 0;
+        if ((sp & 2) && lane == 63)
+          next_word[q] = ld_stream<uint32_t>(reinterpret_cast<const char*>(sp & ~(uintptr_t)3) + 4 * (w0 + 64));
+      }
+#pragma unroll
+      for (int q = 0; q < kFlatNpt; ++q) {
+        const uintptr_t sp = reinterpret_cast<uintptr_t>(lane_pointer(cur, q));
+        if (sp & 2) {
+          uint32_t nb = __shfl_down(lo_word[q], 1);
+          if (lane == 63) nb = next_word[q];
+          raw[q] = (lo_word[q] >> 16) | (nb << 16);
+        } else {
+          raw[q] = lo_word[q];
+        }
+      }
     } else {
 #pragma unroll
       for (int q = 0; q < kFlatNpt; ++q)
