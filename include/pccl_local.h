@@ -39,7 +39,8 @@
  *              descriptor tables are checked as ranges only.  PCCL_CHECK_POINTERS=2 also
  *              copies those arrays back on `stream`, WAITS for the stream, checks every
  *              pointer in them and compares a descriptor table with its host mirror
- *              (PCCL_ERR_INVALID when they differ): not for use under graph capture.  About
+ *              (PCCL_ERR_INVALID when they differ); on a stream that is being captured
+ *              into a graph it behaves as level 1.  About
  *              a microsecond per range; off when unset or 0.  Memory handed out by a
  *              caching sub-allocator is checked against the block it was carved from.
  *   Empty      count == 0 / chunk_bytes == 0 / chunk_count == 0 / nbuckets == 0 succeed

@@ -39,7 +39,13 @@ struct AddressChecks {
   hipStream_t st;
   pccl_status_t status;
   explicit AddressChecks(pccl_stream_t stream)
-      : level(pccl::address_check_level()), st(reinterpret_cast<hipStream_t>(stream)), status(PCCL_OK) {}
+      : level(pccl::address_check_level()), st(reinterpret_cast<hipStream_t>(stream)), status(PCCL_OK) {
+    if (level > 1) {  // level 2 copies tables back and waits: not possible while the stream is being captured
+      hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
+      if (hipStreamIsCapturing(st, &capturing) != hipSuccess) (void)hipGetLastError();
+      if (capturing != hipStreamCaptureStatusNone) level = 1;
+    }
+  }
   bool on() const { return level > 0; }
   void range(const void* p, size_t bytes) {
     if (level > 0 && status == PCCL_OK) status = pccl::check_range(p, bytes);
