@@ -49,7 +49,8 @@
  *              that are multiples of 16 bytes take the 128-bit path; others take a slower
  *              element-wise path with identical results.  Multiples of 128 bytes (a cache
  *              line) are fastest: a shuffle whose chunk size is only a multiple of 16 loses
- *              about 5 % to source reads that straddle lines, a two-level reduce-scatter
+ *              about 5 % to source reads that straddle lines (10 % with odd multiples of 2
+ *              bytes, 18 % with odd byte counts), a two-level reduce-scatter
  *              share 5-10 %, and one whose chunks hold an odd number of 16-bit elements
  *              about 20 % (every other chunk then starts in the middle of a 32-bit word).
  *   Sizes      Counts and byte sizes are size_t; buffers beyond 4 GiB are fine.  The largest
