@@ -35,7 +35,7 @@ HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
 # HBM bytes per 256 MB k_permute launch from the two rocprofv3 --pmc runs summarised in
 # profiles/k_permute_256MB_16x8.txt: FETCH_SIZE 131086.6 KiB (x 2.000, the factor a plain
 # 256 MiB copy calibrates) + WRITE_SIZE 262203.2 KiB (x 1.000).
-PROFILED_PERMUTE_TRAFFIC_BYTES = int((131088.9 * 2.000 + 262189.4 * 1.000) * 1024)
+PROFILED_PERMUTE_TRAFFIC_BYTES = int((131091.8 * 2.000 + 262188.0 * 1.000) * 1024)
 MB = 1 << 20
 
 
