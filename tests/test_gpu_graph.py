@@ -27,12 +27,16 @@ def test_captured_all_reduce_share_replays_match_eager_and_oracle():
     ptrs = pccl.device_pointer_array([srcs[k] for k in range(64 * 8)])
     recv = W.draw(w, 7 * C, DEV, seed_offset=7).view(7, C)
     ring0 = W.draw(w, 8 * C, DEV, seed_offset=8).view(8, C)
+    many = W.draw(w, 40 * 3001, DEV, seed_offset=9).view(40, 3001)        # 40 sources: the LDS-staged flat sum
+    odd = W.draw(w, P * 1501 + 1, DEV, seed_offset=10)[1:]                # a message whose chunks start mid-word
 
     def buffers():
         return dict(packed=torch.empty_like(msg), partial=torch.empty(w.nodes * C, dtype=w.dtype, device=DEV),
                     shard=torch.empty(C, dtype=w.dtype, device=DEV), partial2=torch.empty(w.nodes * C, dtype=w.dtype, device=DEV),
                     shard2=torch.empty(C, dtype=w.dtype, device=DEV), out=torch.empty_like(gathered),
-                    small=torch.empty(512, dtype=torch.float32, device=DEV), ring=torch.empty_like(ring0))
+                    small=torch.empty(512, dtype=torch.float32, device=DEV), ring=torch.empty_like(ring0),
+                    flat=torch.empty(3001, dtype=w.dtype, device=DEV), oddpacked=torch.empty(P * 1501, dtype=w.dtype, device=DEV),
+                    shard3=torch.empty(C, dtype=w.dtype, device=DEV), partial3=torch.empty(w.nodes * C, dtype=w.dtype, device=DEV))
 
     def step(b):
         pccl.pccl_hier_pack(b["packed"], msg, w.nodes, w.gpus)
@@ -43,12 +47,19 @@ def test_captured_all_reduce_share_replays_match_eager_and_oracle():
         pccl.pccl_local_reduce_ptrs_two_level(b["small"], ptrs, 64, 8, 512, w.dtype)
         b["ring"].copy_(ring0)                      # the replay mutates its message in place: reset it first
         pccl.pccl_ring_reduce_scatter_local(b["ring"], recv, 3)
+        pccl.pccl_local_reduce(b["flat"], many)
+        pccl.pccl_hier_pack(b["oddpacked"], odd, w.nodes, w.gpus)
+        pccl.pccl_reduce_scatter_local_unpacked_batched(b["table"], 5)
 
-    eager = buffers()
+    def with_table(b):
+        b["table"] = pccl.BucketTable([(b["shard3"], b["partial3"], msgs)], nodes=w.nodes)   # built outside the capture
+        return b
+
+    eager = with_table(buffers())
     step(eager)
     torch.cuda.synchronize()
 
-    cap = buffers()
+    cap = with_table(buffers())
     g = torch.cuda.CUDAGraph()
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
@@ -60,16 +71,22 @@ def test_captured_all_reduce_share_replays_match_eager_and_oracle():
         step(cap)
     for replay in range(4):
         for t in cap.values():
-            t.view(torch.int16 if t.element_size() == 2 else torch.int32).fill_(0x5A5A)   # poison by an eager kernel
+            if isinstance(t, torch.Tensor):
+                t.view(torch.int16 if t.element_size() == 2 else torch.int32).fill_(0x5A5A)   # poison by an eager kernel
         torch.cuda.synchronize()
         g.replay()
         torch.cuda.synchronize()
         for k in eager:
-            assert same_bits(to_np(cap[k]), to_np(eager[k])), (replay, k)
-        step(buffers())                             # eager work between replays
+            if isinstance(eager[k], torch.Tensor):
+                assert same_bits(to_np(cap[k]), to_np(eager[k])), (replay, k)
+        step(with_table(buffers()))                 # eager work between replays
         torch.cuda.synchronize()
     # and the eager result itself is the oracle's
     ws, wp = oracle.reduce_scatter_local(to_np(x), my_node=1, inter=[to_np(inter[n]) for n in range(w.nodes)], average=True)
     assert same_bits(to_np(eager["shard"]), ws) and same_bits(to_np(eager["partial"]), wp.reshape(-1))
     assert same_bits(to_np(eager["packed"]), oracle.hier_pack(to_np(msg), w.nodes, w.gpus))
     assert same_bits(to_np(eager["ring"]), oracle.ring_rs_local(to_np(ring0), [to_np(recv[s]) for s in range(7)], 3))
+    assert same_bits(to_np(eager["flat"]), oracle.flat_reduce([to_np(many[s]) for s in range(40)]))
+    assert same_bits(to_np(eager["oddpacked"]), oracle.hier_pack(to_np(odd), w.nodes, w.gpus))
+    ws, wp = oracle.reduce_scatter_local_unpacked([to_np(msgs[g]) for g in range(w.gpus)], w.nodes, w.gpus, 5)
+    assert same_bits(to_np(eager["shard3"]), ws) and same_bits(to_np(eager["partial3"]), wp.reshape(-1))
