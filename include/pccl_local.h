@@ -31,7 +31,8 @@
  *              effect.  A failed launch is reported as PCCL_ERR_HIP.
  *   Checked    Raw pointers cannot be checked for free, and a kernel given a host pointer
  *              or a range longer than its allocation takes a GPU memory fault.  With the
- *              environment variable PCCL_CHECK_POINTERS=1 every call, once its arguments
+ *              environment variable PCCL_CHECK_POINTERS=1 (read when the library is loaded,
+ *              see pccl_diag_reload_env) every call, once its arguments
  *              have passed the checks above, asks the HIP runtime whether each range the
  *              host can see lies inside ONE allocation that kernels can address (device,
  *              managed or pinned host memory) and returns PCCL_ERR_ADDRESS instead of
@@ -329,6 +330,16 @@ double pccl_model_two_level(int nodes, int gpus_per_node, double m_bytes, pccl_a
  * [ptr, ptr + bytes) lies inside one allocation that kernels of the current device can address
  * or bytes == 0, PCCL_ERR_NULL for NULL with bytes > 0, else PCCL_ERR_ADDRESS. */
 pccl_status_t pccl_check_device_range(const void* ptr, size_t bytes);
+
+/* Diagnostics.  The library reads a handful of PCCL_* environment variables (checked mode
+ * above; switches that pin a kernel or a block shape for tests and profiler A/B runs) ONCE,
+ * when it is loaded; no call looks at the environment afterwards.  This reads them again.
+ * Not safe against calls running at the same time on other threads. */
+void pccl_diag_reload_env(void);
+
+/* Identity of the sources the library was built from (a hash the build script passes in;
+ * "unknown" for a build made without it).  Static string, never NULL. */
+const char* pccl_build_id(void);
 
 /* Static, human-readable name of a status code (never NULL). */
 const char* pccl_status_string(pccl_status_t status);

@@ -5,7 +5,6 @@ current torch stream becomes the hipStream_t.  Every step of the path runs in th
 kernels; there is no fallback: if the library cannot be loaded or built, calls raise.
 """
 import ctypes
-import os
 
 import torch
 
@@ -23,10 +22,11 @@ EXPORTS = (
     "pccl_reduce_scatter_local_unpacked", "pccl_ring_reduce_scatter_local",
     "pccl_allgather_reassemble_batched", "pccl_hier_pack_batched", "pccl_halving_reduce_scatter_local", "pccl_model_ring", "pccl_model_rec",
     "pccl_choose_algorithm", "pccl_model_two_level", "pccl_status_string", "pccl_check_device_range",
-    "pccl_reduce_scatter_local_unpacked_batched",
+    "pccl_reduce_scatter_local_unpacked_batched", "pccl_diag_reload_env", "pccl_build_id",
 )
 PCCL_ALGO_RING, PCCL_ALGO_REC = 0, 1
-_NO_STATUS = ("pccl_status_string", "pccl_model_ring", "pccl_model_rec", "pccl_model_two_level")
+_NO_STATUS = ("pccl_status_string", "pccl_model_ring", "pccl_model_rec", "pccl_model_two_level",
+              "pccl_diag_reload_env", "pccl_build_id")
 
 
 class pccl_link_model_t(ctypes.Structure):
@@ -54,11 +54,12 @@ _lib = None
 
 
 def lib():
-    """The loaded shared library (built in-tree with hipcc if it is not there yet)."""
+    """The loaded shared library.  A library that is missing, or that was built from other
+    sources than the ones on disk, is rebuilt in-tree with hipcc first; there is no fallback."""
     global _lib
     if _lib is None:
         path = _build.LIB
-        if not os.path.exists(path):
+        if _build.is_stale():
             path = _build.build(force=True)
         L = ctypes.CDLL(path)
         vp, i, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
@@ -88,10 +89,20 @@ def lib():
             if name not in _NO_STATUS:
                 getattr(L, name).restype = i
         L.pccl_check_device_range.argtypes = [vp, ctypes.c_size_t]
+        L.pccl_build_id.argtypes = []
+        L.pccl_build_id.restype = ctypes.c_char_p
+        L.pccl_diag_reload_env.argtypes = []
+        L.pccl_diag_reload_env.restype = None
         L.pccl_status_string.argtypes = [i]
         L.pccl_status_string.restype = ctypes.c_char_p
         _lib = L
     return _lib
+
+
+def diag_reload_env():
+    """Have the library read its PCCL_* diagnostic switches from the environment again (it reads
+    them once, when it is loaded)."""
+    lib().pccl_diag_reload_env()
 
 
 def status_string(status):

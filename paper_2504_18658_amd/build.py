@@ -1,4 +1,5 @@
 """Build libpccl_local.so (HIP kernels + C ABI) for gfx950 with hipcc, in-tree."""
+import hashlib
 import os
 import shutil
 import subprocess
@@ -7,8 +8,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpccl_local.so")
 SOURCES = ["pccl_api.hip", "reduce_kernels.hip", "permute_kernels.hip", "step_kernels.hip",
-           "cost_model.hip", "address_check.hip"]
-HEADERS = ["device_utils.h", "kernels.h", "address_check.h", os.path.join("..", "..", "include", "pccl_local.h")]
+           "cost_model.hip", "address_check.hip", "knobs.hip"]
+HEADERS = ["device_utils.h", "kernels.h", "address_check.h", "knobs.h", os.path.join("..", "..", "include", "pccl_local.h")]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
@@ -27,12 +28,33 @@ def hipcc():
     return exe
 
 
+ID_MARKER = b"pccl-build-id:"
+
+
+def source_id():
+    """Identity of what a build is made from: the compiler flags and the bytes of every source and header."""
+    h = hashlib.sha256(" ".join(HIPCC_FLAGS).encode())
+    for name in SOURCES + HEADERS:
+        h.update(name.encode())
+        with open(os.path.join(CSRC, name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+def built_id(path=LIB):
+    """The source identity compiled into a built library (None when the file or the marker is missing)."""
+    try:
+        with open(path, "rb") as f:
+            data = f.read()
+    except OSError:
+        return None
+    k = data.find(ID_MARKER)
+    return data[k + len(ID_MARKER):k + len(ID_MARKER) + 16].decode("ascii", "replace") if k >= 0 else None
+
+
 def is_stale():
-    if not os.path.exists(LIB):
-        return True
-    t = os.path.getmtime(LIB)
-    deps = [os.path.join(CSRC, s) for s in SOURCES + HEADERS]
-    return any(os.path.getmtime(d) > t for d in deps)
+    """True when the library on disk was not built from the sources on disk (file times play no part)."""
+    return built_id() != source_id()
 
 
 def build(force=True, verbose=False):
@@ -40,7 +62,8 @@ def build(force=True, verbose=False):
     if not force and not is_stale():
         return LIB
     tmp = LIB + ".tmp.%d" % os.getpid()
-    cmd = [hipcc(), *HIPCC_FLAGS, *[os.path.join(CSRC, s) for s in SOURCES], "-o", tmp]
+    cmd = [hipcc(), *HIPCC_FLAGS, '-DPCCL_BUILD_ID="%s"' % source_id(),
+           *[os.path.join(CSRC, s) for s in SOURCES], "-o", tmp]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.check_call(cmd)

@@ -1,18 +1,15 @@
 // Host-only: address checks behind PCCL_CHECK_POINTERS (see address_check.h).
 #include "address_check.h"
 
+#include "knobs.h"
+
 #include <cstdint>
-#include <cstdlib>
 #include <cstring>
 #include <vector>
 
 namespace pccl {
 
-int address_check_level() {
-  const char* v = std::getenv("PCCL_CHECK_POINTERS");
-  if (v == nullptr || v[0] == '\0' || v[0] == '0') return 0;
-  return v[0] == '2' ? 2 : 1;
-}
+int address_check_level() { return knobs().check_pointers; }
 
 pccl_status_t check_range(const void* p, size_t bytes) {
   if (bytes == 0) return PCCL_OK;

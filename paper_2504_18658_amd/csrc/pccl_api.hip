@@ -3,11 +3,11 @@
 // side effect and the error paths can be exercised on a machine without a GPU.  With
 // PCCL_CHECK_POINTERS set, a call that passed those checks then asks the runtime whether every
 // range lies inside memory a kernel can reach, and launches only if so.
-#include <cstdlib>
 
 #include "../../include/pccl_local.h"
 #include "address_check.h"
 #include "kernels.h"
+#include "knobs.h"
 
 namespace {
 
@@ -83,16 +83,6 @@ ReduceProblem blank_problem() {
   return p;
 }
 
-// PCCL_FORCE_TWO_LEVEL_KERNEL=stream|lds pins the kernel behind
-// pccl_local_reduce_ptrs_two_level (for A/B runs under the profiler).
-int forced_two_level_kernel() {
-  const char* v = std::getenv("PCCL_FORCE_TWO_LEVEL_KERNEL");
-  if (v == nullptr) return 0;
-  if (v[0] == 's') return 1;
-  if (v[0] == 'l') return 2;
-  return 0;
-}
-
 // dtype pairs: a type with itself, or fp32 on one side (never bf16 mixed with fp16)
 pccl_status_t check_common(pccl_dtype_t in_dt, pccl_dtype_t out_dt, pccl_op_t op) {
   if (!dtype_ok(in_dt) || !dtype_ok(out_dt)) return PCCL_ERR_UNSUPPORTED;
@@ -146,8 +136,7 @@ hipError_t launch_flat(const ReduceProblem& p, int in_dt, int out_dt, hipStream_
   q.stride_n = p.stride_g;
   q.stride_g = 0;
   if (p.rows == 1 && p.partial == nullptr) {
-    int forced = 0;  // PCCL_FORCE_FLAT_KERNEL=stream|two-level|flat (A/B runs under the profiler)
-    if (const char* v = std::getenv("PCCL_FORCE_FLAT_KERNEL")) forced = v[0] == 's' ? 1 : v[0] == 't' ? 2 : v[0] == 'f' ? 3 : 0;
+    const int forced = pccl::knobs().flat_kernel;  // 1 streaming, 2 two-level LDS, 3 flat LDS: pinned for tests
     if (forced == 3 || (forced == 0 && pccl::prefer_flat_lds(q, in_dt)))
       return pccl::launch_reduce_flat_lds(q, in_dt, out_dt, st);
     if (forced == 2) return pccl::launch_reduce_two_level_lds(q, in_dt, out_dt, st);
@@ -207,6 +196,52 @@ pccl_status_t permute_batched_common(const pccl_permute_bucket_t* d_buckets,
   const hipError_t e = pccl::launch_permute_batched(d_buckets, h_buckets, nbuckets, rows, cols,
                                                     reinterpret_cast<hipStream_t>(stream));
   return e == hipErrorInvalidValue ? PCCL_ERR_INVALID : from_hip(e);
+}
+
+// Sizes of one two-level reduce-scatter share, and the checks that do not involve the partial.
+struct ShareSizes {
+  size_t es, piece_count, piece_bytes, chunk_bytes, span;
+};
+
+pccl_status_t check_share(const void* shard, const void* intra_base, size_t intra_stride_bytes, int nodes,
+                          int gpus_per_node, int my_node, size_t chunk_count, pccl_dtype_t io_dt, pccl_op_t op,
+                          ShareSizes* z) {
+  if (shard == nullptr || intra_base == nullptr) return PCCL_ERR_NULL;
+  if (pccl_status_t s = check_common(io_dt, io_dt, op)) return s;
+  if (nodes < 1 || gpus_per_node < 1 || my_node < 0 || my_node >= nodes) return PCCL_ERR_INVALID;
+  if (!divisor_ok(op, (size_t)nodes * (size_t)gpus_per_node)) return PCCL_ERR_INVALID;
+  z->es = esize(io_dt);
+  if (!mul_ok((size_t)nodes, chunk_count, &z->piece_count) || !mul_ok(z->piece_count, z->es, &z->piece_bytes))
+    return PCCL_ERR_INVALID;
+  z->chunk_bytes = chunk_count * z->es;
+  if (!elem_aligned(shard, z->es) || !elem_aligned(intra_base, z->es)) return PCCL_ERR_INVALID;
+  if (gpus_per_node > 1 && (intra_stride_bytes < z->piece_bytes || intra_stride_bytes % z->es != 0))
+    return PCCL_ERR_INVALID;
+  if (!mul_ok((size_t)(gpus_per_node - 1), gpus_per_node > 1 ? intra_stride_bytes : 0, &z->span) ||
+      !add_ok(z->span, z->piece_bytes, &z->span))
+    return PCCL_ERR_INVALID;
+  if (overlaps(shard, z->chunk_bytes, intra_base, z->span)) return PCCL_ERR_OVERLAP;
+  return PCCL_OK;
+}
+
+// Both phases of a checked share, the phase-1 result going through `partial`.
+pccl_status_t launch_share(void* shard, void* partial, const void* intra_base, size_t intra_stride_bytes,
+                           const void* const* d_inter, int nodes, int gpus_per_node, int my_node,
+                           size_t chunk_count, pccl_dtype_t io_dt, pccl_op_t op, const ShareSizes& z,
+                           hipStream_t st) {
+  const int dt = io_dt;
+  const float divisor = divisor_for(op, (size_t)nodes * (size_t)gpus_per_node);
+  // phase 1 (intra-node): partial[n][e] = sum over g' of piece_g'[n][e], an M-source flat
+  // sum over the nodes*chunk_count elements of a piece
+  ReduceProblem p1 = blank_problem();
+  p1.dst = partial;
+  p1.base = reinterpret_cast<const char*>(intra_base);
+  p1.stride_g = gpus_per_node > 1 ? intra_stride_bytes : 0;
+  p1.count = z.piece_count;
+  p1.gpus = gpus_per_node;
+  const hipError_t e = launch_flat(p1, dt, dt, st);
+  if (e != hipSuccess) return e == hipErrorInvalidValue ? PCCL_ERR_INVALID : PCCL_ERR_HIP;
+  return phase2(shard, partial, d_inter, nodes, my_node, chunk_count, z.chunk_bytes, dt, divisor, st);
 }
 
 }  // namespace
@@ -307,7 +342,7 @@ pccl_status_t pccl_local_reduce_ptrs_two_level(void* dst, const void* const* d_s
   p.divisor = divisor_for(op, ranks);
   const int ib = in_dt, ob = out_dt;
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-  const int forced = forced_two_level_kernel();
+  const int forced = pccl::knobs().two_level_kernel;  // 1 streaming, 2 LDS-staged: pinned for tests
   const bool lds = forced == 2 || (forced == 0 && pccl::prefer_lds_two_level(p, ib));
   const hipError_t e = lds ? pccl::launch_reduce_two_level_lds(p, ib, ob, st)
                            : pccl::launch_reduce(p, ib, ob, st);
@@ -355,51 +390,25 @@ pccl_status_t pccl_reduce_scatter_local(void* shard, void* partial, const void* 
                                         int nodes, int gpus_per_node, int my_node,
                                         size_t chunk_count, pccl_dtype_t io_dt, pccl_op_t op,
                                         pccl_stream_t stream) {
-  if (shard == nullptr || partial == nullptr || intra_base == nullptr) return PCCL_ERR_NULL;
-  if (pccl_status_t s = check_common(io_dt, io_dt, op)) return s;
-  if (nodes < 1 || gpus_per_node < 1 || my_node < 0 || my_node >= nodes) return PCCL_ERR_INVALID;
-  if (!divisor_ok(op, (size_t)nodes * (size_t)gpus_per_node)) return PCCL_ERR_INVALID;
-  const size_t es = esize(io_dt);
-  size_t piece_count, piece_bytes, chunk_bytes, span;
-  if (!mul_ok((size_t)nodes, chunk_count, &piece_count) || !mul_ok(piece_count, es, &piece_bytes))
-    return PCCL_ERR_INVALID;
-  chunk_bytes = chunk_count * es;
-  if (!elem_aligned(shard, es) || !elem_aligned(partial, es) || !elem_aligned(intra_base, es))
-    return PCCL_ERR_INVALID;
-  if (gpus_per_node > 1 && (intra_stride_bytes < piece_bytes || intra_stride_bytes % es != 0))
-    return PCCL_ERR_INVALID;
-  if (!mul_ok((size_t)(gpus_per_node - 1), gpus_per_node > 1 ? intra_stride_bytes : 0, &span) ||
-      !add_ok(span, piece_bytes, &span))
-    return PCCL_ERR_INVALID;
-  if (overlaps(partial, piece_bytes, intra_base, span) ||
-      overlaps(shard, chunk_bytes, intra_base, span) ||
-      overlaps(shard, chunk_bytes, partial, piece_bytes))
+  if (partial == nullptr) return PCCL_ERR_NULL;
+  ShareSizes z;
+  if (pccl_status_t s = check_share(shard, intra_base, intra_stride_bytes, nodes, gpus_per_node, my_node,
+                                    chunk_count, io_dt, op, &z))
+    return s;
+  if (!elem_aligned(partial, z.es)) return PCCL_ERR_INVALID;
+  if (overlaps(partial, z.piece_bytes, intra_base, z.span) || overlaps(shard, z.chunk_bytes, partial, z.piece_bytes))
     return PCCL_ERR_OVERLAP;
   if (chunk_count == 0) return PCCL_OK;
   AddressChecks ck(stream);
   if (ck.on()) {
-    ck.range(shard, chunk_bytes);
-    ck.range(partial, piece_bytes);
-    ck.range(intra_base, span);
-    if (d_inter != nullptr) ck.pointers(d_inter, (size_t)nodes, 0, chunk_bytes, my_node);
+    ck.range(shard, z.chunk_bytes);
+    ck.range(partial, z.piece_bytes);
+    ck.range(intra_base, z.span);
+    if (d_inter != nullptr) ck.pointers(d_inter, (size_t)nodes, 0, z.chunk_bytes, my_node);
     if (ck.status != PCCL_OK) return ck.status;
   }
-  const int dt = io_dt;
-  const float divisor = divisor_for(op, (size_t)nodes * (size_t)gpus_per_node);
-  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-
-  // phase 1 (intra-node): partial[n][e] = sum over g' of piece_g'[n][e], an M-source flat
-  // sum over the nodes*chunk_count elements of a piece
-  ReduceProblem p1 = blank_problem();
-  p1.dst = partial;
-  p1.base = reinterpret_cast<const char*>(intra_base);
-  p1.stride_g = gpus_per_node > 1 ? intra_stride_bytes : 0;
-  p1.count = piece_count;
-  p1.gpus = gpus_per_node;
-  hipError_t e = launch_flat(p1, dt, dt, st);
-  if (e != hipSuccess) return e == hipErrorInvalidValue ? PCCL_ERR_INVALID : PCCL_ERR_HIP;
-
-  return phase2(shard, partial, d_inter, nodes, my_node, chunk_count, chunk_bytes, dt, divisor, st);
+  return launch_share(shard, partial, intra_base, intra_stride_bytes, d_inter, nodes, gpus_per_node, my_node,
+                      chunk_count, io_dt, op, z, reinterpret_cast<hipStream_t>(stream));
 }
 
 pccl_status_t pccl_reduce_scatter_local_unpacked(void* shard, void* partial, const void* msgs_base,

@@ -8,10 +8,9 @@
 // (tile, source row, source column) so that no index division is needed: measured on MI355X
 // this moves 6.7 TB/s, against 6.3 TB/s with 256-thread blocks and 5.2 TB/s with four
 // vectors in flight per lane.  HBM-bound: 2 bytes moved per byte of message.
-#include <cstdlib>
-
 #include "device_utils.h"
 #include "kernels.h"
+#include "knobs.h"
 
 namespace pccl {
 
@@ -179,10 +178,8 @@ __global__ __launch_bounds__(kPermBlock) void k_permute_batched(
 
 bool split_grid_xz(size_t blocks, unsigned threads, unsigned* gx, unsigned* gz) {
   size_t limit = (size_t)1 << 31;  // work-items in x; the hardware packet holds 32 bits
-  if (const char* v = std::getenv("PCCL_GRID_X_LIMIT")) {
-    const long long t = std::atoll(v);
-    if (t >= (long long)threads && (size_t)t < limit) limit = (size_t)t;
-  }
+  const size_t t = knobs().grid_x_limit;  // tests lower it so that small problems take the split
+  if (t >= threads && t < limit) limit = t;
   const size_t max_x = limit / threads;
   if (blocks <= max_x) {
     *gx = (unsigned)(blocks == 0 ? 1 : blocks);
@@ -208,13 +205,13 @@ hipError_t launch_permute(const PermuteProblem& p, hipStream_t st) {
   if (tiles_per_chunk > kPermMaxTilesX || chunks > 0x7FFFFFFFull) return hipErrorInvalidValue;
   if (p.rows <= 65535 && p.cols <= 65535) {
     bool cfast = column_fast_order(p.chunk_bytes, p.rows, p.cols);
-    if (const char* v = std::getenv("PCCL_PERMUTE_ORDER")) cfast = v[0] == 's';  // "src" / "dst"
+    if (knobs().permute_order != 0) cfast = knobs().permute_order == 2;  // forced, for A/B runs
     // Chunk (r, c) starts (r + c) * skew tiles into itself, modulo its tile count: the resident
     // blocks otherwise sit at the same offset of several chunks a power of two apart.  Measured
     // with 131 tiles: 1-7 % faster for chunks of 512 KB-1 MB (256 MB as 64x8: 85.8 -> 79.5 us,
     // 128 MB as 32x8: 43.7 -> 40.9 us), no change from 2 MB up; see skew_pays() for the rest.
     uint32_t skew = skew_pays(p.chunk_bytes) ? kSkewTiles : 0u;
-    if (const char* v = std::getenv("PCCL_PERMUTE_SKEW")) skew = (uint32_t)std::atoi(v);
+    if (knobs().permute_skew >= 0) skew = (uint32_t)knobs().permute_skew;
     if (cfast)
       hipLaunchKernelGGL((k_permute<true, true>), dim3((unsigned)tiles_per_chunk, (unsigned)p.cols, (unsigned)p.rows),
                          dim3(kPermBlock), 0, st, p, (uint32_t)tiles_per_chunk, skew);

@@ -14,10 +14,9 @@
 //                       counts): raw words staged in LDS, ordered pass one tile behind.
 //   k_rs_batched[_rows] the streaming tile body over a flat tile space of many buckets.
 // All are HBM-bound: (sources - 1) adds per element against >= 2 bytes per operand.
-#include <cstdlib>
-
 #include "device_utils.h"
 #include "kernels.h"
+#include "knobs.h"
 
 namespace pccl {
 
@@ -746,12 +745,8 @@ hipError_t launch_flat_lds_io(const ReduceProblem& p, hipStream_t st) {
   // sources are many and short, where sixteen put a whole slice's loads in flight at once.
   const size_t src_bytes = p.count * (narrow(IN) ? 2 : 4);
   int waves = (p.nodes <= 32 || src_bytes >= ((size_t)256 << 10)) ? 4 : (p.nodes <= 64 ? 8 : 16);
-  if (const char* v = std::getenv("PCCL_FLAT_WAVES")) {
-    const int w = std::atoi(v);
-    if (w == 4 || w == 8 || w == 16) waves = w;
-  }
-  bool local = true;
-  if (const char* v = std::getenv("PCCL_FLAT_LOCAL")) local = v[0] != '0';  // for A/B runs
+  if (knobs().flat_waves != 0) waves = knobs().flat_waves;
+  const bool local = knobs().flat_local != 0;  // off for A/B runs only
   const size_t launch_blocks = local ? (blocks + 7) / 8 * 8 : blocks;
   if (!split_grid_xz(launch_blocks, (unsigned)waves * 64, &gx, &gz)) return hipErrorInvalidValue;
   const dim3 grid(gx, 1, gz), block((unsigned)waves * 64);

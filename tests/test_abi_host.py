@@ -38,6 +38,18 @@ def test_library_exports_every_declared_symbol():
     assert set(names) == set(binding.EXPORTS)
 
 
+def test_loaded_library_was_built_from_the_sources_on_disk(tmp_path):
+    from paper_2504_18658_amd import build
+    assert build.source_id() == build.built_id() == pccl.lib().pccl_build_id().decode()
+    assert not build.is_stale()
+    # a file that is not a build of these sources is recognised as such
+    other = tmp_path / "lib.so"
+    other.write_bytes(b"\x7fELF" + b"pccl-build-id:0123456789abcdef" + b"\0" * 8)
+    assert build.built_id(str(other)) == "0123456789abcdef" != build.source_id()
+    other.write_bytes(b"\x7fELF no marker")
+    assert build.built_id(str(other)) is None and build.built_id(str(tmp_path / "absent.so")) is None
+
+
 def test_header_and_binding_constants_agree():
     text = open(os.path.join(ROOT, "include", "pccl_local.h")).read()
     assert int(re.search(r"#define PCCL_MAX_BUCKETS (\d+)", text).group(1)) == pccl.PCCL_MAX_BUCKETS
@@ -50,7 +62,7 @@ def test_header_and_binding_constants_agree():
 
 
 def test_status_strings():
-    for s in range(6):
+    for s in range(7):
         assert pccl.status_string(s).startswith("PCCL_")
     assert "unknown" in pccl.status_string(99)
 
@@ -309,6 +321,7 @@ def test_checked_mode_refuses_addresses_no_kernel_can_reach(monkeypatch):
     assert L.pccl_check_device_range(None, 16) == pccl.PCCL_ERR_NULL
     assert L.pccl_check_device_range(0x10000, 16) == pccl.PCCL_ERR_ADDRESS
     monkeypatch.setenv("PCCL_CHECK_POINTERS", "1")
+    pccl.diag_reload_env()
     a, b = 0x10000000, 0x20000000
     assert L.pccl_local_reduce(a, b, 4096, 2, 1024, pccl.PCCL_F32, pccl.PCCL_F32, pccl.PCCL_SUM, None) == pccl.PCCL_ERR_ADDRESS
     assert L.pccl_accumulate(a, b, 1024, pccl.PCCL_BF16, pccl.PCCL_SUM, None) == pccl.PCCL_ERR_ADDRESS

@@ -56,6 +56,7 @@ def test_pinned_host_memory_is_reachable():
 @pytest.mark.parametrize("level", ["1", "2"])
 def test_valid_calls_are_unchanged_in_checked_mode(monkeypatch, level):
     monkeypatch.setenv("PCCL_CHECK_POINTERS", level)
+    pccl.diag_reload_env()
     n, g, c = 5, 4, 3000 + 5
     P = n * g
     x_h = W.normal(g * n * c, 5, 1.0, "cpu", BF16).view(g, n, c)
@@ -134,6 +135,7 @@ def test_valid_calls_are_unchanged_in_checked_mode(monkeypatch, level):
 
 def test_a_call_with_an_unreachable_range_is_refused_not_launched(monkeypatch):
     monkeypatch.setenv("PCCL_CHECK_POINTERS", "1")
+    pccl.diag_reload_env()
     L = pccl.lib()
     n = 4096
     host = np.ones(2 * n, dtype=np.float32)                      # pageable host memory as the source
@@ -173,6 +175,7 @@ def test_level_two_looks_inside_device_tables(monkeypatch):
     bad = torch.tensor(good[:3] + [host.ctypes.data], dtype=torch.int64, device=DEV)
     dst = torch.full((n,), 7.0, dtype=F32, device=DEV)
     monkeypatch.setenv("PCCL_CHECK_POINTERS", "2")
+    pccl.diag_reload_env()
     rc = L.pccl_local_reduce_ptrs(dst.data_ptr(), bad.data_ptr(), 4, n, pccl.PCCL_F32, pccl.PCCL_F32, pccl.PCCL_SUM, None)
     assert rc == ERR_ADDRESS
     # the slot of the caller's own node is never dereferenced, so it may hold anything

@@ -112,11 +112,13 @@ def test_f16_two_level_ptrs_matches_oracle(force, out_dt, nodes, gpus, count):
     ptrs = pccl.device_pointer_array([dev[s] for s in range(nsrc)])
     dst = _guarded_out(count, out_dt)
     os.environ["PCCL_FORCE_TWO_LEVEL_KERNEL"] = force
+    pccl.diag_reload_env()
     try:
         pccl.pccl_local_reduce_ptrs_two_level(_view(dst, out_dt), ptrs, nodes, gpus, count, F16)
         _sync()
     finally:
         os.environ.pop("PCCL_FORCE_TWO_LEVEL_KERNEL", None)
+        pccl.diag_reload_env()
     want = oracle.two_level_reduce([to_np(host[s]) for s in range(nsrc)], nodes, gpus, ODT[out_dt])
     got = to_np(_view(dst, out_dt))
     assert same_bits(got, want), first_diff(got, want)
@@ -170,11 +172,13 @@ def test_average_hand_cases_on_gpu(golden_dir):
         for force in ("stream", "lds"):
             dst = torch.empty(1, dtype=F32, device=DEV)
             os.environ["PCCL_FORCE_TWO_LEVEL_KERNEL"] = force
+            pccl.diag_reload_env()
             try:
                 pccl.pccl_local_reduce_ptrs_two_level(dst, ptrs, nodes, gpus, 1, F32, average=True)
                 _sync()
             finally:
                 os.environ.pop("PCCL_FORCE_TWO_LEVEL_KERNEL", None)
+                pccl.diag_reload_env()
             assert same_bits(to_np(dst), want), (line, force, to_np(dst))
         if nodes == 1:
             dst = torch.empty(1, dtype=F32, device=DEV)
@@ -261,11 +265,13 @@ def test_average_two_level_ptrs_matches_oracle(force, in_dt, out_dt):
     ptrs = pccl.device_pointer_array([dev[s] for s in range(nsrc)])
     dst = _guarded_out(count, out_dt)
     os.environ["PCCL_FORCE_TWO_LEVEL_KERNEL"] = force
+    pccl.diag_reload_env()
     try:
         pccl.pccl_local_reduce_ptrs_two_level(_view(dst, out_dt), ptrs, nodes, gpus, count, in_dt, average=True)
         _sync()
     finally:
         os.environ.pop("PCCL_FORCE_TWO_LEVEL_KERNEL", None)
+        pccl.diag_reload_env()
     want = oracle.two_level_reduce([to_np(host[s]) for s in range(nsrc)], nodes, gpus, ODT[out_dt], average=True)
     got = to_np(_view(dst, out_dt))
     assert same_bits(got, want), first_diff(got, want)

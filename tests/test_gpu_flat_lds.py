@@ -30,6 +30,7 @@ def _out(n, dtype, offset=0):
 @pytest.fixture(autouse=True)
 def _force_flat(monkeypatch):
     monkeypatch.setenv("PCCL_FORCE_FLAT_KERNEL", "flat")
+    pccl.diag_reload_env()
 
 
 @pytest.mark.parametrize("dtype", [F32, BF16, F16])
@@ -99,6 +100,7 @@ def test_launch_split_over_x_and_z(monkeypatch, nsrc):
     """A tiny x extent makes a small problem take the x/z-split launch that only buffers of tens of
     GiB would otherwise take: blocks past the last slice must leave, every slice must be summed once."""
     monkeypatch.setenv("PCCL_GRID_X_LIMIT", "4096")
+    pccl.diag_reload_env()
     count = 100003
     host = W.normal(nsrc * count, 31, 1.0, "cpu", BF16).view(nsrc, count)
     dst, view = _out(count, BF16)
@@ -139,8 +141,10 @@ def test_slice_order_and_load_kind(monkeypatch, mode, tiny_grid):
     """Slices dealt XCD-major with cached loads (1, the default) or linearly with streaming loads
     (0): the same sums; with a tiny x extent the XCD-major launch is also rounded up over x and z."""
     monkeypatch.setenv("PCCL_FLAT_LOCAL", mode)
+    pccl.diag_reload_env()
     if tiny_grid:
         monkeypatch.setenv("PCCL_GRID_X_LIMIT", "4096")
+        pccl.diag_reload_env()
     for nsrc, count, dtype in ((40, 100003, BF16), (130, 1000, F32), (17, 64 * 9 + 1, BF16), (300, 127, F16)):
         host = W.normal(nsrc * (count + 1), 41, 1.0, "cpu", dtype)[: nsrc * count].view(nsrc, count)
         dst, view = _out(count, dtype)

@@ -78,11 +78,13 @@ def test_two_level_lds_kernel_beyond_4gib():
     ptrs = pccl.device_pointer_array([src[k] for k in range(nodes * gpus)])
     dst = torch.empty(n, dtype=F32, device=DEV)
     os.environ["PCCL_FORCE_TWO_LEVEL_KERNEL"] = "lds"
+    pccl.diag_reload_env()
     try:
         pccl.pccl_local_reduce_ptrs_two_level(dst, ptrs, nodes, gpus, n, F32)
         _sync()
     finally:
         os.environ.pop("PCCL_FORCE_TWO_LEVEL_KERNEL", None)
+        pccl.diag_reload_env()
     assert torch.equal(dst.view(torch.int32), ((src[0] + src[1]) + (src[2] + src[3])).view(torch.int32))
     for lo in _windows(n) + [(1 << 30) - 2048]:
         sl = slice(lo, lo + 4096)
@@ -136,6 +138,7 @@ def tiny_grid_x(monkeypatch):
     """Lower the x extent of a launch to 4096 work-items so that small problems take the
     x/z-split path that buffers of tens of GiB take."""
     monkeypatch.setenv("PCCL_GRID_X_LIMIT", "4096")
+    pccl.diag_reload_env()
 
 
 @pytest.mark.parametrize("dtype", [F32, BF16])
@@ -158,12 +161,14 @@ def test_split_grids_on_small_problems(tiny_grid_x, dtype):
     d2 = h2.to(DEV)
     out = Guarded(cnt, dtype)
     os.environ["PCCL_FORCE_TWO_LEVEL_KERNEL"] = "lds"
+    pccl.diag_reload_env()
     try:
         pccl.pccl_local_reduce_ptrs_two_level(out.view, pccl.device_pointer_array([d2[k] for k in range(nodes * gpus)]),
                                               nodes, gpus, cnt, dtype)
         _sync()
     finally:
         os.environ.pop("PCCL_FORCE_TWO_LEVEL_KERNEL", None)
+        pccl.diag_reload_env()
     assert same_bits(to_np(out.view), O.two_level_reduce([to_np(h2[k]) for k in range(nodes * gpus)], nodes, gpus, odt))
     out.check()
     # accumulate

@@ -109,12 +109,14 @@ def test_hand_worked_order_cases_on_gpu():
         ptrs = pccl.device_pointer_array([src[k] for k in range(nodes * gpus)])
         for force in ("stream", "lds"):
             os.environ["PCCL_FORCE_TWO_LEVEL_KERNEL"] = force
+            pccl.diag_reload_env()
             try:
                 dst = torch.empty(9, dtype=F32, device=DEV)
                 pccl.pccl_local_reduce_ptrs_two_level(dst, ptrs, nodes, gpus, 9, F32)
                 _sync()
             finally:
                 del os.environ["PCCL_FORCE_TWO_LEVEL_KERNEL"]
+                pccl.diag_reload_env()
             assert same_bits(to_np(dst), np.repeat(want, 9)), (line, force, to_np(dst))
 
 
@@ -127,12 +129,14 @@ def test_bf16_partial_rounding_cases_on_gpu():
         ptrs = pccl.device_pointer_array([src[k] for k in range(nodes * gpus)])
         for force in ("stream", "lds"):
             os.environ["PCCL_FORCE_TWO_LEVEL_KERNEL"] = force
+            pccl.diag_reload_env()
             try:
                 dst = torch.empty(19, dtype=BF16, device=DEV)
                 pccl.pccl_local_reduce_ptrs_two_level(dst, ptrs, nodes, gpus, 19, BF16)
                 _sync()
             finally:
                 del os.environ["PCCL_FORCE_TWO_LEVEL_KERNEL"]
+                pccl.diag_reload_env()
             assert bool((dst.float().cpu() == _pf(expected)).all()), (line, force)
 
 
@@ -214,11 +218,13 @@ def test_two_level_ptrs_matches_oracle(force, in_dt, out_dt, nodes, gpus, count,
     dst = Guarded(count, out_dt, offset_elems=shift)
     if force:
         os.environ["PCCL_FORCE_TWO_LEVEL_KERNEL"] = force
+        pccl.diag_reload_env()
     try:
         pccl.pccl_local_reduce_ptrs_two_level(dst.view, ptrs, nodes, gpus, count, in_dt)
         _sync()
     finally:
         os.environ.pop("PCCL_FORCE_TWO_LEVEL_KERNEL", None)
+        pccl.diag_reload_env()
     want = oracle.two_level_reduce(cpu, nodes, gpus, ODT[out_dt])
     assert same_bits(to_np(dst.view), want), first_diff(to_np(dst.view), want)
     dst.check()
@@ -558,7 +564,8 @@ def test_batched_ragged_chunks_and_other_shapes():
 
 def test_cfg5_zero3_buckets_full_size():
     """40 buckets of 16 - 512 MB in one batched call; three whole buckets (smallest, median,
-    largest) and the head of every shard are checked against the oracle."""
+    largest) and the head and tail of every shard are checked against the oracle, and every
+    element of every partial and shard against the same sums written with torch on the GPU."""
     w = W.cfg5()
     sizes = w.extra["bucket_bytes"]
     buckets = _make_buckets(w, sizes, DEV)
@@ -577,6 +584,20 @@ def test_cfg5_zero3_buckets_full_size():
         for sl in (slice(0, head), slice(tail, tail + head)):
             want_shard, _ = oracle.reduce_scatter_local(to_np(x[:, :, sl]))
             assert same_bits(to_np(shard[sl]), want_shard), k
+    # EVERY element of every bucket's partial and shard, on the GPU, against the same order written with
+    # torch: binary32 adds one source after the other, torch's bf16 cast (round to nearest even; the
+    # oracle's rounding is pinned against that cast over all 2^32 patterns) between and after the phases
+    for k, (shard, partial, x) in enumerate(buckets):
+        t = x[0].float()
+        for g in range(1, x.shape[0]):
+            t = t + x[g].float()
+        ref_partial = t.to(BF16)                                   # [nodes][chunk]
+        assert torch.equal(partial.view(torch.int16), ref_partial.view(torch.int16).reshape(-1)), ("partial", k)
+        a = ref_partial[0].float()
+        for n in range(1, x.shape[1]):
+            a = a + ref_partial[n].float()
+        assert torch.equal(shard.view(torch.int16), a.to(BF16).view(torch.int16)), ("shard", k)
+        del t, a, ref_partial
 
 
 # ------------------------------------------------------------------------------- empty inputs

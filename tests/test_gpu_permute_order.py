@@ -27,12 +27,16 @@ def test_pack_unpack_reassemble_in_either_block_order(monkeypatch, order, skew, 
     choice (on from 512 KB chunks), a number forces it for every chunk size below."""
     if order is None:
         monkeypatch.delenv("PCCL_PERMUTE_ORDER", raising=False)
+        pccl.diag_reload_env()
     else:
         monkeypatch.setenv("PCCL_PERMUTE_ORDER", order)
+        pccl.diag_reload_env()
     if skew is None:
         monkeypatch.delenv("PCCL_PERMUTE_SKEW", raising=False)
+        pccl.diag_reload_env()
     else:
         monkeypatch.setenv("PCCL_PERMUTE_SKEW", skew)
+        pccl.diag_reload_env()
     gen = torch.Generator()
     gen.manual_seed(nodes * 100 + gpus)
     P = nodes * gpus
