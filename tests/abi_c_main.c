@@ -1,6 +1,6 @@
 /* A plain C99 caller of the library's header: compiled with -pedantic-errors by
  * tests/test_header_c.py, linked against the built library, and run WITHOUT a GPU.  It only
- * reaches host code: status strings, the cost model (Section III-A, Eq. 1 and Eq. 2) and
+ * reaches host code: status strings, the cost model (Section II-B, Eq. 1 and Eq. 2) and
  * argument checks that reject a call before any HIP call is made. */
 #include <math.h>
 #include <stdio.h>

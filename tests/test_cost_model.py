@@ -50,6 +50,21 @@ def test_oracle_closed_forms_and_limits():
     assert cm.choose(6, 1e3, a, b, a, b)[0] == cm.RING                 # not a power of two
 
 
+def test_oracle_two_level_hand_values(golden_dir):
+    import os
+    n = 0
+    for line in open(os.path.join(golden_dir, "two_level_cost_cases.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        args, want = line.split("|")
+        nodes, gpus, m, algo, ai, bi, aa, ba, local, rate = args.split()
+        got = cm.t_two_level(int(nodes), int(gpus), float(m), cm.RING if algo == "ring" else cm.REC, float(ai),
+                             float(bi), float(aa), float(ba), float(local), float(rate))
+        assert got == pytest.approx(float(want), rel=1e-12), line
+        n += 1
+    assert n == 4
+
+
 def test_oracle_two_level_is_the_sum_of_its_parts():
     n, g, m = 16, 8, 256 * 2 ** 20
     t = cm.t_two_level(n, g, m, cm.REC, 1e-5, 4e-11, 2e-6, 1e-11, 1.4e9, 6.4e12)
