@@ -22,7 +22,9 @@
  *              (d_srcs, d_inter, d_slots) and descriptor tables (d_buckets) are themselves
  *              device-resident.
  *   Ownership  The caller owns every buffer, scratch included.  The library allocates
- *              nothing, frees nothing and keeps no pointer after the call returns.
+ *              nothing, frees nothing and keeps no pointer after the call returns.  (One
+ *              entry point, pccl_reduce_scatter_local_static, keeps its scratch in a static
+ *              device array of the library instead of taking it from the caller.)
  *   Stream     Work is only enqueued on `stream` (a hipStream_t; NULL = the default
  *              stream).  No call synchronises the device; results are valid once the
  *              caller has synchronised the stream.
@@ -85,7 +87,8 @@ typedef enum {
   PCCL_ERR_UNSUPPORTED = 3, /* unknown dtype, dtype pair or op */
   PCCL_ERR_OVERLAP = 4,     /* an output range overlaps an input range */
   PCCL_ERR_HIP = 5,         /* the HIP runtime refused a launch */
-  PCCL_ERR_ADDRESS = 6      /* checked mode: a range is not inside one reachable allocation */
+  PCCL_ERR_ADDRESS = 6,     /* checked mode: a range is not inside one reachable allocation */
+  PCCL_ERR_SCRATCH = 7      /* the call needs more than the library's static workspace holds */
 } pccl_status_t;
 
 /* fp32, bf16 and fp16 (IEEE binary16) elements.  Where an entry point takes an input and an
@@ -174,6 +177,28 @@ pccl_status_t pccl_reduce_scatter_local(void* shard, void* partial, const void* 
                                         int nodes, int gpus_per_node, int my_node,
                                         size_t chunk_count, pccl_dtype_t io_dt, pccl_op_t op,
                                         pccl_stream_t stream);
+
+/* pccl_reduce_scatter_local for callers that cannot allocate device memory -- code running
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc -- and so have
+ * no `partial` buffer to hand over: the phase-1 result is kept in a workspace inside the
+ * library, a static device array of PCCL_STATIC_SCRATCH_BYTES bytes (one copy on every GPU the
+ * library runs on, held until the process ends).  Everything else -- arguments, the two
+ * kernels, the order of the sums, the bits of `shard` -- is as in pccl_reduce_scatter_local.
+ * The call allocates and frees nothing and runs no checked-mode queries, whatever
+ * PCCL_CHECK_POINTERS says; its first use on a device asks the runtime for the workspace's
+ * address there (no stream work) and keeps it.
+ * Limit: nodes*chunk_count*sizeof(io_dt) <= PCCL_STATIC_SCRATCH_BYTES, else PCCL_ERR_SCRATCH
+ * (checked on the host before any HIP call, like every other argument error).
+ * Every call on a GPU uses that GPU's one workspace and overwrites what the last call left
+ * (nothing in it needs clearing: phase 1 writes every element phase 2 reads): two calls whose
+ * kernels may run at the same time on one GPU -- different streams, or graph branches -- RACE;
+ * keep them in stream order.  The partial cannot be read back by the caller. */
+#define PCCL_STATIC_SCRATCH_BYTES ((size_t)32 << 20)
+pccl_status_t pccl_reduce_scatter_local_static(void* shard, const void* intra_base,
+                                               size_t intra_stride_bytes, const void* const* d_inter,
+                                               int nodes, int gpus_per_node, int my_node,
+                                               size_t chunk_count, pccl_dtype_t io_dt, pccl_op_t op,
+                                               pccl_stream_t stream);
 
 /* The same share without the pre-shuffle: phase 1 reads the node-mates' messages in RANK
  * order, so no pccl_hier_pack pass (one read and one write of the whole message on every

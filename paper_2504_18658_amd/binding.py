@@ -10,10 +10,12 @@ import torch
 
 from . import build as _build
 
-PCCL_OK, PCCL_ERR_NULL, PCCL_ERR_INVALID, PCCL_ERR_UNSUPPORTED, PCCL_ERR_OVERLAP, PCCL_ERR_HIP, PCCL_ERR_ADDRESS = range(7)
+PCCL_OK, PCCL_ERR_NULL, PCCL_ERR_INVALID, PCCL_ERR_UNSUPPORTED, PCCL_ERR_OVERLAP, PCCL_ERR_HIP, PCCL_ERR_ADDRESS, \
+    PCCL_ERR_SCRATCH = range(8)
 PCCL_F32, PCCL_BF16, PCCL_F16 = 0, 1, 2
 PCCL_SUM, PCCL_AVG = 0, 1
 PCCL_MAX_BUCKETS = 512
+PCCL_STATIC_SCRATCH_BYTES = 32 << 20
 
 EXPORTS = (
     "pccl_local_reduce", "pccl_local_reduce_ptrs", "pccl_local_reduce_ptrs_two_level",
@@ -22,7 +24,7 @@ EXPORTS = (
     "pccl_reduce_scatter_local_unpacked", "pccl_ring_reduce_scatter_local",
     "pccl_allgather_reassemble_batched", "pccl_hier_pack_batched", "pccl_halving_reduce_scatter_local", "pccl_model_ring", "pccl_model_rec",
     "pccl_choose_algorithm", "pccl_model_two_level", "pccl_status_string", "pccl_check_device_range",
-    "pccl_reduce_scatter_local_unpacked_batched", "pccl_diag_reload_env", "pccl_build_id",
+    "pccl_reduce_scatter_local_unpacked_batched", "pccl_reduce_scatter_local_static", "pccl_diag_reload_env", "pccl_build_id",
 )
 PCCL_ALGO_RING, PCCL_ALGO_REC = 0, 1
 _NO_STATUS = ("pccl_status_string", "pccl_model_ring", "pccl_model_rec", "pccl_model_two_level",
@@ -69,6 +71,7 @@ def lib():
         L.pccl_hier_pack.argtypes = [vp, vp, i, i, sz, vp]
         L.pccl_hier_unpack.argtypes = [vp, vp, i, i, sz, vp]
         L.pccl_reduce_scatter_local.argtypes = [vp, vp, vp, sz, vp, i, i, i, sz, i, i, vp]
+        L.pccl_reduce_scatter_local_static.argtypes = [vp, vp, sz, vp, i, i, i, sz, i, i, vp]
         L.pccl_allgather_reassemble.argtypes = [vp, vp, vp, i, i, sz, vp]
         L.pccl_reduce_scatter_local_batched.argtypes = [vp, vp, i, i, i, i, i, vp]
         L.pccl_reduce_scatter_local_unpacked_batched.argtypes = [vp, vp, i, i, i, i, i, i, vp]
@@ -249,6 +252,21 @@ def pccl_reduce_scatter_local(shard, partial, intra, d_inter=None, my_node=0, st
         _dev(shard, "shard"), _dev(partial, "partial"), base, stride,
         None if d_inter is None else _dev(d_inter, "d_inter"), nodes, gpus, my_node, chunk,
         dtype_code(intra.dtype), _op(average), _stream(stream)), "pccl_reduce_scatter_local")
+    return shard
+
+
+def pccl_reduce_scatter_local_static(shard, intra, d_inter=None, my_node=0, stream=None, average=False):
+    """pccl_reduce_scatter_local with the phase-1 result in the library's static workspace (no
+    `partial` argument; nodes*chunk*element size at most PCCL_STATIC_SCRATCH_BYTES)."""
+    if intra.dim() != 3:
+        raise ValueError("pccl_reduce_scatter_local_static: intra must be [gpus][nodes][chunk]")
+    base, stride, gpus, _ = _rows(intra, "intra")
+    nodes, chunk = intra.shape[1], intra.shape[2]
+    if shard.numel() != chunk or shard.dtype != intra.dtype or not shard.is_contiguous():
+        raise ValueError("pccl_reduce_scatter_local_static: shard is [chunk], contiguous, of the message dtype")
+    _check(lib().pccl_reduce_scatter_local_static(
+        _dev(shard, "shard"), base, stride, None if d_inter is None else _dev(d_inter, "d_inter"), nodes, gpus,
+        my_node, chunk, dtype_code(intra.dtype), _op(average), _stream(stream)), "pccl_reduce_scatter_local_static")
     return shard
 
 

@@ -3,11 +3,39 @@
 // side effect and the error paths can be exercised on a machine without a GPU.  With
 // PCCL_CHECK_POINTERS set, a call that passed those checks then asks the runtime whether every
 // range lies inside memory a kernel can reach, and launches only if so.
+#include <atomic>
 
 #include "../../include/pccl_local.h"
 #include "address_check.h"
 #include "kernels.h"
 #include "knobs.h"
+
+// Workspace of pccl_reduce_scatter_local_static: the phase-1 result of a share whose caller
+// cannot provide (allocate) one.  One copy per GPU the library runs on, held until the process
+// ends.  Host code never uses the array's name as an address: the device address is asked for
+// once per device and kept.
+static __device__ __align__(256) unsigned char scratch[PCCL_STATIC_SCRATCH_BYTES];
+
+static constexpr int kMaxDevices = 64;
+static std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+// Device address of `scratch` on the current device (nullptr when the runtime refuses).
+static void* static_scratch() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+    (void)hipGetLastError();
+    return nullptr;
+  }
+  void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (p == nullptr) {
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) {
+      (void)hipGetLastError();
+      return nullptr;
+    }
+    g_scratch_ptr[dev].store(p, std::memory_order_release);  // every thread finds the same address
+  }
+  return p;
+}
 
 namespace {
 
@@ -411,6 +439,23 @@ pccl_status_t pccl_reduce_scatter_local(void* shard, void* partial, const void* 
                       chunk_count, io_dt, op, z, reinterpret_cast<hipStream_t>(stream));
 }
 
+pccl_status_t pccl_reduce_scatter_local_static(void* shard, const void* intra_base,
+                                               size_t intra_stride_bytes, const void* const* d_inter,
+                                               int nodes, int gpus_per_node, int my_node,
+                                               size_t chunk_count, pccl_dtype_t io_dt, pccl_op_t op,
+                                               pccl_stream_t stream) {
+  ShareSizes z;
+  if (pccl_status_t s = check_share(shard, intra_base, intra_stride_bytes, nodes, gpus_per_node, my_node,
+                                    chunk_count, io_dt, op, &z))
+    return s;
+  if (z.piece_bytes > PCCL_STATIC_SCRATCH_BYTES) return PCCL_ERR_SCRATCH;
+  if (chunk_count == 0) return PCCL_OK;
+  void* partial = static_scratch();
+  if (partial == nullptr) return PCCL_ERR_HIP;
+  return launch_share(shard, partial, intra_base, intra_stride_bytes, d_inter, nodes, gpus_per_node, my_node,
+                      chunk_count, io_dt, op, z, reinterpret_cast<hipStream_t>(stream));
+}
+
 pccl_status_t pccl_reduce_scatter_local_unpacked(void* shard, void* partial, const void* msgs_base,
                                                  size_t msg_stride_bytes,
                                                  const void* const* d_msgs,
@@ -674,6 +719,8 @@ const char* pccl_status_string(pccl_status_t status) {
     case PCCL_ERR_HIP: return "PCCL_ERR_HIP: the HIP runtime refused a kernel launch";
     case PCCL_ERR_ADDRESS:
       return "PCCL_ERR_ADDRESS: a range is not inside one allocation kernels can reach (checked mode)";
+    case PCCL_ERR_SCRATCH:
+      return "PCCL_ERR_SCRATCH: the call needs more than the library's static workspace holds";
   }
   return "PCCL: unknown status";
 }

@@ -62,7 +62,7 @@ def test_header_and_binding_constants_agree():
 
 
 def test_status_strings():
-    for s in range(7):
+    for s in range(8):
         assert pccl.status_string(s).startswith("PCCL_")
     assert "unknown" in pccl.status_string(99)
 
@@ -160,6 +160,33 @@ def test_reduce_scatter_local_rejects_bad_arguments():
     assert call(shard=8 * A + (7 << 16)) == pccl.PCCL_ERR_OVERLAP
     assert call(shard=2 * A + 4096) == pccl.PCCL_ERR_OVERLAP   # shard inside partial
     assert call(chunk=0) == pccl.PCCL_OK
+
+
+def test_static_reduce_scatter_local_rejects_bad_arguments():
+    f = pccl.lib().pccl_reduce_scatter_local_static
+    ok = dict(shard=A, intra=8 * A, stride=1 << 16, inter=None, nodes=4, gpus=8, my=0, chunk=1024, dt=1, op=0)
+
+    def call(**kw):
+        a = dict(ok, **kw)
+        return f(a["shard"], a["intra"], a["stride"], a["inter"], a["nodes"], a["gpus"], a["my"], a["chunk"],
+                 a["dt"], a["op"], None)
+
+    assert call(shard=None) == pccl.PCCL_ERR_NULL
+    assert call(intra=None) == pccl.PCCL_ERR_NULL
+    assert call(nodes=0) == pccl.PCCL_ERR_INVALID
+    assert call(my=4) == pccl.PCCL_ERR_INVALID
+    assert call(dt=9) == pccl.PCCL_ERR_UNSUPPORTED
+    assert call(stride=8190) == pccl.PCCL_ERR_INVALID
+    assert call(chunk=1 << 62) == pccl.PCCL_ERR_INVALID
+    assert call(shard=8 * A + (7 << 16)) == pccl.PCCL_ERR_OVERLAP
+    assert call(chunk=0) == pccl.PCCL_OK
+    # the workspace holds 32 MiB of partial: nodes * chunk * element size
+    limit = pccl.PCCL_STATIC_SCRATCH_BYTES
+    text = open(os.path.join(ROOT, "include", "pccl_local.h")).read()
+    assert "#define PCCL_STATIC_SCRATCH_BYTES ((size_t)32 << 20)" in text and limit == 32 << 20
+    assert call(nodes=16, chunk=limit // 32 + 1, stride=1 << 40) == pccl.PCCL_ERR_SCRATCH
+    assert call(nodes=16, chunk=limit // 64 + 1, dt=0, stride=1 << 40) == pccl.PCCL_ERR_SCRATCH
+    assert "SCRATCH" in pccl.status_string(pccl.PCCL_ERR_SCRATCH)
 
 
 def test_batched_rejects_bad_arguments():
