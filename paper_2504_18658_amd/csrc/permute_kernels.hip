@@ -49,7 +49,11 @@ __device__ __forceinline__ void copy_tile(const char* sp, char* dp, uint32_t len
   const uint32_t lane = threadIdx.x;
   if (aligned_to(sp, 16) && aligned_to(dp, 16)) {
     const uint32_t lo = lane * 16;
-    if (lo + 16 <= len) st_stream<u32x4>(dp + lo, ld_stream<u32x4>(sp + lo));
+    if (lo + 16 <= len) {
+      const u32x4 v = ld_stream<u32x4>(sp + lo);
+      const uint32_t w[4] = {v[0], v[1], v[2], v[3]};
+      st_through<4>(wave_uniform(dp), lo, len, w);
+    }
     const uint32_t b = (len & ~15u) + lane;  // fewer than 16 bytes can be left
     if (b < len) st_stream<uint8_t>(dp + b, ld_stream<uint8_t>(sp + b));
     return;
@@ -72,7 +76,10 @@ __device__ __forceinline__ void copy_tile(const char* sp, char* dp, uint32_t len
       v[2] = __builtin_amdgcn_alignbyte(v[3], v[2], r);
       v[3] = __builtin_amdgcn_alignbyte(up, v[3], r);
     }
-    if (lane < nvec) st_stream<u32x4>(dp + head + 16 * lane, v);
+    if (lane < nvec) {
+      const uint32_t w[4] = {v[0], v[1], v[2], v[3]};
+      st_through<4>(wave_uniform(dp + head), 16 * lane, 16 * nvec, w);
+    }
   }
   const uint32_t b = head + 16 * nvec + lane;  // fewer than 16 bytes can be left
   if (b < len) st_stream<uint8_t>(dp + b, ld_stream<uint8_t>(sp + b));

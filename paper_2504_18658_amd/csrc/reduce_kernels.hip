@@ -70,27 +70,29 @@ __device__ __forceinline__ void ld_batch(const char* const* sp, uint32_t lane_of
   }
 }
 
-// VE consecutive results, starting at element `e`, converted to the output dtype
+// VE consecutive results of this lane, converted to the output dtype: element threadIdx.x * VE
+// of the tile that starts at `dtile` (wave-uniform)
 template <int OUT, int VE, bool ALIGNED>
-__device__ __forceinline__ void store_vals(char* dst, size_t e, const float* a) {
+__device__ __forceinline__ void store_vals(char* dtile, const float* a) {
+  const uint32_t e = threadIdx.x * VE;
   if constexpr (narrow(OUT)) {
     if constexpr (VE == 1) {
-      st_elem<OUT>(dst, e, a[0]);
+      st_elem<OUT>(dtile, e, a[0]);
     } else {
       uint32_t w[VE / 2];
 #pragma unroll
       for (int k = 0; k < VE / 2; ++k) w[k] = pack16<OUT>(a[2 * k], a[2 * k + 1]);
-      st_words<VE / 2, 2, ALIGNED>(dst, e * 2, w);
+      st_tile_words<VE / 2, 2, ALIGNED>(dtile, e * 2, w);
     }
   } else {
     uint32_t w[VE];
 #pragma unroll
     for (int k = 0; k < VE; ++k) w[k] = __float_as_uint(a[k]);
     if constexpr (VE == 8) {
-      st_words<4, 4, ALIGNED>(dst, e * 4, w);
-      st_words<4, 4, ALIGNED>(dst, e * 4 + 16, w + 4);
+      st_tile_words<4, 4, ALIGNED>(dtile, e * 4, w);
+      st_tile_words<4, 4, ALIGNED>(dtile, e * 4 + 16, w + 4);
     } else {
-      st_words<VE, 4, ALIGNED>(dst, e * 4, w);
+      st_tile_words<VE, 4, ALIGNED>(dtile, e * 4, w);
     }
   }
 }
@@ -197,14 +199,14 @@ __device__ __forceinline__ void reduce_tile(const ReduceProblem& p, size_t tile,
           uint32_t w[W];
 #pragma unroll
           for (int k = 0; k < W; ++k) w[k] = pack16<IN>(t[2 * k], t[2 * k + 1]);
-          if (keep) st_words<W, ES, FAST>(prow, lane_off, w);
+          if (keep) st_tile_words<W, ES, FAST>(prow, lane_off, w);
           if (p.round_partial) unpack<IN, W>(w, t);
         }
       } else if (keep) {
         uint32_t w[W];
 #pragma unroll
         for (int k = 0; k < W; ++k) w[k] = __float_as_uint(t[k]);
-        st_words<W, ES, FAST>(prow, lane_off, w);
+        st_tile_words<W, ES, FAST>(prow, lane_off, w);
       }
 
 #pragma unroll
@@ -214,8 +216,10 @@ __device__ __forceinline__ void reduce_tile(const ReduceProblem& p, size_t tile,
 #pragma unroll
       for (int k = 0; k < VE; ++k) acc[k] = acc[k] / p.divisor;
     }
-    // the head offset goes into the base, whose alignment the store checks
-    store_vals<OUT, VE, FAST>(reinterpret_cast<char*>(p.dst) + head * (narrow(OUT) ? 2 : 4), v * VE, acc);
+    // the tile's first output element (the head offset included: the store checks this pointer's
+    // alignment; below the buffer for the idle head of tile 0, as tile_off is)
+    constexpr size_t EO = narrow(OUT) ? 2 : 4;
+    store_vals<OUT, VE, FAST>(reinterpret_cast<char*>(p.dst) + ((tile * BLOCK - shift) * VE + head) * EO, acc);
   }
 
   // the head element and the ragged tail (what the vectors leave): at most VE <= 8 elements

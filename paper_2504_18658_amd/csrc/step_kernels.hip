@@ -24,7 +24,9 @@ __global__ __launch_bounds__(BLOCK) void k_accumulate(char* acc, const char* rec
   const size_t block = linear_block_xz();
   const size_t v = block * BLOCK + threadIdx.x;
   if (v < nvec) {
-    const size_t off = v * (4 * W);
+    const size_t tile = block * BLOCK * (4 * W);  // wave-uniform byte offset of the block's vectors
+    const uint32_t lane_off = threadIdx.x * (4 * W);
+    const size_t off = tile + lane_off;
     uint32_t a[W], r[W], o[W];
     ld_words<W, ES, FAST>(acc, off, a);
     ld_words<W, ES, FAST>(recv, off, r);
@@ -35,7 +37,7 @@ __global__ __launch_bounds__(BLOCK) void k_accumulate(char* acc, const char* rec
       else
         o[k] = __float_as_uint(__uint_as_float(a[k]) + __uint_as_float(r[k]));
     }
-    st_words<W, ES, FAST>(acc, off, o);
+    st_tile_words<W, ES, FAST>(acc + tile, lane_off, o);
   }
   // ragged tail: fewer than VE <= 8 elements, taken by the last block that holds vectors
   if (block == (nvec == 0 ? 0 : (nvec - 1) / BLOCK)) {
