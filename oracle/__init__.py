@@ -296,3 +296,18 @@ def allgather_reassemble(slots, nodes, gpus):
     _check(lib().pccl_oracle_allgather_reassemble(d.ctypes.data, _ptr_array(views), nodes, gpus, cb),
            "allgather_reassemble")
     return d.view(slots[0].dtype)
+
+
+def phase2_reassemble(inter, slots, nodes, gpus, my_node, my_gpu, nthreads=1, divisor=0):
+    """The tail of one rank's two-level all-reduce (Section IV-A: all-reduce = two-level
+    reduce-scatter, then two-level all-gather), by composition of its two definitions: the
+    inter-node phase gives this rank's shard, shard[e] = round_io(sum over n of inter[n][e]);
+    the shard is this rank's own contribution to the all-gather, hierarchical slot
+    my_gpu*nodes + my_node; the gathered slots are shuffled into rank order.
+    slots: one array per hierarchical slot g*nodes+n; the entry at the rank's own slot is
+    ignored (None is fine).  Returns the rank-order buffer [nodes*gpus*chunk]."""
+    shard = rs_phase2(inter, None, nthreads, divisor)
+    filled = list(slots)
+    filled[my_gpu * nodes + my_node] = shard
+    return allgather_reassemble(filled, nodes, gpus)
+

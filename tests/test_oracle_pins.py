@@ -439,3 +439,47 @@ def test_unpacked_share_equals_the_world(nodes, gpus):
         [Yi[n * gpus + g2].reshape(-1) for g2 in range(gpus)], nodes, gpus, g, my_node=n,
         inter=[partial[n2 * gpus + g][n] for n2 in range(nodes)])
     assert _same_bits(shard, total[n * gpus + g])
+
+
+@pytest.mark.parametrize("nodes,gpus", [(2, 3), (4, 2), (1, 4), (3, 1)])
+def test_phase2_reassemble_equals_the_world(nodes, gpus):
+    """The all-reduce tail (inter-node phase, then the all-gather shuffle with the rank's own shard
+    in its own slot) gives every rank exactly the buffer the whole-world two-level all-reduce of
+    Section IV-A gives it -- reals in the fixed order, and on integers the plain sum of all messages."""
+    P, chunk = nodes * gpus, 7
+    rng = np.random.default_rng(91 + P)
+    for kind in ("real", "int", "bf16"):
+        if kind == "real":
+            Y = [rng.standard_normal((P, chunk)).astype(np.float32) for _ in range(P)]
+        else:
+            Y = [rng.integers(-20, 21, (P, chunk)).astype(np.float32) for _ in range(P)]
+        if kind == "bf16":
+            Y = [_torch_bf16_bits(y.reshape(-1)).reshape(P, chunk) for y in Y]
+        shards, partial = world.hier_reduce_scatter(Y, nodes, gpus)
+        final = world.hier_allreduce(Y, nodes, gpus)
+        for n in range(nodes):
+            for g in range(gpus):
+                inter = [partial[n2 * gpus + g][n] for n2 in range(nodes)]
+                # what the all-gather delivered: every OTHER rank's shard; the own slot holds junk
+                slots = [shards[n2 * gpus + g2] for g2 in range(gpus) for n2 in range(nodes)]
+                slots[g * nodes + n] = np.full_like(shards[0], 77)
+                out = oracle.phase2_reassemble(inter, slots, nodes, gpus, n, g)
+                assert _same_bits(out, final[n * gpus + g]), (kind, n, g)
+                if kind == "int":
+                    want = np.sum(np.stack(Y), axis=0).astype(np.float32).reshape(-1)
+                    assert _same_bits(out, want)
+                # rank stamp: chunk (n', g') of the result is rank (n', g')'s shard, the own one included
+                for r in range(P):
+                    assert _same_bits(out.reshape(P, chunk)[r], shards[r])
+
+
+def test_phase2_reassemble_average_and_ignored_slot():
+    """op = average divides the rank's own shard only (the gathered chunks arrive finished), and the
+    entry at the rank's own slot is never read (None is accepted)."""
+    nodes, gpus, chunk = 2, 2, 3
+    inter = [np.array([1, 2, 3], np.float32), np.array([3, 2, 1], np.float32)]
+    slots = [np.full(chunk, 10 * k, np.float32) for k in range(4)]
+    slots[1 * nodes + 0] = None                                  # rank (node 0, gpu 1): slot g*N + n = 2
+    out = oracle.phase2_reassemble(inter, slots, nodes, gpus, 0, 1, divisor=4).reshape(4, chunk)
+    assert out[0 * gpus + 1].tolist() == [1.0, 1.0, 1.0]          # (1+3)/4, (2+2)/4, (3+1)/4
+    assert out[0].tolist() == [0.0] * 3 and out[2].tolist() == [10.0] * 3 and out[3].tolist() == [30.0] * 3
