@@ -170,6 +170,8 @@ pccl_status_t pccl_hier_unpack(void* dst, const void* src, int nodes, int gpus_p
  *            elements each; slot my_node is ignored and partial[my_node] is used.
  * partial is caller-provided scratch/output: [nodes][chunk_count] of io_dt (it is the
  * buffer that would go on the wire between the phases).  Two kernels are enqueued.
+ * shard == NULL runs phase 1 only (one kernel; d_inter and my_node are then unused apart from
+ * their checks): for callers that finish with pccl_phase2_reassemble_local.
  * Errors: NULLs; nodes/gpus < 1; my_node outside [0, nodes); stride < nodes*chunk bytes;
  * shard or partial overlapping the intra span or each other. */
 pccl_status_t pccl_reduce_scatter_local(void* shard, void* partial, const void* intra_base,
@@ -209,7 +211,8 @@ pccl_status_t pccl_reduce_scatter_local_static(void* shard, const void* intra_ba
  * and piece_g'[n][e] = message_g'[(n*gpus_per_node + my_gpu)*chunk_count + e]: the chunks
  * bound for local id my_gpu on every node, read through the node stride.  Everything else
  * (partial, shard, d_inter, my_node, order of the sums) is as in pccl_reduce_scatter_local,
- * and the results are bit-identical to packing every message first.
+ * and the results are bit-identical to packing every message first (shard == NULL: phase 1
+ * only, as there).
  * Errors: as there; my_gpu outside [0, gpus_per_node); nodes > 65535. */
 pccl_status_t pccl_reduce_scatter_local_unpacked(void* shard, void* partial, const void* msgs_base,
                                                  size_t msg_stride_bytes,
@@ -226,6 +229,30 @@ pccl_status_t pccl_reduce_scatter_local_unpacked(void* shard, void* partial, con
 pccl_status_t pccl_allgather_reassemble(void* dst, const void* src, const void* const* d_slots,
                                         int nodes, int gpus_per_node, size_t chunk_bytes,
                                         pccl_stream_t stream);
+
+/* The tail of one rank's two-level all-reduce in ONE launch (Section IV-A: all-reduce = the
+ * two-level reduce-scatter, then the two-level all-gather, whose step 3 is the device-local
+ * shuffle; Section III-A: the timings include the intra-GPU transposes): the inter-node phase
+ * of the reduce-scatter share and the all-gather shuffle together, the rank's own shard being
+ * stored straight at its rank-order place instead of in a buffer that a later pass copies.
+ *   dst chunk (my_node*M + my_gpu)[e] = round_io( sum over n' = 0..N-1, in order, of inter_n'[e] )
+ *            with inter_n' as in phase 2 of pccl_reduce_scatter_local: partial[n'] when
+ *            d_inter == NULL, else d_inter[n'] (slot my_node ignored, partial[my_node] used);
+ *            partial is [nodes][chunk_count] of io_dt, the phase-1 result (read only);
+ *            op = PCCL_AVG divides this chunk's sum by N*M (the gathered chunks arrive finished).
+ *   dst chunk (n*M + g) = slot (g*N + n)  for every other rank (n, g), chunk_count elements
+ *            each, the slots contiguous in hierarchical order at `src` (d_slots == NULL) or
+ *            each in its own buffer (d_slots: device array of P device pointers, `src` unused).
+ *            The rank's own slot, g = my_gpu and n = my_node, is never read.
+ * dst holds N*M*chunk_count elements.  The bits of dst are those of
+ * pccl_reduce_scatter_local's phase 2 followed by pccl_allgather_reassemble with the shard in the
+ * rank's own slot.  Errors: NULL dst / partial / both of src and d_slots; nodes/gpus < 1;
+ * my_node or my_gpu out of range; size overflow; dst overlapping partial or src; more than
+ * 65535 gpus_per_node or nodes. */
+pccl_status_t pccl_phase2_reassemble_local(void* dst, const void* partial, const void* const* d_inter,
+                                           const void* src, const void* const* d_slots, int nodes,
+                                           int gpus_per_node, int my_node, int my_gpu, size_t chunk_count,
+                                           pccl_dtype_t io_dt, pccl_op_t op, pccl_stream_t stream);
 
 /* nbuckets independent two-level reduce-scatter shares (pccl_reduce_scatter_local with
  * d_inter == NULL) in one launch per phase -- the shape of the many reduce-scatters a

@@ -10,7 +10,7 @@ from .binding import (  # noqa: F401
     pccl_allgather_reassemble_batched, pccl_hier_pack_batched, pccl_permute_bucket_t,
     pccl_bucket_t, pccl_check_device_range, pccl_choose_algorithm, pccl_halving_reduce_scatter_local, pccl_hier_pack,
     pccl_hier_unpack, pccl_link_model_t, pccl_local_reduce, pccl_local_reduce_ptrs,
-    pccl_local_reduce_ptrs_two_level, pccl_reduce_scatter_local, pccl_reduce_scatter_local_batched, pccl_reduce_scatter_local_static,
+    pccl_local_reduce_ptrs_two_level, pccl_phase2_reassemble_local, pccl_reduce_scatter_local, pccl_reduce_scatter_local_batched, pccl_reduce_scatter_local_static,
     pccl_reduce_scatter_local_unpacked, pccl_reduce_scatter_local_unpacked_batched,
     pccl_ring_reduce_scatter_local, status_string,
 )

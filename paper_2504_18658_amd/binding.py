@@ -25,6 +25,7 @@ EXPORTS = (
     "pccl_allgather_reassemble_batched", "pccl_hier_pack_batched", "pccl_halving_reduce_scatter_local", "pccl_model_ring", "pccl_model_rec",
     "pccl_choose_algorithm", "pccl_model_two_level", "pccl_status_string", "pccl_check_device_range",
     "pccl_reduce_scatter_local_unpacked_batched", "pccl_reduce_scatter_local_static", "pccl_diag_reload_env", "pccl_build_id",
+    "pccl_phase2_reassemble_local",
 )
 PCCL_ALGO_RING, PCCL_ALGO_REC = 0, 1
 _NO_STATUS = ("pccl_status_string", "pccl_model_ring", "pccl_model_rec", "pccl_model_two_level",
@@ -73,6 +74,7 @@ def lib():
         L.pccl_reduce_scatter_local.argtypes = [vp, vp, vp, sz, vp, i, i, i, sz, i, i, vp]
         L.pccl_reduce_scatter_local_static.argtypes = [vp, vp, sz, vp, i, i, i, sz, i, i, vp]
         L.pccl_allgather_reassemble.argtypes = [vp, vp, vp, i, i, sz, vp]
+        L.pccl_phase2_reassemble_local.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, sz, i, i, vp]
         L.pccl_reduce_scatter_local_batched.argtypes = [vp, vp, i, i, i, i, i, vp]
         L.pccl_reduce_scatter_local_unpacked_batched.argtypes = [vp, vp, i, i, i, i, i, i, vp]
         L.pccl_accumulate.argtypes = [vp, vp, sz, i, i, vp]
@@ -238,18 +240,18 @@ def pccl_reduce_scatter_local(shard, partial, intra, d_inter=None, my_node=0, st
 
     intra: [gpus][nodes][chunk] (piece g' = intra[g'], rows may be strided apart);
     partial: [nodes][chunk] scratch/output; shard: [chunk]; d_inter: optional int64 device
-    tensor of `nodes` pointers to the chunks received from the other nodes."""
+    tensor of `nodes` pointers to the chunks received from the other nodes.  shard=None: phase 1 only."""
     if intra.dim() != 3:
         raise ValueError("pccl_reduce_scatter_local: intra must be [gpus][nodes][chunk]")
     base, stride, gpus, _ = _rows(intra, "intra")
     nodes, chunk = intra.shape[1], intra.shape[2]
-    if partial.numel() != nodes * chunk or shard.numel() != chunk or \
-            partial.dtype != intra.dtype or shard.dtype != intra.dtype or \
-            not partial.is_contiguous() or not shard.is_contiguous():
+    if partial.numel() != nodes * chunk or partial.dtype != intra.dtype or not partial.is_contiguous() or \
+            (shard is not None and (shard.numel() != chunk or shard.dtype != intra.dtype or
+                                    not shard.is_contiguous())):
         raise ValueError("pccl_reduce_scatter_local: partial is [nodes][chunk], shard is [chunk], "
                          "both contiguous and of the message dtype")
     _check(lib().pccl_reduce_scatter_local(
-        _dev(shard, "shard"), _dev(partial, "partial"), base, stride,
+        None if shard is None else _dev(shard, "shard"), _dev(partial, "partial"), base, stride,
         None if d_inter is None else _dev(d_inter, "d_inter"), nodes, gpus, my_node, chunk,
         dtype_code(intra.dtype), _op(average), _stream(stream)), "pccl_reduce_scatter_local")
     return shard
@@ -277,6 +279,26 @@ def pccl_allgather_reassemble(dst, src=None, d_slots=None, nodes=1, gpus_per_nod
         _dev(dst, "dst"), None if src is None else _dev(src, "src"),
         None if d_slots is None else _dev(d_slots, "d_slots"), nodes, gpus_per_node, cb,
         _stream(stream)), "pccl_allgather_reassemble")
+    return dst
+
+
+def pccl_phase2_reassemble_local(dst, partial, d_inter=None, src=None, d_slots=None, nodes=1, gpus_per_node=1,
+                                 my_node=0, my_gpu=0, stream=None, average=False):
+    """The all-reduce tail in one launch: the inter-node phase into the rank's own chunk of dst, and
+    the other chunks from their hierarchical slots (contiguous src, or int64 pointer tensor d_slots)
+    into rank order.  partial: [nodes][chunk] phase-1 result; dst: [nodes*gpus*chunk]."""
+    if partial.numel() % nodes != 0:
+        raise ValueError("pccl_phase2_reassemble_local: partial is [nodes][chunk]")
+    chunk = partial.numel() // nodes
+    if dst.numel() != nodes * gpus_per_node * chunk or dst.dtype != partial.dtype or not dst.is_contiguous() or \
+            not partial.is_contiguous() or (src is not None and (src.numel() != dst.numel() or
+                                                                 src.dtype != dst.dtype or not src.is_contiguous())):
+        raise ValueError("pccl_phase2_reassemble_local: dst and src are [nodes*gpus*chunk] of partial's dtype")
+    _check(lib().pccl_phase2_reassemble_local(
+        _dev(dst, "dst"), _dev(partial, "partial"), None if d_inter is None else _dev(d_inter, "d_inter"),
+        None if src is None else _dev(src, "src"), None if d_slots is None else _dev(d_slots, "d_slots"),
+        nodes, gpus_per_node, my_node, my_gpu, chunk, dtype_code(partial.dtype), _op(average), _stream(stream)),
+        "pccl_phase2_reassemble_local")
     return dst
 
 
@@ -381,7 +403,13 @@ def pccl_reduce_scatter_local_unpacked(shard, partial, msgs=None, d_msgs=None, d
     """The two-level reduce-scatter share straight from the node-mates' rank-order messages.
 
     msgs: [gpus][nodes*gpus*chunk] tensor (row g' = node-mate g's message, rows may be strided
-    apart), or d_msgs: int64 device tensor of `gpus` pointers to such messages."""
+    apart), or d_msgs: int64 device tensor of `gpus` pointers to such messages.
+    shard=None: phase 1 only (the chunk size then follows from partial)."""
+    only_phase1 = shard is None
+    if only_phase1:
+        if partial.numel() % nodes != 0:
+            raise ValueError("pccl_reduce_scatter_local_unpacked: partial is [nodes][chunk]")
+        shard = partial[: partial.numel() // nodes]              # stands in for the dtype and chunk size only
     chunk = shard.numel()
     if partial.numel() != nodes * chunk or partial.dtype != shard.dtype or \
             not partial.is_contiguous() or not shard.is_contiguous():
@@ -395,11 +423,11 @@ def pccl_reduce_scatter_local_unpacked(shard, partial, msgs=None, d_msgs=None, d
         if d_msgs.numel() != gpus_per_node:
             raise ValueError("pccl_reduce_scatter_local_unpacked: need gpus_per_node message pointers")
     _check(lib().pccl_reduce_scatter_local_unpacked(
-        _dev(shard, "shard"), _dev(partial, "partial"), base, stride,
+        None if only_phase1 else _dev(shard, "shard"), _dev(partial, "partial"), base, stride,
         None if d_msgs is None else _dev(d_msgs, "d_msgs"),
         None if d_inter is None else _dev(d_inter, "d_inter"), nodes, gpus_per_node, my_node, my_gpu, chunk,
         dtype_code(shard.dtype), _op(average), _stream(stream)), "pccl_reduce_scatter_local_unpacked")
-    return shard
+    return None if only_phase1 else shard
 
 
 def pccl_choose_algorithm(p, m_bytes, alpha_ring, beta_ring, alpha_rec, beta_rec):

@@ -8,8 +8,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpccl_local.so")
 SOURCES = ["pccl_api.hip", "reduce_kernels.hip", "permute_kernels.hip", "step_kernels.hip",
-           "cost_model.hip", "address_check.hip", "knobs.hip"]
-HEADERS = ["device_utils.h", "kernels.h", "address_check.h", "knobs.h", os.path.join("..", "..", "include", "pccl_local.h")]
+           "fused_kernels.hip", "cost_model.hip", "address_check.hip", "knobs.hip"]
+HEADERS = ["device_utils.h", "kernels.h", "address_check.h", "knobs.h", "reduce_device.h", "permute_device.h", os.path.join("..", "..", "include", "pccl_local.h")]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

@@ -51,6 +51,19 @@ struct PermuteProblem {
   int cols;
 };
 
+// Launch shape of the kernel that runs a flat sum and a chunk transpose in one grid: blocks with
+// blockIdx.z < reduce_planes are reduction tiles (linear index over z, y, x; reduce_tiles of
+// them do work), the others copy tiles of source chunk (blockIdx.y, blockIdx.z - reduce_planes),
+// except chunk (own_r, own_c), whose destination the reduction writes.
+struct FusedShape {
+  uint32_t tiles_per_chunk;
+  uint32_t skew;
+  uint32_t reduce_planes;
+  uint32_t reduce_tiles;
+  int own_r;
+  int own_c;
+};
+
 constexpr int kMaxBuckets = PCCL_MAX_BUCKETS;
 
 // Prefix of tiles over the buckets of a batch, passed by value to the batched kernels.
@@ -83,6 +96,12 @@ hipError_t launch_permute_batched(const pccl_permute_bucket_t* d_buckets,
 bool split_grid_xz(size_t blocks, unsigned threads, unsigned* gx, unsigned* gz);
 
 hipError_t launch_permute(const PermuteProblem& p, hipStream_t st);
+
+// One launch for a flat sum (p: one node of p.gpus sources of dtype dt, result into p.dst, no
+// partial kept, one row) and the chunk transpose q without its source chunk (own_r, own_c);
+// p.dst is expected to be that chunk's place in q.dst.
+hipError_t launch_phase2_reassemble(const ReduceProblem& p, const PermuteProblem& q, int own_r, int own_c, int dt,
+                                    hipStream_t st);
 
 // acc[e] = round_io(acc[e] + recv[e]) for e < count, in place (the two ranges are disjoint).
 hipError_t launch_accumulate(void* acc, const void* recv, size_t count, int dt, hipStream_t st);

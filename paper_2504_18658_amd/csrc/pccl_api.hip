@@ -231,10 +231,11 @@ struct ShareSizes {
   size_t es, piece_count, piece_bytes, chunk_bytes, span;
 };
 
+// (a NULL shard is the caller's business: phase 1 only, where the entry point allows it)
 pccl_status_t check_share(const void* shard, const void* intra_base, size_t intra_stride_bytes, int nodes,
                           int gpus_per_node, int my_node, size_t chunk_count, pccl_dtype_t io_dt, pccl_op_t op,
                           ShareSizes* z) {
-  if (shard == nullptr || intra_base == nullptr) return PCCL_ERR_NULL;
+  if (intra_base == nullptr) return PCCL_ERR_NULL;
   if (pccl_status_t s = check_common(io_dt, io_dt, op)) return s;
   if (nodes < 1 || gpus_per_node < 1 || my_node < 0 || my_node >= nodes) return PCCL_ERR_INVALID;
   if (!divisor_ok(op, (size_t)nodes * (size_t)gpus_per_node)) return PCCL_ERR_INVALID;
@@ -248,7 +249,7 @@ pccl_status_t check_share(const void* shard, const void* intra_base, size_t intr
   if (!mul_ok((size_t)(gpus_per_node - 1), gpus_per_node > 1 ? intra_stride_bytes : 0, &z->span) ||
       !add_ok(z->span, z->piece_bytes, &z->span))
     return PCCL_ERR_INVALID;
-  if (overlaps(shard, z->chunk_bytes, intra_base, z->span)) return PCCL_ERR_OVERLAP;
+  if (shard != nullptr && overlaps(shard, z->chunk_bytes, intra_base, z->span)) return PCCL_ERR_OVERLAP;
   return PCCL_OK;
 }
 
@@ -269,6 +270,7 @@ pccl_status_t launch_share(void* shard, void* partial, const void* intra_base, s
   p1.gpus = gpus_per_node;
   const hipError_t e = launch_flat(p1, dt, dt, st);
   if (e != hipSuccess) return e == hipErrorInvalidValue ? PCCL_ERR_INVALID : PCCL_ERR_HIP;
+  if (shard == nullptr) return PCCL_OK;  // phase 1 only
   return phase2(shard, partial, d_inter, nodes, my_node, chunk_count, z.chunk_bytes, dt, divisor, st);
 }
 
@@ -424,12 +426,13 @@ pccl_status_t pccl_reduce_scatter_local(void* shard, void* partial, const void* 
                                     chunk_count, io_dt, op, &z))
     return s;
   if (!elem_aligned(partial, z.es)) return PCCL_ERR_INVALID;
-  if (overlaps(partial, z.piece_bytes, intra_base, z.span) || overlaps(shard, z.chunk_bytes, partial, z.piece_bytes))
+  if (overlaps(partial, z.piece_bytes, intra_base, z.span) ||
+      (shard != nullptr && overlaps(shard, z.chunk_bytes, partial, z.piece_bytes)))
     return PCCL_ERR_OVERLAP;
   if (chunk_count == 0) return PCCL_OK;
   AddressChecks ck(stream);
   if (ck.on()) {
-    ck.range(shard, z.chunk_bytes);
+    if (shard != nullptr) ck.range(shard, z.chunk_bytes);
     ck.range(partial, z.piece_bytes);
     ck.range(intra_base, z.span);
     if (d_inter != nullptr) ck.pointers(d_inter, (size_t)nodes, 0, z.chunk_bytes, my_node);
@@ -444,6 +447,7 @@ pccl_status_t pccl_reduce_scatter_local_static(void* shard, const void* intra_ba
                                                int nodes, int gpus_per_node, int my_node,
                                                size_t chunk_count, pccl_dtype_t io_dt, pccl_op_t op,
                                                pccl_stream_t stream) {
+  if (shard == nullptr) return PCCL_ERR_NULL;  // the partial cannot be read back: there is no phase-1-only form
   ShareSizes z;
   if (pccl_status_t s = check_share(shard, intra_base, intra_stride_bytes, nodes, gpus_per_node, my_node,
                                     chunk_count, io_dt, op, &z))
@@ -463,8 +467,7 @@ pccl_status_t pccl_reduce_scatter_local_unpacked(void* shard, void* partial, con
                                                  int gpus_per_node, int my_node, int my_gpu,
                                                  size_t chunk_count, pccl_dtype_t io_dt,
                                                  pccl_op_t op, pccl_stream_t stream) {
-  if (shard == nullptr || partial == nullptr || (msgs_base == nullptr && d_msgs == nullptr))
-    return PCCL_ERR_NULL;
+  if (partial == nullptr || (msgs_base == nullptr && d_msgs == nullptr)) return PCCL_ERR_NULL;
   if (pccl_status_t s = check_common(io_dt, io_dt, op)) return s;
   if (nodes < 1 || gpus_per_node < 1 || my_node < 0 || my_node >= nodes || my_gpu < 0 ||
       my_gpu >= gpus_per_node || nodes > 65535 ||
@@ -478,7 +481,7 @@ pccl_status_t pccl_reduce_scatter_local_unpacked(void* shard, void* partial, con
       !mul_ok(chunk_bytes, (size_t)nodes, &piece_bytes))
     return PCCL_ERR_INVALID;
   if (!elem_aligned(shard, es) || !elem_aligned(partial, es)) return PCCL_ERR_INVALID;
-  if (overlaps(shard, chunk_bytes, partial, piece_bytes)) return PCCL_ERR_OVERLAP;
+  if (shard != nullptr && overlaps(shard, chunk_bytes, partial, piece_bytes)) return PCCL_ERR_OVERLAP;
   if (d_msgs == nullptr) {
     if (!elem_aligned(msgs_base, es)) return PCCL_ERR_INVALID;
     if (gpus_per_node > 1 && (msg_stride_bytes < msg_bytes || msg_stride_bytes % es != 0))
@@ -487,13 +490,13 @@ pccl_status_t pccl_reduce_scatter_local_unpacked(void* shard, void* partial, con
         !add_ok(span, msg_bytes, &span))
       return PCCL_ERR_INVALID;
     if (overlaps(partial, piece_bytes, msgs_base, span) ||
-        overlaps(shard, chunk_bytes, msgs_base, span))
+        (shard != nullptr && overlaps(shard, chunk_bytes, msgs_base, span)))
       return PCCL_ERR_OVERLAP;
   }
   if (chunk_count == 0) return PCCL_OK;
   AddressChecks ck(stream);
   if (ck.on()) {
-    ck.range(shard, chunk_bytes);
+    if (shard != nullptr) ck.range(shard, chunk_bytes);
     ck.range(partial, piece_bytes);
     if (d_msgs == nullptr)
       ck.range(msgs_base, span);
@@ -527,7 +530,65 @@ pccl_status_t pccl_reduce_scatter_local_unpacked(void* shard, void* partial, con
   }
   const hipError_t e = pccl::launch_reduce(p1, dt, dt, st);
   if (e != hipSuccess) return e == hipErrorInvalidValue ? PCCL_ERR_INVALID : PCCL_ERR_HIP;
+  if (shard == nullptr) return PCCL_OK;  // phase 1 only
   return phase2(shard, partial, d_inter, nodes, my_node, chunk_count, chunk_bytes, dt, divisor, st);
+}
+
+pccl_status_t pccl_phase2_reassemble_local(void* dst, const void* partial, const void* const* d_inter,
+                                           const void* src, const void* const* d_slots, int nodes,
+                                           int gpus_per_node, int my_node, int my_gpu, size_t chunk_count,
+                                           pccl_dtype_t io_dt, pccl_op_t op, pccl_stream_t stream) {
+  if (dst == nullptr || partial == nullptr || (src == nullptr && d_slots == nullptr)) return PCCL_ERR_NULL;
+  if (pccl_status_t s = check_common(io_dt, io_dt, op)) return s;
+  if (nodes < 1 || gpus_per_node < 1 || my_node < 0 || my_node >= nodes || my_gpu < 0 || my_gpu >= gpus_per_node)
+    return PCCL_ERR_INVALID;
+  size_t ranks, chunk_bytes, piece_bytes, total;
+  if (!mul_ok((size_t)nodes, (size_t)gpus_per_node, &ranks) || ranks > 0x7FFFFFFFull || !divisor_ok(op, ranks))
+    return PCCL_ERR_INVALID;
+  const size_t es = esize(io_dt);
+  if (!mul_ok(chunk_count, es, &chunk_bytes) || !mul_ok(chunk_bytes, (size_t)nodes, &piece_bytes) ||
+      !mul_ok(chunk_bytes, ranks, &total))
+    return PCCL_ERR_INVALID;
+  if (!elem_aligned(dst, es) || !elem_aligned(partial, es)) return PCCL_ERR_INVALID;
+  if (overlaps(dst, total, partial, piece_bytes)) return PCCL_ERR_OVERLAP;
+  if (d_slots == nullptr && overlaps(dst, total, src, total)) return PCCL_ERR_OVERLAP;
+  if (chunk_count == 0) return PCCL_OK;
+  AddressChecks ck(stream);
+  if (ck.on()) {
+    ck.range(dst, total);
+    ck.range(partial, piece_bytes);
+    if (d_inter != nullptr) ck.pointers(d_inter, (size_t)nodes, 0, chunk_bytes, my_node);
+    if (d_slots == nullptr)
+      ck.range(src, total);
+    else
+      ck.pointers(d_slots, ranks, 0, chunk_bytes, (long long)my_gpu * nodes + my_node);
+    if (ck.status != PCCL_OK) return ck.status;
+  }
+  // inter-node phase: a flat sum of `nodes` chunks into the rank's own chunk of the result
+  ReduceProblem p2 = blank_problem();
+  p2.dst = reinterpret_cast<char*>(dst) + ((size_t)my_node * gpus_per_node + my_gpu) * chunk_bytes;
+  p2.count = chunk_count;
+  p2.gpus = nodes;
+  p2.divisor = divisor_for(op, ranks);
+  if (d_inter == nullptr) {
+    p2.base = reinterpret_cast<const char*>(partial);
+    p2.stride_g = chunk_bytes;
+  } else {
+    p2.ptrs = d_inter;
+    p2.override_index = my_node;
+    p2.override_ptr = reinterpret_cast<const char*>(partial) + (size_t)my_node * chunk_bytes;
+  }
+  // shuffle: source chunk (g, n) = hierarchical slot g*N + n -> rank-order chunk n*M + g
+  PermuteProblem q;
+  q.dst = reinterpret_cast<char*>(dst);
+  q.src = d_slots != nullptr ? nullptr : reinterpret_cast<const char*>(src);
+  q.slots = d_slots;
+  q.chunk_bytes = chunk_bytes;
+  q.rows = gpus_per_node;
+  q.cols = nodes;
+  const hipError_t e = pccl::launch_phase2_reassemble(p2, q, my_gpu, my_node, io_dt,
+                                                      reinterpret_cast<hipStream_t>(stream));
+  return e == hipErrorInvalidValue ? PCCL_ERR_INVALID : from_hip(e);
 }
 
 // Both batched shares.  my_gpu < 0: intra_base holds gpus_per_node pre-shuffled pieces of

@@ -145,7 +145,8 @@ def test_reduce_scatter_local_rejects_bad_arguments():
         return f(a["shard"], a["partial"], a["intra"], a["stride"], a["inter"], a["nodes"], a["gpus"],
                  a["my"], a["chunk"], a["dt"], a["op"], None)
 
-    assert call(shard=None) == pccl.PCCL_ERR_NULL
+    assert call(shard=None, chunk=0) == pccl.PCCL_OK          # no shard: phase 1 only
+    assert call(shard=None, partial=None) == pccl.PCCL_ERR_NULL
     assert call(partial=None) == pccl.PCCL_ERR_NULL
     assert call(intra=None) == pccl.PCCL_ERR_NULL
     assert call(nodes=0) == pccl.PCCL_ERR_INVALID
@@ -298,7 +299,7 @@ def test_unpacked_reduce_scatter_rejects_bad_arguments():
         return f(a["shard"], a["partial"], a["msgs"], a["stride"], a["d_msgs"], a["d_inter"], a["n"], a["m"],
                  a["my_n"], a["my_g"], a["c"], a["dt"], a["op"], None)
 
-    assert call(shard=None) == pccl.PCCL_ERR_NULL
+    assert call(shard=None, c=0) == pccl.PCCL_OK               # no shard: phase 1 only
     assert call(partial=None) == pccl.PCCL_ERR_NULL
     assert call(msgs=None) == pccl.PCCL_ERR_NULL               # neither a base nor a pointer array
     assert call(my_g=2) == pccl.PCCL_ERR_INVALID
@@ -383,3 +384,33 @@ def test_unpacked_batched_rejects_bad_arguments():
     assert f(A, ctypes.addressof(bad), 1, 4, 8, 3, 1, 0, None) == pccl.PCCL_ERR_NULL
     empty = (pccl.pccl_bucket_t * 1)(pccl.pccl_bucket_t(None, None, None, 0, 0))
     assert f(A, ctypes.addressof(empty), 1, 4, 8, 3, 1, 0, None) == pccl.PCCL_OK
+
+
+def test_phase2_reassemble_rejects_bad_arguments():
+    f = pccl.lib().pccl_phase2_reassemble_local
+    # 4 nodes x 2 gpus, 256-element fp32 chunks: the result is 8 KiB, the partial 4 KiB
+    ok = dict(dst=A, partial=2 * A, inter=None, src=8 * A, slots=None, n=4, m=2, my_n=1, my_g=1, c=256, dt=0, op=0)
+
+    def call(**kw):
+        a = dict(ok, **kw)
+        return f(a["dst"], a["partial"], a["inter"], a["src"], a["slots"], a["n"], a["m"], a["my_n"], a["my_g"],
+                 a["c"], a["dt"], a["op"], None)
+
+    assert call(dst=None) == pccl.PCCL_ERR_NULL
+    assert call(partial=None) == pccl.PCCL_ERR_NULL
+    assert call(src=None) == pccl.PCCL_ERR_NULL                # neither contiguous slots nor a pointer array
+    assert call(n=0) == pccl.PCCL_ERR_INVALID
+    assert call(m=0) == pccl.PCCL_ERR_INVALID
+    assert call(my_n=4) == pccl.PCCL_ERR_INVALID
+    assert call(my_g=2) == pccl.PCCL_ERR_INVALID
+    assert call(my_g=-1) == pccl.PCCL_ERR_INVALID
+    assert call(c=1 << 61) == pccl.PCCL_ERR_INVALID
+    assert call(n=1 << 20, m=1 << 12, my_n=0) == pccl.PCCL_ERR_INVALID     # 2^32 ranks
+    assert call(dt=5) == pccl.PCCL_ERR_UNSUPPORTED
+    assert call(op=3) == pccl.PCCL_ERR_UNSUPPORTED
+    assert call(dst=A + 2) == pccl.PCCL_ERR_INVALID            # fp32 result not 4-byte aligned
+    assert call(partial=A + 8188) == pccl.PCCL_ERR_OVERLAP     # partial starts in the last word of the result
+    assert call(src=A + 4096) == pccl.PCCL_ERR_OVERLAP
+    assert call(dst=8 * A + 8188) == pccl.PCCL_ERR_OVERLAP
+    assert call(c=0) == pccl.PCCL_OK
+    assert call(op=1, n=1 << 13, m=1 << 12, my_n=0, c=0) == pccl.PCCL_ERR_INVALID   # average: 2^25 ranks
