@@ -317,14 +317,31 @@ pccl_status_t pccl_hier_pack_batched(const pccl_permute_bucket_t* d_buckets,
 pccl_status_t pccl_accumulate(void* acc, const void* recv, size_t count, pccl_dtype_t io_dt,
                               pccl_op_t op, pccl_stream_t stream);
 
+/* npairs independent steps acc_k += recv_k (pccl_accumulate) of different sizes in ONE launch:
+ * what a rank runs when several collectives -- the reduce-scatters of many gradient buckets,
+ * Section II-A -- reach the same ring or halving step together.  d_pairs: device array read by
+ * the kernel; h_pairs: HOST copy of the same descriptors for the argument checks and the launch
+ * size.  A pair with count == 0 is skipped; npairs <= PCCL_MAX_BUCKETS.
+ * Errors: NULLs; size overflow; an acc range overlapping its own recv, or any range of an
+ * earlier pair other than recv with recv (two pairs may read the same received buffer). */
+typedef struct {
+  void* acc;        /* in/out: count elements of io_dt */
+  const void* recv; /* in    : count elements of io_dt */
+  size_t count;
+} pccl_accumulate_pair_t;
+pccl_status_t pccl_accumulate_batched(const pccl_accumulate_pair_t* d_pairs, const pccl_accumulate_pair_t* h_pairs,
+                                      int npairs, pccl_dtype_t io_dt, pccl_op_t op, pccl_stream_t stream);
+
 /* One rank's reduction work in a ring reduce-scatter over `nranks` ranks (Section II-B ring;
  * Section IV-B PCCL_ring): every rank sends to rank+1 and receives from rank-1, and rank r
  * ends up owning chunk r.  msg is this rank's message, [nranks][chunk_count] of io_dt,
  * updated in place.  At step s = 0 .. nranks-2 the chunk received from rank-1,
  *     recv_s = (const char*)recv_base + s*recv_stride_bytes   (chunk_count elements),
  * is added into chunk (rank - 2 - s) mod nranks of msg; that chunk is what step s+1 would
- * forward, and after the last step chunk `rank` of msg is the owned shard.  One kernel per
- * step is enqueued (in a real run a message arrival separates them).
+ * forward, and after the last step chunk `rank` of msg is the owned shard.  The steps update
+ * nranks-1 DIFFERENT chunks, so ONE kernel is enqueued for all of them (every received chunk
+ * must be there when it starts); a caller that starts each step as its message arrives calls
+ * pccl_accumulate per step instead, with the same bits.
  * Errors: NULLs; nranks < 1; rank outside [0, nranks); recv_stride_bytes < chunk bytes when
  * more than one chunk is received; msg overlapping the recv span. */
 pccl_status_t pccl_ring_reduce_scatter_local(void* msg, const void* recv_base,
@@ -339,7 +356,11 @@ pccl_status_t pccl_ring_reduce_scatter_local(void* msg, const void* recv_base,
  * [nranks][chunk_count] of io_dt, updated in place; recv holds the received halves back to
  * back: step t's half ([nranks >> (t+1)][chunk_count]) starts at element
  * chunk_count * (nranks - (nranks >> t)), (nranks-1)*chunk_count elements in all.  After the
- * last step chunk `rank` of msg is the owned shard.  One kernel per step is enqueued.
+ * last step chunk `rank` of msg is the owned shard.  The kept ranges are nested, so ONE kernel
+ * is enqueued: every chunk of the first kept half is read once, takes the additions of the
+ * steps it is part of in registers -- each sum rounded through io_dt exactly as the stored
+ * result of a step is -- and is written once (every received half must be there at the start;
+ * per step, call pccl_accumulate on the kept range: same bits).
  * Errors: NULLs; nranks not a power of two; rank outside [0, nranks); msg overlapping recv. */
 pccl_status_t pccl_halving_reduce_scatter_local(void* msg, const void* recv, int nranks, int rank,
                                                 size_t chunk_count, pccl_dtype_t io_dt,

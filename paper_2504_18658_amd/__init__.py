@@ -6,7 +6,7 @@ its thin ctypes binding plus the seeded workload generators.  Nothing is loaded 
 from .binding import (  # noqa: F401
     PCCL_ALGO_REC, PCCL_ALGO_RING, PCCL_AVG, PCCL_BF16, PCCL_ERR_ADDRESS, PCCL_ERR_HIP, PCCL_ERR_INVALID, PCCL_ERR_NULL,
     PCCL_ERR_OVERLAP, PCCL_ERR_SCRATCH, PCCL_ERR_UNSUPPORTED, PCCL_F16, PCCL_F32, PCCL_MAX_BUCKETS, PCCL_OK, PCCL_STATIC_SCRATCH_BYTES, PCCL_SUM,
-    BucketTable, PcclError, PermuteTable, device_pointer_array, diag_reload_env, lib, pccl_accumulate, pccl_allgather_reassemble,
+    AccumulateTable, BucketTable, PcclError, PermuteTable, device_pointer_array, diag_reload_env, lib, pccl_accumulate, pccl_accumulate_batched, pccl_accumulate_pair_t, pccl_allgather_reassemble,
     pccl_allgather_reassemble_batched, pccl_hier_pack_batched, pccl_permute_bucket_t,
     pccl_bucket_t, pccl_check_device_range, pccl_choose_algorithm, pccl_halving_reduce_scatter_local, pccl_hier_pack,
     pccl_hier_unpack, pccl_link_model_t, pccl_local_reduce, pccl_local_reduce_ptrs,

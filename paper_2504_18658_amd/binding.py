@@ -25,7 +25,7 @@ EXPORTS = (
     "pccl_allgather_reassemble_batched", "pccl_hier_pack_batched", "pccl_halving_reduce_scatter_local", "pccl_model_ring", "pccl_model_rec",
     "pccl_choose_algorithm", "pccl_model_two_level", "pccl_status_string", "pccl_check_device_range",
     "pccl_reduce_scatter_local_unpacked_batched", "pccl_reduce_scatter_local_static", "pccl_diag_reload_env", "pccl_build_id",
-    "pccl_phase2_reassemble_local",
+    "pccl_phase2_reassemble_local", "pccl_accumulate_batched",
 )
 PCCL_ALGO_RING, PCCL_ALGO_REC = 0, 1
 _NO_STATUS = ("pccl_status_string", "pccl_model_ring", "pccl_model_rec", "pccl_model_two_level",
@@ -41,6 +41,10 @@ class pccl_bucket_t(ctypes.Structure):
     _fields_ = [("shard", ctypes.c_void_p), ("partial", ctypes.c_void_p),
                 ("intra_base", ctypes.c_void_p), ("intra_stride_bytes", ctypes.c_size_t),
                 ("chunk_count", ctypes.c_size_t)]
+
+
+class pccl_accumulate_pair_t(ctypes.Structure):
+    _fields_ = [("acc", ctypes.c_void_p), ("recv", ctypes.c_void_p), ("count", ctypes.c_size_t)]
 
 
 class pccl_permute_bucket_t(ctypes.Structure):
@@ -78,6 +82,7 @@ def lib():
         L.pccl_reduce_scatter_local_batched.argtypes = [vp, vp, i, i, i, i, i, vp]
         L.pccl_reduce_scatter_local_unpacked_batched.argtypes = [vp, vp, i, i, i, i, i, i, vp]
         L.pccl_accumulate.argtypes = [vp, vp, sz, i, i, vp]
+        L.pccl_accumulate_batched.argtypes = [vp, vp, i, i, i, vp]
         L.pccl_allgather_reassemble_batched.argtypes = [vp, vp, i, i, i, vp]
         L.pccl_hier_pack_batched.argtypes = [vp, vp, i, i, i, vp]
         L.pccl_reduce_scatter_local_unpacked.argtypes = [vp, vp, vp, sz, vp, vp, i, i, i, i, sz, i, i, vp]
@@ -364,6 +369,35 @@ def pccl_accumulate(acc, recv, stream=None):
     _check(lib().pccl_accumulate(_dev(acc, "acc"), _dev(recv, "recv"), acc.numel(), dtype_code(acc.dtype),
                                  PCCL_SUM, _stream(stream)), "pccl_accumulate")
     return acc
+
+
+class AccumulateTable:
+    """Descriptor table of a batch of acc += recv steps: host array + device copy, built once and reused."""
+
+    def __init__(self, pairs):
+        """pairs: list of (acc, recv) contiguous tensors of one dtype, equal sizes within a pair."""
+        n = len(pairs)
+        self.host = (pccl_accumulate_pair_t * max(n, 1))()
+        self.npairs = n
+        self.dtype = pairs[0][0].dtype if n else torch.float32
+        for k, (acc, recv) in enumerate(pairs):
+            if acc.dtype != self.dtype or recv.dtype != self.dtype or acc.numel() != recv.numel() or \
+                    not acc.is_contiguous() or not recv.is_contiguous():
+                raise ValueError("AccumulateTable: acc and recv must be contiguous, of one dtype, equal in size")
+            c = acc.numel()
+            self.host[k] = pccl_accumulate_pair_t(_dev(acc, "acc") if c else None, _dev(recv, "recv") if c else None, c)
+        raw = bytes(self.host)[: n * ctypes.sizeof(pccl_accumulate_pair_t)]
+        dev = pairs[0][0].device if n else "cuda"
+        self.device = torch.frombuffer(bytearray(raw), dtype=torch.uint8).to(dev) if n else None
+        self._keep = pairs  # the table holds raw pointers: keep the tensors alive
+
+
+def pccl_accumulate_batched(table, stream=None):
+    """Every pair of an AccumulateTable: acc += recv, one launch."""
+    if table.npairs == 0:
+        return
+    _check(lib().pccl_accumulate_batched(table.device.data_ptr(), ctypes.addressof(table.host), table.npairs,
+                                         dtype_code(table.dtype), PCCL_SUM, _stream(stream)), "pccl_accumulate_batched")
 
 
 def pccl_ring_reduce_scatter_local(msg, recv, rank, stream=None):

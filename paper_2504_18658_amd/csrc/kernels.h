@@ -106,6 +106,18 @@ hipError_t launch_phase2_reassemble(const ReduceProblem& p, const PermuteProblem
 // acc[e] = round_io(acc[e] + recv[e]) for e < count, in place (the two ranges are disjoint).
 hipError_t launch_accumulate(void* acc, const void* recv, size_t count, int dt, hipStream_t st);
 
+// Every step of one rank's ring / recursive-halving reduce-scatter in one launch (the layouts
+// of pccl_ring_reduce_scatter_local / pccl_halving_reduce_scatter_local): hipErrorInvalidValue
+// when the steps (ring) or half the ranks (halving) exceed 65535, the caller then launches step
+// by step.
+hipError_t launch_ring_steps(void* msg, const void* recv_base, size_t recv_stride, size_t count, int nranks, int rank,
+                             int dt, hipStream_t st);
+hipError_t launch_halving_steps(void* msg, const void* recv, size_t count, int nranks, int rank, int dt,
+                                hipStream_t st);
+// npairs independent acc += recv steps in one launch; h_pairs is the host copy used to size the grid.
+hipError_t launch_accumulate_batched(const pccl_accumulate_pair_t* d_pairs, const pccl_accumulate_pair_t* h_pairs,
+                                     int npairs, int dt, hipStream_t st);
+
 // Batched two-level reduce-scatter share; h_buckets is the host copy used to size the grid.
 // Phase 2 divides by `divisor` when it is not 0 (op = average).  my_gpu < 0: a bucket's
 // intra_base holds pre-shuffled pieces; my_gpu >= 0: it holds `gpus` rank-order messages

@@ -18,7 +18,7 @@ struct Knobs {
   long long permute_skew;  // PCCL_PERMUTE_SKEW: -1 chooser, else tiles
   size_t grid_x_limit;     // PCCL_GRID_X_LIMIT: 0 = the hardware's, else work-items in x
   int check_pointers;      // PCCL_CHECK_POINTERS: 0 off, 1 ranges, 2 also device-resident tables
-  int fused_steps;         // PCCL_STEP_LAUNCHES: 0 one launch for a whole replay, 1 one launch per step
+  int step_launches;         // PCCL_STEP_LAUNCHES: 0 one launch for a whole replay, 1 one launch per step
 };
 
 const Knobs& knobs();

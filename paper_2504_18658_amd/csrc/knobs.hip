@@ -42,8 +42,8 @@ Knobs read_env() {
   }
   k.check_pointers = 0;
   if ((v = std::getenv("PCCL_CHECK_POINTERS")) && v[0] != '\0' && v[0] != '0') k.check_pointers = v[0] == '2' ? 2 : 1;
-  k.fused_steps = 0;
-  if ((v = std::getenv("PCCL_STEP_LAUNCHES"))) k.fused_steps = v[0] == '1';
+  k.step_launches = 0;
+  if ((v = std::getenv("PCCL_STEP_LAUNCHES"))) k.step_launches = v[0] == '1';
   return k;
 }
 

@@ -690,6 +690,45 @@ pccl_status_t pccl_accumulate(void* acc, const void* recv, size_t count, pccl_dt
   return e == hipErrorInvalidValue ? PCCL_ERR_INVALID : from_hip(e);
 }
 
+pccl_status_t pccl_accumulate_batched(const pccl_accumulate_pair_t* d_pairs, const pccl_accumulate_pair_t* h_pairs,
+                                      int npairs, pccl_dtype_t io_dt, pccl_op_t op, pccl_stream_t stream) {
+  if (npairs < 0 || npairs > PCCL_MAX_BUCKETS) return PCCL_ERR_INVALID;
+  if (npairs > 0 && (d_pairs == nullptr || h_pairs == nullptr)) return PCCL_ERR_NULL;
+  if (pccl_status_t s = check_common(io_dt, io_dt, op)) return s;
+  if (op != PCCL_SUM) return PCCL_ERR_UNSUPPORTED;
+  const size_t es = esize(io_dt);
+  bool any = false;
+  for (int b = 0; b < npairs; ++b) {
+    const pccl_accumulate_pair_t& k = h_pairs[b];
+    if (k.count == 0) continue;  // an empty pair is skipped whatever its pointers are
+    if (k.acc == nullptr || k.recv == nullptr) return PCCL_ERR_NULL;
+    size_t bytes;
+    if (!mul_ok(k.count, es, &bytes)) return PCCL_ERR_INVALID;
+    if (!elem_aligned(k.acc, es) || !elem_aligned(k.recv, es)) return PCCL_ERR_INVALID;
+    if (overlaps(k.acc, bytes, k.recv, bytes)) return PCCL_ERR_OVERLAP;
+    for (int a = 0; a < b; ++a) {  // two pairs that update the same elements would race
+      const pccl_accumulate_pair_t& j = h_pairs[a];
+      if (j.count != 0 && (overlaps(k.acc, bytes, j.acc, j.count * es) || overlaps(k.acc, bytes, j.recv, j.count * es) ||
+                           overlaps(k.recv, bytes, j.acc, j.count * es)))
+        return PCCL_ERR_OVERLAP;
+    }
+    any = true;
+  }
+  if (!any) return PCCL_OK;
+  AddressChecks ck(stream);
+  if (ck.on()) {
+    ck.descriptors(d_pairs, h_pairs, (size_t)npairs * sizeof(pccl_accumulate_pair_t));
+    for (int b = 0; b < npairs; ++b) {
+      ck.range(h_pairs[b].acc, h_pairs[b].count * es);
+      ck.range(h_pairs[b].recv, h_pairs[b].count * es);
+    }
+    if (ck.status != PCCL_OK) return ck.status;
+  }
+  const hipError_t e = pccl::launch_accumulate_batched(d_pairs, h_pairs, npairs, io_dt,
+                                                       reinterpret_cast<hipStream_t>(stream));
+  return e == hipErrorInvalidValue ? PCCL_ERR_INVALID : from_hip(e);
+}
+
 pccl_status_t pccl_ring_reduce_scatter_local(void* msg, const void* recv_base,
                                              size_t recv_stride_bytes, int nranks, int rank,
                                              size_t chunk_count, pccl_dtype_t io_dt,
@@ -718,6 +757,13 @@ pccl_status_t pccl_ring_reduce_scatter_local(void* msg, const void* recv_base,
     if (ck.status != PCCL_OK) return ck.status;
   }
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  // The steps touch distinct chunks, so one launch takes them all; step by step only on request
+  // (A/B runs) or beyond the launch's 65535 rows.
+  if (steps > 0 && steps <= 65535 && !pccl::knobs().step_launches) {
+    const hipError_t e = pccl::launch_ring_steps(msg, recv_base, steps > 1 ? recv_stride_bytes : 0, chunk_count,
+                                                 nranks, rank, io_dt, st);
+    return e == hipErrorInvalidValue ? PCCL_ERR_INVALID : from_hip(e);
+  }
   for (int s = 0; s < steps; ++s) {
     // rank r forwards chunk r-1 first; what arrives at step s is chunk r-2-s, further reduced
     const int c = ((rank - 2 - s) % nranks + nranks) % nranks;
@@ -752,6 +798,12 @@ pccl_status_t pccl_halving_reduce_scatter_local(void* msg, const void* recv, int
     if (ck.status != PCCL_OK) return ck.status;
   }
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  // The kept ranges are nested: one launch reads every chunk of the first kept half once, applies
+  // the steps it takes part in in registers and writes it once.  Step by step only on request.
+  if (nranks > 1 && (nranks >> 1) <= 65535 && !pccl::knobs().step_launches) {
+    const hipError_t e = pccl::launch_halving_steps(msg, recv, chunk_count, nranks, rank, io_dt, st);
+    return e == hipErrorInvalidValue ? PCCL_ERR_INVALID : from_hip(e);
+  }
   size_t lo = 0, len = (size_t)nranks, recv_off = 0;  // active chunk range, received chunks so far
   for (int dist = nranks >> 1; dist >= 1; dist >>= 1) {
     len >>= 1;

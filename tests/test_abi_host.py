@@ -414,3 +414,31 @@ def test_phase2_reassemble_rejects_bad_arguments():
     assert call(dst=8 * A + 8188) == pccl.PCCL_ERR_OVERLAP
     assert call(c=0) == pccl.PCCL_OK
     assert call(op=1, n=1 << 13, m=1 << 12, my_n=0, c=0) == pccl.PCCL_ERR_INVALID   # average: 2^25 ranks
+
+
+def test_accumulate_batched_rejects_bad_arguments():
+    f = pccl.lib().pccl_accumulate_batched
+    T = pccl.pccl_accumulate_pair_t
+    good = (T * 3)(T(A, 8 * A, 1024), T(2 * A, 16 * A, 100), T(None, None, 0))
+    h = ctypes.addressof(good)
+    assert f(None, h, 3, 0, 0, None) == pccl.PCCL_ERR_NULL
+    assert f(A, None, 3, 0, 0, None) == pccl.PCCL_ERR_NULL
+    assert f(A, h, -1, 0, 0, None) == pccl.PCCL_ERR_INVALID
+    assert f(A, h, pccl.PCCL_MAX_BUCKETS + 1, 0, 0, None) == pccl.PCCL_ERR_INVALID
+    assert f(A, h, 3, 7, 0, None) == pccl.PCCL_ERR_UNSUPPORTED
+    assert f(A, h, 3, 0, 1, None) == pccl.PCCL_ERR_UNSUPPORTED            # a step adds; no average
+    assert f(None, None, 0, 0, 0, None) == pccl.PCCL_OK
+    empty = (T * 2)(T(None, None, 0), T(A, None, 0))
+    assert f(A, ctypes.addressof(empty), 2, 0, 0, None) == pccl.PCCL_OK    # only empty pairs: nothing to launch
+    for bad, want in ((T(None, 8 * A, 4), pccl.PCCL_ERR_NULL), (T(A, None, 4), pccl.PCCL_ERR_NULL),
+                      (T(A + 2, 8 * A, 4), pccl.PCCL_ERR_INVALID), (T(A, 8 * A, 1 << 62), pccl.PCCL_ERR_INVALID),
+                      (T(A, A + 8, 4), pccl.PCCL_ERR_OVERLAP)):
+        one = (T * 1)(bad)
+        assert f(A, ctypes.addressof(one), 1, 0, 0, None) == want
+    # two pairs that update the same elements, or one that reads what another updates
+    two = (T * 2)(T(A, 8 * A, 1024), T(A + 4092, 16 * A, 8))
+    assert f(A, ctypes.addressof(two), 2, 0, 0, None) == pccl.PCCL_ERR_OVERLAP
+    two = (T * 2)(T(A, 8 * A, 1024), T(2 * A, A + 100, 8))
+    assert f(A, ctypes.addressof(two), 2, 0, 0, None) == pccl.PCCL_ERR_OVERLAP
+    assert ctypes.sizeof(T) == 24
+

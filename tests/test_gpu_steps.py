@@ -80,10 +80,19 @@ def test_accumulate_special_values():
         assert same_bits(got[ok].astype(np.float32), want[ok].astype(np.float32))
 
 
+@pytest.fixture(params=["one launch", "launch per step"])
+def launches(request, monkeypatch):
+    """Both forms of the replays: every step in one launch (the default) and one launch per step."""
+    if request.param == "launch per step":
+        monkeypatch.setenv("PCCL_STEP_LAUNCHES", "1")
+        pccl.diag_reload_env()
+    return request.param
+
+
 @pytest.mark.parametrize("dtype", [F32, BF16])
-@pytest.mark.parametrize("p,chunk", [(2, 5), (3, 1000), (8, 4096 + 8), (16, 333), (1, 64)])
-def test_ring_local_matches_oracle(dtype, p, chunk):
-    print("case", dtype, p, chunk, flush=True)
+@pytest.mark.parametrize("p,chunk", [(2, 5), (3, 1000), (8, 4096 + 8), (16, 333), (1, 64), (7, 1029), (33, 520)])
+def test_ring_local_matches_oracle(dtype, p, chunk, launches):
+    print("case", dtype, p, chunk, launches, flush=True)
     for rank in sorted({0, p // 2, p - 1}):
         msg_h = W.uniform_pm1(p * chunk, 31 + p, "cpu", dtype).view(p, chunk)
         recv_h = W.uniform_pm1(max(p - 1, 1) * chunk, 32 + p, "cpu", dtype).view(max(p - 1, 1), chunk)
@@ -98,10 +107,10 @@ def test_ring_local_matches_oracle(dtype, p, chunk):
 
 
 @pytest.mark.parametrize("dtype", [F32, BF16])
-@pytest.mark.parametrize("p,chunk", [(1, 10), (2, 7), (4, 1000), (16, 2048 + 8), (64, 65)])
-def test_halving_local_matches_oracle(dtype, p, chunk):
-    print("case", dtype, p, chunk, flush=True)
-    for rank in sorted({0, p // 3, p - 1}):
+@pytest.mark.parametrize("p,chunk", [(1, 10), (2, 7), (4, 1000), (16, 2048 + 8), (64, 65), (8, 1031), (256, 24)])
+def test_halving_local_matches_oracle(dtype, p, chunk, launches):
+    print("case", dtype, p, chunk, launches, flush=True)
+    for rank in sorted({0, p // 3, p - 1, p // 2}):
         msg_h = W.uniform_pm1(p * chunk, 41 + p, "cpu", dtype).view(p, chunk)
         recv_h = W.uniform_pm1(max(p - 1, 1) * chunk, 42 + p, "cpu", dtype)
         msg = _guarded_copy(msg_h)
@@ -119,6 +128,62 @@ def test_halving_local_matches_oracle(dtype, p, chunk):
         assert same_bits(to_np(msg.view).reshape(p, chunk), want), first_diff(to_np(msg.view), want)
         msg.check()
         recv.check()
+
+
+@pytest.mark.parametrize("dtype", [F32, BF16])
+@pytest.mark.parametrize("off", [1, 3])
+def test_ring_and_halving_unaligned_buffers(dtype, off):
+    """Buffers that start off a 16-byte boundary take the element-wise capable paths: same bits."""
+    p, chunk = 8, 777
+    msg_h = W.uniform_pm1(p * chunk, 61, "cpu", dtype).view(p, chunk)
+    recv_h = W.uniform_pm1((p - 1) * chunk, 62, "cpu", dtype).view(p - 1, chunk)
+    for rank in (0, 5):
+        msg = _guarded_copy(msg_h, off)
+        recv = _guarded_copy(recv_h, off + 1)
+        pccl.pccl_ring_reduce_scatter_local(msg.view.view(p, chunk), recv.view.view(p - 1, chunk), rank)
+        _sync()
+        want = oracle.ring_rs_local(to_np(msg_h), [to_np(recv_h[s]) for s in range(p - 1)], rank)
+        assert same_bits(to_np(msg.view).reshape(p, chunk), want), first_diff(to_np(msg.view), want)
+        msg.check()
+        msg = _guarded_copy(msg_h, off)
+        pccl.pccl_halving_reduce_scatter_local(msg.view.view(p, chunk), recv.view, rank)
+        _sync()
+        flat = recv_h.reshape(-1)
+        halves = [to_np(flat[0:4 * chunk]), to_np(flat[4 * chunk:6 * chunk]), to_np(flat[6 * chunk:7 * chunk])]
+        want = oracle.halving_rs_local(to_np(msg_h), halves, rank)
+        assert same_bits(to_np(msg.view).reshape(p, chunk), want), first_diff(to_np(msg.view), want)
+        msg.check()
+        recv.check()
+
+
+@pytest.mark.parametrize("dtype", [F32, BF16])
+def test_accumulate_batched_matches_oracle(dtype):
+    """Pairs of different sizes (empty, ragged, unaligned, several blocks) in one launch, each against
+    the oracle's single step; two pairs may share a received buffer."""
+    counts = [1000, 0, 7, 4096 * 5 + 3, 8, 1 << 18, 129]
+    offs = [0, 0, 1, 0, 3, 0, 2]
+    accs, recvs, hosts = [], [], []
+    for k, (c, o) in enumerate(zip(counts, offs)):
+        a = W.normal(c, 300 + k, 1.0, "cpu", dtype)
+        r = W.normal(c, 400 + k, 1e-2, "cpu", dtype)
+        accs.append(_guarded_copy(a, o))
+        recvs.append(_guarded_copy(r, o))
+        hosts.append((a, r))
+    # an eighth pair that reads pair 0's received buffer again
+    a = W.normal(counts[0], 500, 1.0, "cpu", dtype)
+    accs.append(_guarded_copy(a))
+    recvs.append(recvs[0])
+    hosts.append((a, hosts[0][1]))
+    table = pccl.AccumulateTable([(x.view, y.view) for x, y in zip(accs, recvs)])
+    pccl.pccl_accumulate_batched(table)
+    _sync()
+    for k, (a, r) in enumerate(hosts):
+        want = oracle.accumulate(to_np(a), to_np(r))
+        assert same_bits(to_np(accs[k].view), want), (k, first_diff(to_np(accs[k].view), want))
+        assert same_bits(to_np(recvs[k].view), to_np(r))
+        accs[k].check()
+        recvs[k].check()
+    pccl.pccl_accumulate_batched(pccl.AccumulateTable([]))      # an empty batch launches nothing
 
 
 def test_ring_and_halving_full_size_inter_node_phase():
