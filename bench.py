@@ -10,10 +10,14 @@ A step is one GPU's share of a two-level all-reduce of one 256 MB bf16 message a
 Inputs are seeded synthetic tensors already resident in HBM; every step works on the next of
 several disjoint buffer sets so that the last-level cache cannot serve a re-run.
 
-Prints ONE JSON line.  `value` = algorithmic bytes of a step / wall time of a step.
-`roofline` is for the dominant kernel (the chunk transpose), timed with events on the launch
-stream inside the timed region (on every 8th step: an event pair stalls the stream for about
-3 us, which would otherwise add 13 us to every 220 us step).  `cpu_baseline` times the CPU oracle on the same workload.
+Prints ONE JSON line.  `value` = algorithmic bytes of a step / wall time of a step (no event is
+recorded inside the timed steps).  `roofline` is for the dominant kernel (the chunk transpose):
+after the timed steps, 24 pack and 24 reassemble launches run back to back over the rotating
+buffer sets between ONE pair of HIP events on the launch stream, whatever --steps is; `calls`
+holds the same measurement for each of the three calls, and next to it the figure with every
+call bracketed by its own event pair (an event record stalls the stream for about 3 us, so that
+figure is the larger one).  `size_sweep` repeats the kernels at 64 / 128 / 256 MB messages (the
+metric's range; 16 MB - 1 GB with --sweep).  `cpu_baseline` times the CPU oracle on the same workload.
 """
 import argparse
 import json
@@ -32,10 +36,11 @@ import paper_2504_18658_amd as pccl  # noqa: E402
 from paper_2504_18658_amd import workloads as W  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
-# HBM bytes per 256 MB k_permute launch from the two rocprofv3 --pmc runs summarised in
-# profiles/k_permute_256MB_16x8.txt: FETCH_SIZE 131086.6 KiB (x 2.000, the factor a plain
-# 256 MiB copy calibrates) + WRITE_SIZE 262203.2 KiB (x 1.000).
-PROFILED_PERMUTE_TRAFFIC_BYTES = int((131091.8 * 2.000 + 262188.0 * 1.000) * 1024)
+# HBM bytes of one 256 MB k_permute launch, from profiles/k_permute_256MB_16x8.txt (two rocprofv3 --pmc
+# runs of this file, FETCH_SIZE and WRITE_SIZE in KiB per dispatch, each scaled by what the same counter
+# reads for a plain 256 MiB copy: FETCH_SIZE x 2.000, WRITE_SIZE x 1.000).  A profiler figure, not measured here.
+PROFILED_PERMUTE_FETCH_KIB, PROFILED_PERMUTE_WRITE_KIB = 131086.6, 262203.2
+PROFILED_PERMUTE_TRAFFIC_BYTES = int((PROFILED_PERMUTE_FETCH_KIB * 2.000 + PROFILED_PERMUTE_WRITE_KIB * 1.000) * 1024)
 MB = 1 << 20
 
 
@@ -86,6 +91,17 @@ class AllReduceShare:
         if events is not None:
             events[3].record()
 
+    def call(self, name):
+        """One of the three calls of a step, as a function."""
+        w = self.w
+        return {
+            "pccl_hier_pack": lambda: pccl.pccl_hier_pack(self.packed, self.msg, w.nodes, w.gpus),
+            "pccl_reduce_scatter_local": lambda: pccl.pccl_reduce_scatter_local(
+                self.shard, self.partial, self.x, d_inter=self.d_inter, my_node=self.my_node),
+            "pccl_allgather_reassemble": lambda: pccl.pccl_allgather_reassemble(
+                self.out, src=self.gathered, nodes=w.nodes, gpus_per_node=w.gpus),
+        }[name]
+
     def oracle_step(self, host, nthreads=1):
         import oracle
         w = self.w
@@ -125,6 +141,22 @@ def time_calls(fn_list, trials=10, warm=3):
     b.record()
     torch.cuda.synchronize()
     return float(np.mean(ms)), float(np.min(ms)), float(np.std(ms)), a.elapsed_time(b) / trials
+
+
+def back_to_back(fn_list, launches=24, warm=4):
+    """Microseconds per call of `launches` calls fn_list[k % len]() enqueued back to back between ONE pair of
+    events on the current stream (no event between the launches)."""
+    for k in range(warm):
+        fn_list[k % len(fn_list)]()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    torch.cuda._sleep(2_000_000)     # the GPU is busy while the host enqueues: the launches then run gap-free
+    a.record()
+    for k in range(launches):
+        fn_list[k % len(fn_list)]()
+    b.record()
+    torch.cuda.synchronize()
+    return a.elapsed_time(b) * 1e3 / launches
 
 
 def other_workloads(dev):
@@ -252,17 +284,18 @@ def other_workloads(dev):
              W.draw(w, (p8 - 1) * c8, dev, seed_offset=70 + k).view(p8 - 1, c8)) for k in range(4)]
     entry("step_ring_rs_local_8_ranks_bf16_256MB", 3 * (p8 - 1) * c8 * 2,
           *time_calls([lambda s=s: pccl.pccl_ring_reduce_scatter_local(s[0], s[1], 3) for s in sets]),
-          launches_per_call=p8 - 1)
+          launches_per_call=1)
     del sets
     sets = [(W.draw(w, w.nodes * w.chunk, dev, seed_offset=80 + k).view(w.nodes, w.chunk),
              W.draw(w, (w.nodes - 1) * w.chunk, dev, seed_offset=90 + k).view(w.nodes - 1, w.chunk))
             for k in range(8)]
     entry("step_ring_rs_local_16_nodes_bf16_32MB", 3 * (w.nodes - 1) * w.chunk * 2,
           *time_calls([lambda s=s: pccl.pccl_ring_reduce_scatter_local(s[0], s[1], 5) for s in sets]),
-          launches_per_call=w.nodes - 1)
-    entry("step_halving_rs_local_16_nodes_bf16_32MB", 3 * (w.nodes - 1) * w.chunk * 2,
+          launches_per_call=1)
+    # one launch: the first kept half is read and written once (2 * p/2 chunks), every received chunk read once (p - 1)
+    entry("step_halving_rs_local_16_nodes_bf16_32MB", (2 * w.nodes - 1) * w.chunk * 2,
           *time_calls([lambda s=s: pccl.pccl_halving_reduce_scatter_local(s[0], s[1].view(-1), 5) for s in sets]),
-          launches_per_call=4)
+          launches_per_call=1, bytes_if_launched_per_step=3 * (w.nodes - 1) * w.chunk * 2)
     del sets
     # cfg5: 40 ZeRO-3-shaped buckets in one batched call
     w = W.cfg5()
@@ -307,9 +340,12 @@ def other_workloads(dev):
 
 
 def fused_leg(dev, steps, warmup, nsets=4, my_node=5, my_gpu=3):
-    """The same all-reduce share without the pre-shuffle: phase 1 reads the eight node-mates'
-    rank-order 256 MB messages through the node stride (pccl_reduce_scatter_local_unpacked), then
-    pccl_allgather_reassemble.  Saves the 512 MB of traffic of pccl_hier_pack."""
+    """The same all-reduce share in two launches instead of four: phase 1 reads the eight node-mates'
+    rank-order 256 MB messages through the node stride (pccl_reduce_scatter_local_unpacked with no shard:
+    no pccl_hier_pack pass, 512 MB less traffic), then pccl_phase2_reassemble_local sums the inter-node
+    phase straight into the rank's own chunk of the all-gather result while the other chunks are shuffled
+    in (no separate phase-2 launch, no copy of the shard).  Timed next to the three-launch form
+    (pccl_reduce_scatter_local_unpacked + pccl_allgather_reassemble)."""
     w = W.cfg3()
     n = w.ranks * w.chunk
     sets = []
@@ -323,38 +359,57 @@ def fused_leg(dev, steps, warmup, nsets=4, my_node=5, my_gpu=3):
                          gathered=W.draw(w, n, dev, seed_offset=220 + k),
                          out=torch.empty(n, dtype=w.dtype, device=dev)))
 
+    def phase1(s):
+        pccl.pccl_reduce_scatter_local_unpacked(None, s["partial"], msgs=s["msgs"], nodes=w.nodes,
+                                                gpus_per_node=w.gpus, my_node=my_node, my_gpu=my_gpu)
+
+    def tail(s):
+        pccl.pccl_phase2_reassemble_local(s["out"], s["partial"], d_inter=s["d_inter"], src=s["gathered"],
+                                          nodes=w.nodes, gpus_per_node=w.gpus, my_node=my_node, my_gpu=my_gpu)
+
     def run(s):
+        phase1(s)
+        tail(s)
+
+    def run_three_launches(s):
         pccl.pccl_reduce_scatter_local_unpacked(s["shard"], s["partial"], msgs=s["msgs"], d_inter=s["d_inter"],
                                                 nodes=w.nodes, gpus_per_node=w.gpus, my_node=my_node, my_gpu=my_gpu)
         pccl.pccl_allgather_reassemble(s["out"], src=s["gathered"], nodes=w.nodes, gpus_per_node=w.gpus)
 
-    for k in range(warmup):
-        run(sets[k % nsets])
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for k in range(steps):
-        run(sets[k % nsets])
-    torch.cuda.synchronize()
-    ms = (time.perf_counter() - t0) * 1e3 / steps
+    def wall(fn):
+        for k in range(warmup):
+            fn(sets[k % nsets])
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for k in range(steps):
+            fn(sets[k % nsets])
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / steps
+
+    ms, ms3 = wall(run), wall(run_three_launches)
     e = w.esize
-    nbytes = (w.gpus + 1) * w.nodes * w.chunk * e + (w.nodes + 1) * w.chunk * e + 2 * n * e
-    rs_ms = time_calls([lambda s=s: pccl.pccl_reduce_scatter_local_unpacked(
-        s["shard"], s["partial"], msgs=s["msgs"], d_inter=s["d_inter"], nodes=w.nodes, gpus_per_node=w.gpus,
-        my_node=my_node, my_gpu=my_gpu) for s in sets])
-    return dict(what="pccl_reduce_scatter_local_unpacked (no pccl_hier_pack pass) + pccl_allgather_reassemble",
-                ms_per_step=round(ms, 4), algorithmic_bytes_per_step=nbytes,
+    p1_bytes = (w.gpus + 1) * w.nodes * w.chunk * e
+    tail_bytes = (w.nodes + 1) * w.chunk * e + 2 * (n - w.chunk) * e     # the own chunk is summed, not copied
+    nbytes = p1_bytes + tail_bytes
+    p1_us = back_to_back([lambda s=s: phase1(s) for s in sets])
+    tail_us = back_to_back([lambda s=s: tail(s) for s in sets])
+    return dict(what="pccl_reduce_scatter_local_unpacked (phase 1 only, no pccl_hier_pack pass) + "
+                     "pccl_phase2_reassemble_local (inter-node phase and all-gather shuffle in one launch)",
+                launches_per_step=2, ms_per_step=round(ms, 4), algorithmic_bytes_per_step=nbytes,
                 GBps=round(nbytes / (ms * 1e-3) / 1e9, 1),
-                unpacked_reduce_scatter_us=round(rs_ms[0] * 1e3, 2),
-                unpacked_reduce_scatter_GBps=round((nbytes - 2 * n * e) / (rs_ms[0] * 1e-3) / 1e9, 1),
-                unpacked_reduce_scatter_back_to_back_us=round(rs_ms[3] * 1e3, 2))
+                phase1_from_rank_order_messages_us=round(p1_us, 2),
+                phase1_from_rank_order_messages_GBps=round(p1_bytes / (p1_us * 1e-6) / 1e9, 1),
+                phase2_reassemble_us=round(tail_us, 2), phase2_reassemble_GBps=round(tail_bytes / (tail_us * 1e-6) / 1e9, 1),
+                three_launch_form_ms_per_step=round(ms3, 4))
 
 
-def size_sweep(dev):
-    """Message sizes of the paper's range (16 MB - 1 GB, Section V-A) through the three kernels:
-    chunk transpose (16 x 8 ranks), 8-source bf16 reduce (phase 1) and the two-source step."""
+def size_sweep(dev, sizes_mb=(64, 128, 256)):
+    """Message sizes through the three kernels: chunk transpose (16 x 8 ranks), 8-source bf16 reduce
+    (phase 1) and the two-source step; back-to-back launches over rotating buffer sets.  By default the
+    metric's range (64 - 256 MB); the paper's whole range (16 MB - 1 GB, Section V-A) with --sweep."""
     w = W.cfg3()
     out = []
-    for mb in (16, 32, 64, 128, 256, 512, 1024):
+    for mb in sizes_mb:
         m = mb * MB
         n = m // 2                                              # bf16 elements of the message
         nsets = max(2, min(8, (1024 * MB) // m + 1))             # rotate over at least ~1 GB of inputs
@@ -363,15 +418,18 @@ def size_sweep(dev):
         t = time_calls([lambda s=s: pccl.pccl_hier_pack(s[0], s[1], w.nodes, w.gpus) for s in sets], trials=2 * nsets)
         row["hier_pack_us"] = round(t[3] * 1e3, 2)
         row["hier_pack_GBps"] = round(2 * m / (t[3] * 1e-3) / 1e9, 1)
+        row["hier_pack_frac_of_peak"] = round(2 * m / (t[3] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
         # phase 1 of the share of this message: 8 pieces of m/8 -> m/8
         t = time_calls([lambda s=s: pccl.pccl_local_reduce(s[0][: n // 8], s[1].view(8, n // 8)) for s in sets],
                        trials=2 * nsets)
         row["reduce8_us"] = round(t[3] * 1e3, 2)
         row["reduce8_GBps"] = round((m + m // 8) / (t[3] * 1e-3) / 1e9, 1)
+        row["reduce8_frac_of_peak"] = round((m + m // 8) / (t[3] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
         # first halving step on this message: m/2 += m/2
         t = time_calls([lambda s=s: pccl.pccl_accumulate(s[0][: n // 2], s[1][: n // 2]) for s in sets], trials=2 * nsets)
         row["accumulate_us"] = round(t[3] * 1e3, 2)
         row["accumulate_GBps"] = round(3 * (m // 2) / (t[3] * 1e-3) / 1e9, 1)
+        row["accumulate_frac_of_peak"] = round(3 * (m // 2) / (t[3] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
         out.append(row)
         del sets
         torch.cuda.empty_cache()
@@ -425,13 +483,12 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--sets", type=int, default=4, help="disjoint buffer sets rotated over (cold cache)")
-    ap.add_argument("--no-kernel-events", action="store_true", help="do not record per-call events")
-    ap.add_argument("--events-every", type=int, default=8,
-                    help="bracket the calls of every n-th timed step with events (an event pair costs the "
-                         "stream about 3 us, 13 us per step when every call of every step is bracketed)")
+    ap.add_argument("--kernel-launches", type=int, default=24,
+                    help="back-to-back launches per call in the kernel timing loops after the timed steps")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-others", action="store_true", help="skip the other four configurations")
-    ap.add_argument("--sweep", action="store_true", help="also time the kernels over 16 MB - 1 GB messages and 4 - 256 nodes")
+    ap.add_argument("--sweep", action="store_true", help="time the kernels over 16 MB - 1 GB messages and 4 - 256 nodes "
+                                                         "(the default run covers 64 - 256 MB only)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run plain 256 MB device-to-device copies (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -454,48 +511,47 @@ def main():
     for k in range(args.warmup):
         sets[k % len(sets)].run()
     torch.cuda.synchronize()
-
-    use_ev = not args.no_kernel_events
-    every = max(1, args.events_every)
-    # sampled steps: every `every`-th, shifted by one set per sample so that all buffer sets are sampled
-    sampled = [k for k in range(args.steps) if k % every == (k // every) % min(every, len(sets))] if use_ev else []
-    events = {k: [torch.cuda.Event(enable_timing=True) for _ in range(4)] for k in sampled}
-    torch.cuda.synchronize()
     t0 = time.perf_counter()
     for k in range(args.steps):
-        sets[k % len(sets)].run(events.get(k))
+        sets[k % len(sets)].run()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     value = step_bytes / (ms_per_step * 1e-3) / 1e9
 
+    # kernel timing loops, independent of --steps: every call back to back between one pair of events on the
+    # launch stream; then a few steps with every call bracketed by its own pair (the figure that includes the stall)
+    names = ["pccl_hier_pack", "pccl_reduce_scatter_local", "pccl_allgather_reassemble"]
+    nl = max(20, args.kernel_launches)
     calls = {}
-    roofline = None
-    if use_ev:
-        names = ["pccl_hier_pack", "pccl_reduce_scatter_local", "pccl_allgather_reassemble"]
-        dur = {n: [] for n in names}
-        for ev in events.values():
-            for j, n in enumerate(names):
-                dur[n].append(ev[j].elapsed_time(ev[j + 1]))
-        for n in names:
-            m = float(np.mean(dur[n]))
-            calls[n] = dict(bytes=per_call[n], mean_us=round(m * 1e3, 2), min_us=round(float(np.min(dur[n])) * 1e3, 2),
-                            std_us=round(float(np.std(dur[n])) * 1e3, 2),
-                            GBps=round(per_call[n] / (m * 1e-3) / 1e9, 1))
-        perm = dur["pccl_hier_pack"] + dur["pccl_allgather_reassemble"]
-        avg_ms = float(np.mean(perm))
-        achieved = per_call["pccl_hier_pack"] / (avg_ms * 1e-3) / 1e9
-        roofline = dict(kernel="k_permute (pccl_hier_pack / pccl_allgather_reassemble, 256 MB each)",
-                        bound="hbm", achieved=round(achieved, 1), peak=HBM_PEAK_GBS, unit="GB/s",
-                        frac=round(achieved / HBM_PEAK_GBS, 4), traffic=PROFILED_PERMUTE_TRAFFIC_BYTES,
-                        algorithmic_bytes_per_launch=per_call["pccl_hier_pack"],
-                        avg_launch_us=round(avg_ms * 1e3, 2), launches=len(perm))
-        red = dur["pccl_reduce_scatter_local"]
-        roofline["reduce"] = dict(
-            kernel="k_reduce phase 1 (8 x 32 MB) + phase 2 (16 x 2 MB), one call", bound="hbm",
-            achieved=round(per_call["pccl_reduce_scatter_local"] / (float(np.mean(red)) * 1e-3) / 1e9, 1),
-            peak=HBM_PEAK_GBS, unit="GB/s",
-            frac=round(per_call["pccl_reduce_scatter_local"] / (float(np.mean(red)) * 1e-3) / 1e9 / HBM_PEAK_GBS, 4))
+    for n in names:
+        us = back_to_back([s.call(n) for s in sets], launches=nl)
+        calls[n] = dict(bytes=per_call[n], launches=nl, back_to_back_us=round(us, 2),
+                        GBps=round(per_call[n] / (us * 1e-6) / 1e9, 1),
+                        frac_of_peak=round(per_call[n] / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4))
+    bracketed = {n: [] for n in names}
+    for k in range(3 * len(sets)):
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+        sets[k % len(sets)].run(ev)
+        torch.cuda.synchronize()
+        for j, n in enumerate(names):
+            bracketed[n].append(ev[j].elapsed_time(ev[j + 1]) * 1e3)
+    for n in names:
+        calls[n]["event_bracketed_us"] = round(float(np.mean(bracketed[n][len(sets):])), 2)   # first round: warm-up
+    perm_us = 0.5 * (calls["pccl_hier_pack"]["back_to_back_us"] + calls["pccl_allgather_reassemble"]["back_to_back_us"])
+    achieved = per_call["pccl_hier_pack"] / (perm_us * 1e-6) / 1e9
+    roofline = dict(kernel="k_permute (pccl_hier_pack / pccl_allgather_reassemble, 256 MB each)",
+                    bound="hbm", achieved=round(achieved, 1), peak=HBM_PEAK_GBS, unit="GB/s",
+                    frac=round(achieved / HBM_PEAK_GBS, 4), traffic=PROFILED_PERMUTE_TRAFFIC_BYTES,
+                    traffic_source="profiles/k_permute_256MB_16x8.txt (rocprofv3 --pmc FETCH_SIZE, WRITE_SIZE; not measured in this run)",
+                    algorithmic_bytes_per_launch=per_call["pccl_hier_pack"], avg_launch_us=round(perm_us, 2),
+                    launches=2 * nl, timing="HIP events around back-to-back launches on the launch stream, rotating buffer sets",
+                    event_bracketed_frac=round(per_call["pccl_hier_pack"] / (0.5 * (
+                        calls["pccl_hier_pack"]["event_bracketed_us"] + calls["pccl_allgather_reassemble"]["event_bracketed_us"])
+                        * 1e-6) / 1e9 / HBM_PEAK_GBS, 4))
+    red = calls["pccl_reduce_scatter_local"]
+    roofline["reduce"] = dict(kernel="k_reduce phase 1 (8 x 32 MB) + phase 2 (16 x 2 MB), one call, two launches",
+                              bound="hbm", achieved=red["GBps"], peak=HBM_PEAK_GBS, unit="GB/s", frac=red["frac_of_peak"])
 
     # parity of the timed configuration + CPU baseline: the oracle on the very same buffers
     cpu_baseline, parity = None, None
@@ -532,11 +588,9 @@ def main():
                                            sample="%d whole steps, %.1f s" % (reps2, t2))
         # warm numbers, labelled: the same buffer set over and over (the 256 MB last-level cache holds part of it)
         warm = {}
-        for name, fn in (("pccl_hier_pack", lambda: pccl.pccl_hier_pack(s0.packed, s0.msg, w.nodes, w.gpus)),
-                         ("pccl_reduce_scatter_local", lambda: pccl.pccl_reduce_scatter_local(
-                             s0.shard, s0.partial, s0.x, d_inter=s0.d_inter, my_node=s0.my_node))):
-            t = time_calls([fn], trials=20, warm=5)
-            warm[name] = dict(back_to_back_us=round(t[3] * 1e3, 2), GBps=round(per_call[name] / (t[3] * 1e-3) / 1e9, 1))
+        for name in ("pccl_hier_pack", "pccl_reduce_scatter_local"):
+            us = back_to_back([s0.call(name)], launches=20)
+            warm[name] = dict(back_to_back_us=round(us, 2), GBps=round(per_call[name] / (us * 1e-6) / 1e9, 1))
         calls["warm_same_buffers"] = warm
     del sets
     torch.cuda.empty_cache()
@@ -545,8 +599,8 @@ def main():
     if fused is not None:
         fused["speedup_vs_three_call_step"] = round(ms_per_step / fused["ms_per_step"], 3)
     torch.cuda.empty_cache()
+    sweep = size_sweep(dev, (16, 32, 64, 128, 256, 512, 1024) if args.sweep else (64, 128, 256))
     others = None if args.no_others else other_workloads(dev)
-    sweep = size_sweep(dev) if args.sweep else None
     scale = scale_sweep(dev) if args.sweep else None
     if args.calibration_copy:
         a = torch.empty(256 * MB, dtype=torch.uint8, device=dev)
@@ -564,9 +618,9 @@ def main():
         "config": {"workload": w.name + ": pack 256 MB + two-level reduce (8 x 32 MB, 16 x 2 MB) + reassemble 256 MB",
                    "nodes": w.nodes, "gpus_per_node": w.gpus, "message_MB": w.ranks * w.chunk * w.esize // MB,
                    "accumulate": "f32", "algorithmic_bytes_per_step": step_bytes, "buffer_sets": args.sets,
-                   "kernel_events_in_timed_region": use_ev, "kernel_events_every_n_steps": every if use_ev else None},
+                   "kernel_events_in_timed_region": False, "kernel_timing_launches_per_call": nl},
         "roofline": roofline, "cpu_baseline": cpu_baseline, "parity_vs_oracle": parity,
-        "calls": calls, "fused_step": fused, "other_workloads": others, "size_sweep": sweep, "scale_sweep": scale,
+        "calls": calls, "fused_step": fused, "size_sweep": sweep, "other_workloads": others, "scale_sweep": scale,
     }
     print(json.dumps(out), flush=True)
 

@@ -51,10 +51,12 @@ struct PermuteProblem {
   int cols;
 };
 
-// Launch shape of the kernel that runs a flat sum and a chunk transpose in one grid: blocks with
-// blockIdx.z < reduce_planes are reduction tiles (linear index over z, y, x; reduce_tiles of
-// them do work), the others copy tiles of source chunk (blockIdx.y, blockIdx.z - reduce_planes),
-// except chunk (own_r, own_c), whose destination the reduction writes.
+// Launch shape of the kernel that runs a flat sum and a chunk transpose in one grid (blockIdx =
+// (tile, source row, plane)): the first reduce_planes planes hold LDS-staged reduction slices
+// (linear index over z, y, x; reduce_tiles of them do work; 0 planes for up to 16 sources), the
+// others copy tiles of source chunk (blockIdx.y, blockIdx.z - reduce_planes) -- except in chunk
+// (own_r, own_c), whose blocks compute its destination instead (tiles below reduce_tiles, when
+// there are no planes).
 struct FusedShape {
   uint32_t tiles_per_chunk;
   uint32_t skew;

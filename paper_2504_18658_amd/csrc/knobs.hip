@@ -35,6 +35,11 @@ Knobs read_env() {
     const long long t = std::atoll(v);
     if (t >= 0 && t <= 0xFFFFFFFFll) k.permute_skew = t;
   }
+  k.two_level_npt = 0;
+  if ((v = std::getenv("PCCL_TWO_LEVEL_NPT"))) {
+    const int w = std::atoi(v);
+    if (w == 2 || w == 4 || w == 8) k.two_level_npt = w;
+  }
   k.grid_x_limit = 0;
   if ((v = std::getenv("PCCL_GRID_X_LIMIT"))) {
     const long long t = std::atoll(v);

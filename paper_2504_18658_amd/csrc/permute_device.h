@@ -102,6 +102,11 @@ inline size_t tiles_per_chunk_for(const void* dst, size_t chunk_bytes) {
   return (m + chunk_bytes + kPermTile - 1) / kPermTile;
 }
 
+// Largest launch: a grid dimension holds fewer than 2^32 work-items, so a chunk has at most
+// 2^26 - 1 one-wavefront tiles (just under 64 GiB) in the 3-D form, and the whole message that
+// many in the flat form (used only when a side of the chunk matrix exceeds 65535).
+constexpr size_t kPermMaxTilesX = ((size_t)1 << 32) / kPermBlock - 1;
+
 // Which chunk index the resident blocks sweep first.  Measured on MI355X for N x 8 and 8 x N
 // chunk matrices of 32-256 MB (both orders within 0.3 % run to run): with chunks of 64-256 KB
 // the order whose fast index is the SHORT side of the matrix is 2-10 % faster (the resident

@@ -96,11 +96,6 @@ bool split_grid_xz(size_t blocks, unsigned threads, unsigned* gx, unsigned* gz) 
   return true;
 }
 
-// Largest launch: a grid dimension holds fewer than 2^32 work-items, so a chunk has at most
-// 2^26 - 1 one-wavefront tiles (just under 64 GiB) in the 3-D form, and the whole message that
-// many in the flat form (used only when a side of the chunk matrix exceeds 65535).
-constexpr size_t kPermMaxTilesX = ((size_t)1 << 32) / kPermBlock - 1;
-
 hipError_t launch_permute(const PermuteProblem& p, hipStream_t st) {
   const size_t tiles_per_chunk = tiles_per_chunk_for(p.dst, p.chunk_bytes);
   const size_t chunks = (size_t)p.rows * (size_t)p.cols;
