@@ -39,7 +39,7 @@ HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
 # HBM bytes of one 256 MB k_permute launch, from profiles/k_permute_256MB_16x8.txt (two rocprofv3 --pmc
 # runs of this file, FETCH_SIZE and WRITE_SIZE in KiB per dispatch, each scaled by what the same counter
 # reads for a plain 256 MiB copy: FETCH_SIZE x 2.000, WRITE_SIZE x 1.000).  A profiler figure, not measured here.
-PROFILED_PERMUTE_FETCH_KIB, PROFILED_PERMUTE_WRITE_KIB = 131086.6, 262203.2
+PROFILED_PERMUTE_FETCH_KIB, PROFILED_PERMUTE_WRITE_KIB = 131091.7, 262144.0
 PROFILED_PERMUTE_TRAFFIC_BYTES = int((PROFILED_PERMUTE_FETCH_KIB * 2.000 + PROFILED_PERMUTE_WRITE_KIB * 1.000) * 1024)
 MB = 1 << 20
 
