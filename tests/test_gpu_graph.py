@@ -36,7 +36,9 @@ def test_captured_all_reduce_share_replays_match_eager_and_oracle():
                     shard2=torch.empty(C, dtype=w.dtype, device=DEV), out=torch.empty_like(gathered),
                     small=torch.empty(512, dtype=torch.float32, device=DEV), ring=torch.empty_like(ring0),
                     flat=torch.empty(3001, dtype=w.dtype, device=DEV), oddpacked=torch.empty(P * 1501, dtype=w.dtype, device=DEV),
-                    shard3=torch.empty(C, dtype=w.dtype, device=DEV), partial3=torch.empty(w.nodes * C, dtype=w.dtype, device=DEV))
+                    shard3=torch.empty(C, dtype=w.dtype, device=DEV), partial3=torch.empty(w.nodes * C, dtype=w.dtype, device=DEV),
+                    tail=torch.empty_like(gathered), halving=torch.empty_like(ring0), shard4=torch.empty(C, dtype=w.dtype, device=DEV),
+                    acc_a=torch.empty(3001, dtype=w.dtype, device=DEV), acc_b=torch.empty(C, dtype=w.dtype, device=DEV))
 
     def step(b):
         pccl.pccl_hier_pack(b["packed"], msg, w.nodes, w.gpus)
@@ -50,9 +52,20 @@ def test_captured_all_reduce_share_replays_match_eager_and_oracle():
         pccl.pccl_local_reduce(b["flat"], many)
         pccl.pccl_hier_pack(b["oddpacked"], odd, w.nodes, w.gpus)
         pccl.pccl_reduce_scatter_local_unpacked_batched(b["table"], 5)
+        # the one-launch all-reduce tail (reads the partial of the second call above), the one-launch halving
+        # replay, the share whose partial lives in the library's static workspace, and a batch of two steps
+        pccl.pccl_phase2_reassemble_local(b["tail"], b["partial2"], d_inter=d_inter, src=gathered, nodes=w.nodes,
+                                          gpus_per_node=w.gpus, my_node=2, my_gpu=5)
+        b["halving"].copy_(ring0)
+        pccl.pccl_halving_reduce_scatter_local(b["halving"], recv.view(-1), 6)
+        pccl.pccl_reduce_scatter_local_static(b["shard4"], x, d_inter=d_inter, my_node=1, average=True)
+        b["acc_a"].copy_(many[0])
+        b["acc_b"].copy_(inter[0])
+        pccl.pccl_accumulate_batched(b["acc_table"])
 
     def with_table(b):
         b["table"] = pccl.BucketTable([(b["shard3"], b["partial3"], msgs)], nodes=w.nodes)   # built outside the capture
+        b["acc_table"] = pccl.AccumulateTable([(b["acc_a"], many[1]), (b["acc_b"], inter[1])])
         return b
 
     eager = with_table(buffers())
@@ -90,3 +103,12 @@ def test_captured_all_reduce_share_replays_match_eager_and_oracle():
     assert same_bits(to_np(eager["oddpacked"]), oracle.hier_pack(to_np(odd), w.nodes, w.gpus))
     ws, wp = oracle.reduce_scatter_local_unpacked([to_np(msgs[g]) for g in range(w.gpus)], w.nodes, w.gpus, 5)
     assert same_bits(to_np(eager["shard3"]), ws) and same_bits(to_np(eager["partial3"]), wp.reshape(-1))
+    assert same_bits(to_np(eager["shard4"]), to_np(eager["shard"]))
+    rows = [to_np(eager["partial2"].view(w.nodes, C)[n]) if n == 2 else to_np(inter[n]) for n in range(w.nodes)]
+    slots = [to_np(gathered.view(P, C)[k]) for k in range(P)]
+    assert same_bits(to_np(eager["tail"]), oracle.phase2_reassemble(rows, slots, w.nodes, w.gpus, 2, 5))
+    flat = recv.reshape(-1)
+    halves = [to_np(flat[:4 * C]), to_np(flat[4 * C:6 * C]), to_np(flat[6 * C:7 * C])]
+    assert same_bits(to_np(eager["halving"]), oracle.halving_rs_local(to_np(ring0), halves, 6))
+    assert same_bits(to_np(eager["acc_a"]), oracle.accumulate(to_np(many[0]), to_np(many[1])))
+    assert same_bits(to_np(eager["acc_b"]), oracle.accumulate(to_np(inter[0]), to_np(inter[1])))

@@ -133,6 +133,69 @@ def test_pack_and_unpack_chunks_beyond_4gib():
     assert torch.equal(back, src)                          # round trip = identity
 
 
+def test_fused_tail_chunks_beyond_4gib():
+    """pccl_phase2_reassemble_local with 4 GiB + 48 B chunks: tile indices, chunk offsets and the own
+    chunk's reduction all beyond 2^32 bytes."""
+    nodes, gpus, my_node, my_gpu = 2, 2, 1, 0
+    c = (1 << 31) + 24                                     # bf16 elements per chunk
+    partial = _rand(nodes * c, BF16, 21).view(nodes, c)
+    gathered = _rand(nodes * gpus * c, BF16, 22)
+    out = torch.empty_like(gathered)
+    pccl.pccl_phase2_reassemble_local(out, partial.view(-1), src=gathered, nodes=nodes, gpus_per_node=gpus,
+                                      my_node=my_node, my_gpu=my_gpu)
+    _sync()
+    o, gsrc = out.view(nodes, gpus, c), gathered.view(gpus, nodes, c)
+    for n in range(nodes):
+        for k in range(gpus):
+            if (n, k) == (my_node, my_gpu):
+                want = (partial[0].float() + partial[1].float()).to(BF16)     # two terms: one add, one rounding
+                step = 1 << 28
+                for lo in range(0, c, step):
+                    sl = slice(lo, min(c, lo + step))
+                    assert torch.equal(o[n, k, sl].view(torch.int16), want[sl].view(torch.int16)), lo
+                del want
+            else:
+                assert torch.equal(o[n, k], gsrc[k, n]), (n, k)
+    for lo in (0, c // 2, c - 4096):                       # the oracle on windows of the own chunk
+        sl = slice(lo, lo + 4096)
+        want = oracle.rs_phase2([to_np(partial[0, sl]), to_np(partial[1, sl])])
+        assert same_bits(to_np(o[my_node, my_gpu, sl]), want)
+
+
+def test_ring_and_halving_one_launch_beyond_4gib():
+    """Four ranks with 1 GiB + 16 B chunks: the message and the received buffers are 4 GiB and more,
+    so row and chunk offsets of the one-launch replays pass 2^32 bytes."""
+    p, c = 4, (1 << 29) + 8                                # bf16 elements per chunk
+    msg0 = _rand(p * c, BF16, 31).view(p, c)
+    recv = _rand((p - 1) * c, BF16, 32).view(p - 1, c)
+    rank = 2
+    msg = msg0.clone()
+    pccl.pccl_ring_reduce_scatter_local(msg, recv, rank)
+    _sync()
+    for s_ in range(p - 1):
+        ch = (rank - 2 - s_) % p
+        assert torch.equal(msg[ch].view(torch.int16), (msg0[ch] + recv[s_]).view(torch.int16)), s_
+    assert torch.equal(msg[(rank - 1) % p], msg0[(rank - 1) % p])             # the one chunk no step touches
+    for lo in (0, c - 4096):
+        sl = slice(lo, lo + 4096)
+        want = oracle.ring_rs_local(to_np(msg0[:, sl]), [to_np(recv[s_, sl]) for s_ in range(p - 1)], rank)
+        assert same_bits(to_np(msg[:, sl]), want)
+    msg = msg0.clone()
+    pccl.pccl_halving_reduce_scatter_local(msg, recv.view(-1), rank)
+    _sync()
+    flat = recv.view(-1)
+    # rank 2 keeps chunks 2..3 at step 0 (adds the first received half), then chunk 2 (adds the last chunk)
+    first = (msg0[2:4].reshape(-1) + flat[: 2 * c]).view(2, c)
+    assert torch.equal(msg[3].view(torch.int16), first[1].view(torch.int16))
+    assert torch.equal(msg[2].view(torch.int16), (first[0] + flat[2 * c:]).view(torch.int16))
+    assert torch.equal(msg[:2], msg0[:2])
+    for lo in (0, c - 4096):
+        sl = slice(lo, lo + 4096)
+        halves = [to_np(torch.stack([flat[lo:lo + 4096], flat[c + lo:c + lo + 4096]])), to_np(flat[2 * c + lo:2 * c + lo + 4096])]
+        want = oracle.halving_rs_local(to_np(msg0[:, sl]), halves, rank)
+        assert same_bits(to_np(msg[:, sl]), want)
+
+
 @pytest.fixture
 def tiny_grid_x(monkeypatch):
     """Lower the x extent of a launch to 4096 work-items so that small problems take the
