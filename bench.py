@@ -197,10 +197,10 @@ def other_workloads(dev):
                      torch.empty(w.ranks * w.chunk, dtype=w.dtype, device=dev)))
     entry("cfg4_reduce_ptrs_two_level_256x8_f32_128MB", (w.ranks + 1) * w.chunk * 4,
           *time_calls([lambda s=s: pccl.pccl_local_reduce_ptrs_two_level(
-              s[0], s[1], w.nodes, w.gpus, w.chunk, w.dtype) for s in sets]))
+              s[0], s[1], w.nodes, w.gpus, w.chunk, w.dtype) for s in sets], trials=24, warm=8))
     entry("cfg4_allgather_reassemble_256x8_f32_128MB", 2 * w.ranks * w.chunk * 4,
           *time_calls([lambda s=s: pccl.pccl_allgather_reassemble(
-              s[3], src=s[2], nodes=w.nodes, gpus_per_node=w.gpus) for s in sets]))
+              s[3], src=s[2], nodes=w.nodes, gpus_per_node=w.gpus) for s in sets], trials=24, warm=8))
     del sets
     # op = average and fp16 messages on the 256 MB two-level share (same bytes as the headline's reduce call)
     w = W.cfg3()
