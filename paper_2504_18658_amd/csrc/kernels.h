@@ -37,6 +37,7 @@ struct ReduceProblem {
   int round_partial;
   int rows;
   int row_pad;  // rows > 1: one more tile per row, so that a row's tile grid can be shifted onto cache lines
+  int keep_cached;  // streaming kernel: store dst non-temporally instead of through (the batched phase 1, whose output phase 2 reads at once)
   float divisor;
 };
 

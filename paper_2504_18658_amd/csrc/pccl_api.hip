@@ -107,6 +107,7 @@ ReduceProblem blank_problem() {
   p.round_partial = 0;
   p.rows = 1;
   p.row_pad = 0;
+  p.keep_cached = 0;
   p.divisor = 0.0f;
   return p;
 }

@@ -58,9 +58,15 @@ __device__ __forceinline__ void ld_batch(const char* const* sp, uint32_t lane_of
 }
 
 // VE consecutive results of this lane, converted to the output dtype: element threadIdx.x * VE
-// of the tile that starts at `dtile` (wave-uniform)
+// of the tile that starts at `dtile` (wave-uniform).  `through` (wave-uniform) picks the store's
+// cache policy: written through to memory, or non-temporal (the lines may stay in the L2 and the
+// last-level cache for a while).  Measured on MI355X: a result nobody reads soon is best written
+// through (the 8 x 32 MB -> 32 MB reduce and the 16-chunk phase 2 behind it: 54.0 against 55.5 us
+// per call; 52.0 against 54.8 us even when phase 2 then reads all 32 MB of it); hundreds of MB that
+// the NEXT launch reads in full are best left non-temporal (the 40-bucket batch, whose phase 2
+// reads the 650 MB of partials phase 1 has just written: 1080 against 1107 us).
 template <int OUT, int VE, bool ALIGNED>
-__device__ __forceinline__ void store_vals(char* dtile, const float* a) {
+__device__ __forceinline__ void store_vals(char* dtile, const float* a, bool through) {
   const uint32_t e = threadIdx.x * VE;
   if constexpr (narrow(OUT)) {
     if constexpr (VE == 1) {
@@ -69,17 +75,22 @@ __device__ __forceinline__ void store_vals(char* dtile, const float* a) {
       uint32_t w[VE / 2];
 #pragma unroll
       for (int k = 0; k < VE / 2; ++k) w[k] = pack16<OUT>(a[2 * k], a[2 * k + 1]);
-      st_tile_words<VE / 2, 2, ALIGNED>(dtile, e * 2, w);
+      if (through)
+        st_tile_words<VE / 2, 2, ALIGNED>(dtile, e * 2, w);
+      else
+        st_words<VE / 2, 2, ALIGNED>(dtile, e * 2, w);
     }
   } else {
     uint32_t w[VE];
 #pragma unroll
     for (int k = 0; k < VE; ++k) w[k] = __float_as_uint(a[k]);
-    if constexpr (VE == 8) {
-      st_tile_words<4, 4, ALIGNED>(dtile, e * 4, w);
-      st_tile_words<4, 4, ALIGNED>(dtile, e * 4 + 16, w + 4);
+    constexpr int W1 = VE == 8 ? 4 : VE;
+    if (through) {
+      st_tile_words<W1, 4, ALIGNED>(dtile, e * 4, w);
+      if constexpr (VE == 8) st_tile_words<4, 4, ALIGNED>(dtile, e * 4 + 16, w + 4);
     } else {
-      st_tile_words<VE, 4, ALIGNED>(dtile, e * 4, w);
+      st_words<W1, 4, ALIGNED>(dtile, e * 4, w);
+      if constexpr (VE == 8) st_words<4, 4, ALIGNED>(dtile, e * 4 + 16, w + 4);
     }
   }
 }
@@ -206,7 +217,7 @@ __device__ __forceinline__ void reduce_tile(const ReduceProblem& p, size_t tile,
     // the tile's first output element (the head offset included: the store checks this pointer's
     // alignment; below the buffer for the idle head of tile 0, as tile_off is)
     constexpr size_t EO = narrow(OUT) ? 2 : 4;
-    store_vals<OUT, VE, FAST>(reinterpret_cast<char*>(p.dst) + ((tile * BLOCK - shift) * VE + head) * EO, acc);
+    store_vals<OUT, VE, FAST>(reinterpret_cast<char*>(p.dst) + ((tile * BLOCK - shift) * VE + head) * EO, acc, p.keep_cached == 0);
   }
 
   // the head element and the ragged tail (what the vectors leave): at most VE <= 8 elements

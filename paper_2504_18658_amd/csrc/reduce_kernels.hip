@@ -372,6 +372,7 @@ __global__ __launch_bounds__(kBlock) void k_rs_batched(const pccl_bucket_t* __re
   p.row_stride_dst = 0;
   p.rows = 1;
   p.row_pad = 0;
+  p.keep_cached = PHASE == 1 ? 1 : 0;  // phase 2 of the batch reads every partial phase 1 writes
   p.divisor = PHASE == 2 ? divisor : 0.0f;
   if (PHASE == 1) {  // partial[n][e] = sum over g' of piece_g'[n][e]
     p.dst = b.partial;
@@ -461,6 +462,7 @@ __global__ __launch_bounds__(kBlockSmall) void k_rs_batched_rows(const pccl_buck
   p.row_stride_dst = 0;
   p.rows = 1;
   p.row_pad = 0;
+  p.keep_cached = 1;  // phase 2 of the batch reads every partial this launch writes
   p.divisor = 0.0f;
   p.dst = reinterpret_cast<char*>(b.partial) + (size_t)row * chunk_bytes;
   p.base = reinterpret_cast<const char*>(b.intra_base) + ((size_t)row * gpus + my_gpu) * chunk_bytes;
