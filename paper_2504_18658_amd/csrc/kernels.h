@@ -67,6 +67,22 @@ struct FusedShape {
   int own_c;
 };
 
+// One two-level reduce-scatter share with received inter-node chunks, for the one-launch form:
+// pieces g at intra_base + g*intra_stride, each [nodes][chunk_count] of the message dtype;
+// partial [nodes][chunk_count]; inter[n] for n != my_node from the device pointer array.
+struct ShareProblem {
+  void* shard;
+  void* partial;
+  const char* intra_base;
+  const void* const* d_inter;
+  size_t intra_stride;
+  size_t chunk_count;
+  int nodes;
+  int gpus;
+  int my_node;
+  float divisor;
+};
+
 constexpr int kMaxBuckets = PCCL_MAX_BUCKETS;
 
 // Prefix of tiles over the buckets of a batch, passed by value to the batched kernels.
@@ -78,6 +94,11 @@ struct BatchTiles {
 hipError_t launch_reduce(const ReduceProblem& p, int in_dt, int out_dt, hipStream_t st);
 hipError_t launch_reduce_two_level_lds(const ReduceProblem& p, int in_dt, int out_dt,
                                        hipStream_t st);
+// Both phases of a share in ONE launch (up to kShareFusedMaxNodes nodes, a per-node source count
+// with an unrolled body): hipErrorNotSupported when the shape has no such form (the caller then
+// launches phase by phase), other errors as above.
+constexpr int kShareFusedMaxNodes = 16;
+hipError_t launch_share_fused(const ShareProblem& s, int dt, hipStream_t st);
 // True when the LDS-staged kernel is the better choice for this shape.
 bool prefer_lds_two_level(const ReduceProblem& p, int in_dt);
 // A flat sum written as p.nodes sources (p.gpus == 1, one row, no partial kept) through the

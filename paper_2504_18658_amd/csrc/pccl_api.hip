@@ -261,6 +261,23 @@ pccl_status_t launch_share(void* shard, void* partial, const void* intra_base, s
                            hipStream_t st) {
   const int dt = io_dt;
   const float divisor = divisor_for(op, (size_t)nodes * (size_t)gpus_per_node);
+  // With the other nodes' chunks at hand phase 2 only needs the own node's row of the partial:
+  // one launch does both phases (step by step on request, for A/B runs, and for shapes without that form).
+  if (d_inter != nullptr && shard != nullptr && !pccl::knobs().share_launches) {
+    pccl::ShareProblem sp;
+    sp.shard = shard;
+    sp.partial = partial;
+    sp.intra_base = reinterpret_cast<const char*>(intra_base);
+    sp.d_inter = d_inter;
+    sp.intra_stride = gpus_per_node > 1 ? intra_stride_bytes : 0;
+    sp.chunk_count = chunk_count;
+    sp.nodes = nodes;
+    sp.gpus = gpus_per_node;
+    sp.my_node = my_node;
+    sp.divisor = divisor;
+    const hipError_t e = pccl::launch_share_fused(sp, dt, st);
+    if (e != hipErrorNotSupported) return e == hipErrorInvalidValue ? PCCL_ERR_INVALID : from_hip(e);
+  }
   // phase 1 (intra-node): partial[n][e] = sum over g' of piece_g'[n][e], an M-source flat
   // sum over the nodes*chunk_count elements of a piece
   ReduceProblem p1 = blank_problem();

@@ -341,6 +341,177 @@ hipError_t launch_flat_lds_io(const ReduceProblem& p, hipStream_t st) {
 }
 
 // ------------------------------------------------------------------------------------------
+// Both phases of a two-level reduce-scatter share in one launch, when the other nodes' chunks
+// are there already (d_inter).  Of the partial, only the row of the rank's own node feeds phase 2
+// (the other rows leave for the other nodes), so nothing forces a second launch to wait for the
+// whole of phase 1: the tiles of the OWN row go on, in the same block, to add the received
+// chunks in node order and store the shard.  The own row is then written but never read back
+// (2*C*e bytes of the 35 MB a separate phase 2 moves at half the bandwidth of a large launch),
+// and a dispatch with its fixed cost disappears.
+//   T0 tiles of the own row: phase 1 of C elements, then phase 2 of the same
+//   TA tiles: phase 1 of the rows below my_node (one flat reduction of my_node*C elements)
+//   TB tiles: phase 1 of the rows above it
+// The own row's tiles (M + N - 1 loads per lane) take the lowest block indices.  Dealing them evenly among the
+// others instead measured the same (52.2 against 52.0 us at 16 x 8 x 2 MB) -- provided their places cycle
+// through the residues mod 8: blocks go to the 8 XCDs round-robin, and with one such tile at every 16th block
+// ALL of them ran on one XCD, which finished 30 us after the other seven (81 us for the launch).
+// Same adds in the same order as the two-launch form, so the same bits.
+template <int DT, int M, bool FAST, int BLOCK>
+__device__ __forceinline__ void own_row_tile(const ShareProblem& s, size_t tile) {
+  constexpr int W = words_for(M);
+  constexpr int VE = narrow(DT) ? 2 * W : W;
+  constexpr int ES = narrow(DT) ? 2 : 4;
+  constexpr int VB = 4 * W;
+  constexpr int NMAX = kShareFusedMaxNodes;
+  const size_t count = s.chunk_count;
+  const size_t row_off = (size_t)s.my_node * count * ES;
+  const char* own = s.intra_base + row_off;
+  char* prow = reinterpret_cast<char*>(s.partial) + row_off;
+  char* shard = reinterpret_cast<char*>(s.shard);
+  const size_t nvec = count / VE;
+  const size_t ntiles = (nvec + BLOCK - 1) / BLOCK;
+  const size_t last_tile = ntiles == 0 ? 0 : ntiles - 1;
+  const size_t v = tile * BLOCK + threadIdx.x;
+  const size_t tile_off = tile * BLOCK * (size_t)VB;
+  const uint32_t lane_off = threadIdx.x * VB;
+  if (v < nvec) {
+    const char* sp[M];
+#pragma unroll
+    for (int g = 0; g < M; ++g) sp[g] = own + (size_t)g * s.intra_stride + tile_off;
+    uint32_t raw[M][W];
+    ld_batch<M, W, ES, FAST>(sp, lane_off, raw);
+    uint32_t rin[NMAX][W];
+#pragma unroll
+    for (int n = 0; n < NMAX; ++n)
+      if (n < s.nodes && n != s.my_node) ld_words<W, ES, false>(ld_pointer(s.d_inter, n) + tile_off, lane_off, rin[n]);
+    float t[VE];
+    unpack<DT, W>(raw[0], t);
+#pragma unroll
+    for (int g = 1; g < M; ++g) {
+      float x[VE];
+      unpack<DT, W>(raw[g], x);
+#pragma unroll
+      for (int k = 0; k < VE; ++k) t[k] = t[k] + x[k];
+    }
+    // the own node's partial: rounded through the message dtype, stored, and used as rounded
+    uint32_t w[W];
+    if (narrow(DT)) {
+#pragma unroll
+      for (int k = 0; k < W; ++k) w[k] = pack16<DT>(t[2 * k], t[2 * k + 1]);
+      unpack<DT, W>(w, t);
+    } else {
+#pragma unroll
+      for (int k = 0; k < W; ++k) w[k] = __float_as_uint(t[k]);
+    }
+    st_tile_words<W, ES, FAST>(prow + tile_off, lane_off, w);
+    float acc[VE];
+#pragma unroll
+    for (int n = 0; n < NMAX; ++n)
+      if (n < s.nodes) {
+        float x[VE];
+        if (n == s.my_node) {
+#pragma unroll
+          for (int k = 0; k < VE; ++k) x[k] = t[k];
+        } else {
+          unpack<DT, W>(rin[n], x);
+        }
+#pragma unroll
+        for (int k = 0; k < VE; ++k) acc[k] = (n == 0) ? x[k] : acc[k] + x[k];
+      }
+    if (s.divisor != 0.0f) {
+#pragma unroll
+      for (int k = 0; k < VE; ++k) acc[k] = acc[k] / s.divisor;
+    }
+    store_vals<DT, VE, FAST>(shard + tile_off, acc, true);
+  }
+  if (tile == last_tile) {  // the ragged tail: fewer than VE elements
+    const size_t e = nvec * VE + threadIdx.x;
+    if (e < count) {
+      float t = ld_elem<DT>(own, e);
+      for (int g = 1; g < M; ++g) t = t + ld_elem<DT>(own + (size_t)g * s.intra_stride, e);
+      t = round_through<DT>(t);
+      st_elem<DT>(prow, e, t);
+      float acc = 0.0f;
+      for (int n = 0; n < s.nodes; ++n) {
+        const float x = n == s.my_node ? t : ld_elem<DT>(ld_pointer(s.d_inter, n), e);
+        acc = n == 0 ? x : acc + x;
+      }
+      if (s.divisor != 0.0f) acc = acc / s.divisor;
+      st_elem<DT>(shard, e, acc);
+    }
+  }
+}
+
+inline size_t own_row_tiles(size_t count, int m, bool in_narrow, int block) { return tiles_for(count, m, in_narrow, block); }
+
+template <int DT, int M, bool FAST>
+__global__ __launch_bounds__(kBlock) void k_share_fused(ShareProblem s, uint32_t t0, uint32_t ta, uint32_t tb) {
+  constexpr size_t ES = narrow(DT) ? 2 : 4;
+  const size_t block = linear_block_xz();
+  if (block < t0) {
+    own_row_tile<DT, M, FAST, kBlock>(s, block);
+    return;
+  }
+  if (block >= (size_t)t0 + ta + tb) return;  // the x*z rectangle is rounded up
+  const bool above = block >= (size_t)t0 + ta;
+  const size_t first_row = above ? (size_t)s.my_node + 1 : 0;
+  const size_t off = first_row * s.chunk_count * ES;
+  ReduceProblem p;
+  p.ptrs = nullptr;
+  p.override_ptr = nullptr;
+  p.override_index = -1;
+  p.partial = nullptr;
+  p.round_partial = 0;
+  p.nodes = 1;
+  p.stride_n = 0;
+  p.src_offset = 0;
+  p.row_stride_src = 0;
+  p.row_stride_dst = 0;
+  p.rows = 1;
+  p.row_pad = 0;
+  p.keep_cached = 0;
+  p.divisor = 0.0f;
+  p.dst = reinterpret_cast<char*>(s.partial) + off;
+  p.base = s.intra_base + off;
+  p.stride_g = s.intra_stride;
+  p.count = (above ? (size_t)(s.nodes - 1 - s.my_node) : (size_t)s.my_node) * s.chunk_count;
+  p.gpus = M;
+  reduce_tile<DT, DT, M, words_for(M), FAST, kBlock>(p, block - t0 - (above ? ta : 0));
+}
+
+template <int DT, int M>
+hipError_t launch_share_m(const ShareProblem& s, hipStream_t st) {
+  const size_t es = narrow(DT) ? 2 : 4;
+  const size_t t0 = own_row_tiles(s.chunk_count, M, narrow(DT), kBlock);
+  const size_t ca = (size_t)s.my_node * s.chunk_count, cb = (size_t)(s.nodes - 1 - s.my_node) * s.chunk_count;
+  const size_t ta = ca ? tiles_for(ca, M, narrow(DT), kBlock) : 0, tb = cb ? tiles_for(cb, M, narrow(DT), kBlock) : 0;
+  if (t0 > 0xFFFFFFFFull || ta > 0xFFFFFFFFull || tb > 0xFFFFFFFFull) return hipErrorInvalidValue;
+  unsigned gx, gz;
+  if (!split_grid_xz(t0 + ta + tb, kBlock, &gx, &gz)) return hipErrorInvalidValue;
+  const bool fast = is16(s.shard) && is16(s.partial) && is16(s.intra_base) && s.intra_stride % 16 == 0 &&
+                    (s.chunk_count * es) % 16 == 0;
+  if (fast)
+    hipLaunchKernelGGL((k_share_fused<DT, M, true>), dim3(gx, 1, gz), dim3(kBlock), 0, st, s, (uint32_t)t0, (uint32_t)ta,
+                       (uint32_t)tb);
+  else
+    hipLaunchKernelGGL((k_share_fused<DT, M, false>), dim3(gx, 1, gz), dim3(kBlock), 0, st, s, (uint32_t)t0, (uint32_t)ta,
+                       (uint32_t)tb);
+  return hipGetLastError();
+}
+
+template <int DT>
+hipError_t launch_share_dt(const ShareProblem& s, hipStream_t st) {
+  switch (pick_m(s.gpus)) {
+    case 1: return launch_share_m<DT, 1>(s, st);
+    case 2: return launch_share_m<DT, 2>(s, st);
+    case 4: return launch_share_m<DT, 4>(s, st);
+    case 8: return launch_share_m<DT, 8>(s, st);
+    case 16: return launch_share_m<DT, 16>(s, st);
+    default: return hipErrorNotSupported;
+  }
+}
+
+// ------------------------------------------------------------------------------------------
 // batched two-level reduce-scatter share: a flat tile space over all buckets, one launch
 // per phase.  Each block finds its bucket by bisection in the tile prefix (kernel argument).
 template <int DT, int M, int PHASE, bool FAST>
@@ -560,6 +731,14 @@ hipError_t launch_reduce_two_level_lds(const ReduceProblem& p, int in_dt, int ou
 
 hipError_t launch_reduce_flat_lds(const ReduceProblem& p, int in_dt, int out_dt, hipStream_t st) {
   PCCL_DISPATCH_IO(launch_flat_lds_io, in_dt, out_dt, p, st);
+}
+
+hipError_t launch_share_fused(const ShareProblem& s, int dt, hipStream_t st) {
+  if (s.nodes > kShareFusedMaxNodes || s.d_inter == nullptr || s.chunk_count == 0) return hipErrorNotSupported;
+  if (dt == kF32) return launch_share_dt<kF32>(s, st);
+  if (dt == kBF16) return launch_share_dt<kBF16>(s, st);
+  if (dt == kF16) return launch_share_dt<kF16>(s, st);
+  return hipErrorInvalidValue;
 }
 
 bool prefer_flat_lds(const ReduceProblem& p, int in_dt) {
