@@ -4,8 +4,8 @@
 A step is one GPU's share of a two-level all-reduce of one 256 MB bf16 message at
 16 nodes x 8 GPUs (the 256 MB workload of the configuration list):
     pccl_hier_pack            256 MB rank-order message -> hierarchical order
-    pccl_reduce_scatter_local phase 1: 8 x 32 MB -> 32 MB partial; phase 2: 16 x 2 MB -> 2 MB
-                              (the 15 foreign chunks arrive through a device pointer array)
+    pccl_reduce_scatter_local phase 1: 8 x 32 MB -> 32 MB partial; phase 2: 16 x 2 MB -> 2 MB, both in
+                              one launch (the 15 foreign chunks arrive through a device pointer array)
     pccl_allgather_reassemble 256 MB of gathered shards -> rank order
 Inputs are seeded synthetic tensors already resident in HBM; every step works on the next of
 several disjoint buffer sets so that the last-level cache cannot serve a re-run.
@@ -39,7 +39,7 @@ HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
 # HBM bytes of one 256 MB k_permute launch, from profiles/k_permute_256MB_16x8.txt (two rocprofv3 --pmc
 # runs of this file, FETCH_SIZE and WRITE_SIZE in KiB per dispatch, each scaled by what the same counter
 # reads for a plain 256 MiB copy: FETCH_SIZE x 2.000, WRITE_SIZE x 1.000).  A profiler figure, not measured here.
-PROFILED_PERMUTE_FETCH_KIB, PROFILED_PERMUTE_WRITE_KIB = 131091.7, 262144.0
+PROFILED_PERMUTE_FETCH_KIB, PROFILED_PERMUTE_WRITE_KIB = 131091.6, 262144.0
 PROFILED_PERMUTE_TRAFFIC_BYTES = int((PROFILED_PERMUTE_FETCH_KIB * 2.000 + PROFILED_PERMUTE_WRITE_KIB * 1.000) * 1024)
 MB = 1 << 20
 
@@ -550,7 +550,7 @@ def main():
                         calls["pccl_hier_pack"]["event_bracketed_us"] + calls["pccl_allgather_reassemble"]["event_bracketed_us"])
                         * 1e-6) / 1e9 / HBM_PEAK_GBS, 4))
     red = calls["pccl_reduce_scatter_local"]
-    roofline["reduce"] = dict(kernel="k_reduce phase 1 (8 x 32 MB) + phase 2 (16 x 2 MB), one call, two launches",
+    roofline["reduce"] = dict(kernel="k_share_fused: phase 1 (8 x 32 MB) and phase 2 (16 x 2 MB), one call, one launch",
                               bound="hbm", achieved=red["GBps"], peak=HBM_PEAK_GBS, unit="GB/s", frac=red["frac_of_peak"])
 
     # parity of the timed configuration + CPU baseline: the oracle on the very same buffers

@@ -169,10 +169,11 @@ pccl_status_t pccl_hier_unpack(void* dst, const void* src, int nodes, int gpus_p
  *            else d_inter is a device array of `nodes` device pointers to chunk_count
  *            elements each; slot my_node is ignored and partial[my_node] is used.
  * partial is caller-provided scratch/output: [nodes][chunk_count] of io_dt (it is the
- * buffer that would go on the wire between the phases).  With d_inter given, up to 16 nodes
- * and 1, 2, 4, 8 or 16 GPUs per node, ONE kernel is enqueued: phase 2 needs only the own node's
- * row of the partial, so the blocks that compute that row go straight on to add the received
- * chunks (every row of partial is still written; same bits).  Otherwise two kernels.
+ * buffer that would go on the wire between the phases).  With d_inter given and 1, 2, 4, 8 or
+ * 16 GPUs per node, ONE kernel is enqueued: phase 2 needs only the own node's row of the
+ * partial, so the blocks that compute that row go straight on to add the received chunks
+ * (every row of partial is still written; same bits).  Otherwise, and beyond 16 nodes when
+ * the message is too short to cover that longer tail (under about 10 MiB per 16 nodes), two.
  * shard == NULL runs phase 1 only (one kernel; d_inter and my_node are then unused apart from
  * their checks): for callers that finish with pccl_phase2_reassemble_local.
  * Errors: NULLs; nodes/gpus < 1; my_node outside [0, nodes); stride < nodes*chunk bytes;

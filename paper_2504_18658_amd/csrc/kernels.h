@@ -94,11 +94,12 @@ struct BatchTiles {
 hipError_t launch_reduce(const ReduceProblem& p, int in_dt, int out_dt, hipStream_t st);
 hipError_t launch_reduce_two_level_lds(const ReduceProblem& p, int in_dt, int out_dt,
                                        hipStream_t st);
-// Both phases of a share in ONE launch (up to kShareFusedMaxNodes nodes, a per-node source count
-// with an unrolled body): hipErrorNotSupported when the shape has no such form (the caller then
-// launches phase by phase), other errors as above.
+// Both phases of a share in ONE launch (a per-node source count with an unrolled body; the blocks
+// of the own row add the received chunks kShareFusedMaxNodes at a time): hipErrorNotSupported when
+// the shape has no such form, or (unless any_shape) is one where a launch per phase measured faster
+// (the caller then launches phase by phase), other errors as above.
 constexpr int kShareFusedMaxNodes = 16;
-hipError_t launch_share_fused(const ShareProblem& s, int dt, hipStream_t st);
+hipError_t launch_share_fused(const ShareProblem& s, int dt, bool any_shape, hipStream_t st);
 // True when the LDS-staged kernel is the better choice for this shape.
 bool prefer_lds_two_level(const ReduceProblem& p, int in_dt);
 // A flat sum written as p.nodes sources (p.gpus == 1, one row, no partial kept) through the

@@ -36,7 +36,7 @@ Knobs read_env() {
     if (t >= 0 && t <= 0xFFFFFFFFll) k.permute_skew = t;
   }
   k.share_launches = 0;
-  if ((v = std::getenv("PCCL_SHARE_LAUNCHES"))) k.share_launches = v[0] == '2';
+  if ((v = std::getenv("PCCL_SHARE_LAUNCHES"))) k.share_launches = v[0] == '2' ? 2 : v[0] == '1' ? 1 : 0;
   k.two_level_npt = 0;
   if ((v = std::getenv("PCCL_TWO_LEVEL_NPT"))) {
     const int w = std::atoi(v);

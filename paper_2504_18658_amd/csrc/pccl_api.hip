@@ -263,7 +263,7 @@ pccl_status_t launch_share(void* shard, void* partial, const void* intra_base, s
   const float divisor = divisor_for(op, (size_t)nodes * (size_t)gpus_per_node);
   // With the other nodes' chunks at hand phase 2 only needs the own node's row of the partial:
   // one launch does both phases (step by step on request, for A/B runs, and for shapes without that form).
-  if (d_inter != nullptr && shard != nullptr && !pccl::knobs().share_launches) {
+  if (d_inter != nullptr && shard != nullptr && pccl::knobs().share_launches != 2) {
     pccl::ShareProblem sp;
     sp.shard = shard;
     sp.partial = partial;
@@ -275,7 +275,7 @@ pccl_status_t launch_share(void* shard, void* partial, const void* intra_base, s
     sp.gpus = gpus_per_node;
     sp.my_node = my_node;
     sp.divisor = divisor;
-    const hipError_t e = pccl::launch_share_fused(sp, dt, st);
+    const hipError_t e = pccl::launch_share_fused(sp, dt, pccl::knobs().share_launches == 1, st);
     if (e != hipErrorNotSupported) return e == hipErrorInvalidValue ? PCCL_ERR_INVALID : from_hip(e);
   }
   // phase 1 (intra-node): partial[n][e] = sum over g' of piece_g'[n][e], an M-source flat

@@ -356,7 +356,9 @@ hipError_t launch_flat_lds_io(const ReduceProblem& p, hipStream_t st) {
 // through the residues mod 8: blocks go to the 8 XCDs round-robin, and with one such tile at every 16th block
 // ALL of them ran on one XCD, which finished 30 us after the other seven (81 us for the launch).
 // Same adds in the same order as the two-launch form, so the same bits.
-template <int DT, int M, bool FAST, int BLOCK>
+// MANY = more than kShareFusedMaxNodes nodes: the received chunks are then loaded and added in
+// rounds of kShareFusedMaxNodes (still ascending node order, one sequential chain per element).
+template <int DT, int M, bool FAST, int BLOCK, bool MANY>
 __device__ __forceinline__ void own_row_tile(const ShareProblem& s, size_t tile) {
   constexpr int W = words_for(M);
   constexpr int VE = narrow(DT) ? 2 * W : W;
@@ -384,6 +386,7 @@ __device__ __forceinline__ void own_row_tile(const ShareProblem& s, size_t tile)
 #pragma unroll
     for (int n = 0; n < NMAX; ++n)
       if (n < s.nodes && n != s.my_node) ld_words<W, ES, false>(ld_pointer(s.d_inter, n) + tile_off, lane_off, rin[n]);
+    // (with MANY these are the first round's loads, in flight under phase 1 like the others)
     float t[VE];
     unpack<DT, W>(raw[0], t);
 #pragma unroll
@@ -418,6 +421,27 @@ __device__ __forceinline__ void own_row_tile(const ShareProblem& s, size_t tile)
 #pragma unroll
         for (int k = 0; k < VE; ++k) acc[k] = (n == 0) ? x[k] : acc[k] + x[k];
       }
+    if (MANY) {
+      for (int n0 = NMAX; n0 < s.nodes; n0 += NMAX) {
+#pragma unroll
+        for (int j = 0; j < NMAX; ++j)
+          if (n0 + j < s.nodes && n0 + j != s.my_node)
+            ld_words<W, ES, false>(ld_pointer(s.d_inter, n0 + j) + tile_off, lane_off, rin[j]);
+#pragma unroll
+        for (int j = 0; j < NMAX; ++j)
+          if (n0 + j < s.nodes) {
+            float x[VE];
+            if (n0 + j == s.my_node) {
+#pragma unroll
+              for (int k = 0; k < VE; ++k) x[k] = t[k];
+            } else {
+              unpack<DT, W>(rin[j], x);
+            }
+#pragma unroll
+            for (int k = 0; k < VE; ++k) acc[k] = acc[k] + x[k];
+          }
+      }
+    }
     if (s.divisor != 0.0f) {
 #pragma unroll
       for (int k = 0; k < VE; ++k) acc[k] = acc[k] / s.divisor;
@@ -444,12 +468,12 @@ __device__ __forceinline__ void own_row_tile(const ShareProblem& s, size_t tile)
 
 inline size_t own_row_tiles(size_t count, int m, bool in_narrow, int block) { return tiles_for(count, m, in_narrow, block); }
 
-template <int DT, int M, bool FAST>
+template <int DT, int M, bool FAST, bool MANY>
 __global__ __launch_bounds__(kBlock) void k_share_fused(ShareProblem s, uint32_t t0, uint32_t ta, uint32_t tb) {
   constexpr size_t ES = narrow(DT) ? 2 : 4;
   const size_t block = linear_block_xz();
   if (block < t0) {
-    own_row_tile<DT, M, FAST, kBlock>(s, block);
+    own_row_tile<DT, M, FAST, kBlock, MANY>(s, block);
     return;
   }
   if (block >= (size_t)t0 + ta + tb) return;  // the x*z rectangle is rounded up
@@ -490,12 +514,17 @@ hipError_t launch_share_m(const ShareProblem& s, hipStream_t st) {
   if (!split_grid_xz(t0 + ta + tb, kBlock, &gx, &gz)) return hipErrorInvalidValue;
   const bool fast = is16(s.shard) && is16(s.partial) && is16(s.intra_base) && s.intra_stride % 16 == 0 &&
                     (s.chunk_count * es) % 16 == 0;
-  if (fast)
-    hipLaunchKernelGGL((k_share_fused<DT, M, true>), dim3(gx, 1, gz), dim3(kBlock), 0, st, s, (uint32_t)t0, (uint32_t)ta,
-                       (uint32_t)tb);
+  const bool many = s.nodes > kShareFusedMaxNodes;
+  const dim3 grid(gx, 1, gz), blk(kBlock);
+  const uint32_t a0 = (uint32_t)t0, a1 = (uint32_t)ta, a2 = (uint32_t)tb;
+  if (fast && !many)
+    hipLaunchKernelGGL((k_share_fused<DT, M, true, false>), grid, blk, 0, st, s, a0, a1, a2);
+  else if (fast)
+    hipLaunchKernelGGL((k_share_fused<DT, M, true, true>), grid, blk, 0, st, s, a0, a1, a2);
+  else if (!many)
+    hipLaunchKernelGGL((k_share_fused<DT, M, false, false>), grid, blk, 0, st, s, a0, a1, a2);
   else
-    hipLaunchKernelGGL((k_share_fused<DT, M, false>), dim3(gx, 1, gz), dim3(kBlock), 0, st, s, (uint32_t)t0, (uint32_t)ta,
-                       (uint32_t)tb);
+    hipLaunchKernelGGL((k_share_fused<DT, M, false, true>), grid, blk, 0, st, s, a0, a1, a2);
   return hipGetLastError();
 }
 
@@ -733,8 +762,19 @@ hipError_t launch_reduce_flat_lds(const ReduceProblem& p, int in_dt, int out_dt,
   PCCL_DISPATCH_IO(launch_flat_lds_io, in_dt, out_dt, p, st);
 }
 
-hipError_t launch_share_fused(const ShareProblem& s, int dt, hipStream_t st) {
-  if (s.nodes > kShareFusedMaxNodes || s.d_inter == nullptr || s.chunk_count == 0) return hipErrorNotSupported;
+hipError_t launch_share_fused(const ShareProblem& s, int dt, bool any_shape, hipStream_t st) {
+  if (s.d_inter == nullptr || s.chunk_count == 0) return hipErrorNotSupported;
+  // Beyond kShareFusedMaxNodes nodes a block of the own row walks the received chunks in rounds, each
+  // a pointer fetch and a load behind the last (about 1.8 us); phase 1 has to run long enough to
+  // cover that chain.  Measured, bf16, 8 per node, one launch against two: 256 MB at 32-256 nodes
+  // 52-53 against 57-59 us; 64 MB at 64 nodes 16.9 against 17.7, at 128 nodes 21.3 against 18.5;
+  // 16 MB at 64 nodes 10.3 against 8.3.
+  if (s.nodes > kShareFusedMaxNodes && !any_shape) {
+    const size_t rounds = ((size_t)s.nodes + kShareFusedMaxNodes - 1) / kShareFusedMaxNodes;
+    const size_t es = (dt == kF32) ? 4 : 2;
+    const size_t phase1_in = (size_t)s.gpus * s.nodes * s.chunk_count * es;
+    if (phase1_in < rounds * ((size_t)10 << 20)) return hipErrorNotSupported;
+  }
   if (dt == kF32) return launch_share_dt<kF32>(s, st);
   if (dt == kBF16) return launch_share_dt<kBF16>(s, st);
   if (dt == kF16) return launch_share_dt<kF16>(s, st);

@@ -15,10 +15,12 @@ DEV = "cuda"
 F32, BF16, F16 = torch.float32, torch.bfloat16, torch.float16
 
 
-@pytest.fixture(params=["one launch", "launch per phase"])
+@pytest.fixture(params=["one launch", "launch per phase", "chooser"])
 def launches(request, monkeypatch):
-    if request.param == "launch per phase":
-        monkeypatch.setenv("PCCL_SHARE_LAUNCHES", "2")
+    # "1" takes the one-launch form wherever it exists (the chooser leaves small messages at many
+    # nodes to a launch per phase), "2" never
+    if request.param != "chooser":
+        monkeypatch.setenv("PCCL_SHARE_LAUNCHES", "1" if request.param == "one launch" else "2")
         pccl.diag_reload_env()
     return request.param
 
@@ -54,7 +56,7 @@ def _run(dtype, nodes, gpus, chunk, my_node, seed, average=False, piece_pad=0, o
 
 
 @pytest.mark.parametrize("dtype", [F32, BF16, F16])
-@pytest.mark.parametrize("nodes", [1, 2, 3, 8, 16, 17])
+@pytest.mark.parametrize("nodes", [1, 2, 3, 8, 16, 17, 33, 130])
 @pytest.mark.parametrize("gpus", [1, 2, 4, 8, 16, 5])
 def test_share_shapes(launches, dtype, nodes, gpus):
     print("share", launches, dtype, nodes, gpus, flush=True)
@@ -72,6 +74,13 @@ def test_share_unaligned_and_strided(launches, dtype):
 @pytest.mark.parametrize("dtype", [F32, BF16, F16])
 def test_share_average(launches, dtype):
     _run(dtype, 16, 8, 5000, 7, seed=8, average=True)
+
+
+def test_share_many_nodes_beyond_the_chooser_threshold(launches):
+    """128 x 8 ranks with 64 KB chunks (a 64 MB bf16 message: the chooser picks a launch per phase)
+    and with 160 KB chunks (160 MB: one launch), own node first, in the middle of a round, last."""
+    for chunk, my_node in ((32768, 0), (81920, 37), (81920 + 8, 127)):
+        _run(BF16, 128, 8, chunk, my_node, seed=40 + my_node)
 
 
 def test_static_share_takes_the_same_path(launches):
