@@ -17,7 +17,8 @@ struct Knobs {
   int permute_order;       // PCCL_PERMUTE_ORDER: 0 chooser, 1 "dst", 2 "src"
   long long permute_skew;  // PCCL_PERMUTE_SKEW: -1 chooser, else tiles
   int share_launches;      // PCCL_SHARE_LAUNCHES: 0 one launch for both phases of a share where that is faster, 1: wherever that form exists, 2: one per phase
-  int two_level_npt;       // PCCL_TWO_LEVEL_NPT: 0 default, else nodes per wavefront and tile of the LDS two-level kernel (2, 4, 8)
+  int two_level_npt;       // PCCL_TWO_LEVEL_NPT: 0 default; 4: four nodes per wavefront and tile where the default is eight
+  int two_level_pipe;      // PCCL_TWO_LEVEL_PIPE: 1 (default) loads kept in flight across tile boundaries where the shape allows, 0 the plain loop
   size_t grid_x_limit;     // PCCL_GRID_X_LIMIT: 0 = the hardware's, else work-items in x
   int check_pointers;      // PCCL_CHECK_POINTERS: 0 off, 1 ranges, 2 also device-resident tables
   int step_launches;         // PCCL_STEP_LAUNCHES: 0 one launch for a whole replay, 1 one launch per step

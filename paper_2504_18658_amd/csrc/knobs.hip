@@ -40,8 +40,10 @@ Knobs read_env() {
   k.two_level_npt = 0;
   if ((v = std::getenv("PCCL_TWO_LEVEL_NPT"))) {
     const int w = std::atoi(v);
-    if (w == 2 || w == 4 || w == 8) k.two_level_npt = w;
+    if (w == 4 || w == 8) k.two_level_npt = w;
   }
+  k.two_level_pipe = 1;
+  if ((v = std::getenv("PCCL_TWO_LEVEL_PIPE"))) k.two_level_pipe = v[0] != '0';
   k.grid_x_limit = 0;
   if ((v = std::getenv("PCCL_GRID_X_LIMIT"))) {
     const long long t = std::atoll(v);

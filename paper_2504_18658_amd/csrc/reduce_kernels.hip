@@ -113,7 +113,9 @@ hipError_t launch_io(const ReduceProblem& p, hipStream_t st) {
 //     array, so ONE per-lane load fetches them (a tile ahead) and v_readlane hands each to
 //     the scalar unit as the base of a load;
 //   * the parking area is double-buffered: the ordered sum of tile k-1 runs while the loads
-//     of tile k are in flight, so only the last tile's sum is exposed.
+//     of tile k are in flight, so only the last tile's sum is exposed;
+//   * on whole shapes (UNITS > 0 below) the next tile's loads are issued ahead of the barrier
+//     and the ordered sum follows half a tile behind.
 constexpr int kLdsBlock = 1024;
 constexpr int kLdsWaves = kLdsBlock / 64;
 constexpr int kLdsBatch = 8;  // sources per batch when the per-node count is not a template constant
@@ -160,7 +162,10 @@ __device__ __forceinline__ float ordered_sum(const float* parked, int tn, bool f
   return acc;
 }
 
-template <int IN, int OUT, int M, int NPT = lds_npt(M, narrow(IN))>
+// UNITS > 0 (chosen by the host): every tile is whole (nodes a multiple of TN), every slice is
+// whole (count a multiple of E) and every source starts on a 32-bit word, so no load needs a
+// check; a wave's share of a tile is then loaded, summed and chained in UNITS parts (below).
+template <int IN, int OUT, int M, int NPT = lds_npt(M, narrow(IN)), int UNITS = 0>
 __global__ __launch_bounds__(kLdsBlock) void k_reduce2l_lds(ReduceProblem p) {
   constexpr int EPL = narrow(IN) ? 2 : 1;
   constexpr int E = 64 * EPL;
@@ -186,7 +191,98 @@ __global__ __launch_bounds__(kLdsBlock) void k_reduce2l_lds(ReduceProblem p) {
   };
 
   float acc = 0.0f;
-  if constexpr (M > 0) {
+  if constexpr (M > 0 && UNITS > 0) {
+    // A wave's NPT nodes of a tile are loaded and summed in UNITS parts, and the loads of the NEXT
+    // tile's part are issued as soon as the registers of this tile's are free -- ahead of the
+    // barrier -- so a wave always has nearly a whole tile of loads in flight and the memory
+    // pipeline of the CU does not drain at a tile boundary (one 1024-thread block per CU: nothing
+    // else would fill such a gap).  Part u of all waves together is nodes [u*UT, (u+1)*UT) of the
+    // tile, so the ordered sum runs one part behind the loads and only the last part's is
+    // exposed.  Addresses are fetched two tiles ahead, so that the fetch is older than the loads
+    // it would otherwise wait behind (loads return in order).
+    static_assert(NPT % UNITS == 0, "whole parts");
+    constexpr int H = NPT / UNITS;  // nodes of a wave in one part
+    constexpr int UT = TN / UNITS;  // nodes of the tile in one part
+    // Lane l < NPT*M holds source (node, l % M), node = part (q / H), place wave*H + q % H in it,
+    // q = l / M.  No branch around the load and no use of its result here (either would make the
+    // wave wait for every load ahead of it): lanes past NPT*M repeat the last source, and the
+    // caller's own-slot override is applied by `resolve` when the addresses are used, a tile later.
+    const int l = lane < NPT * M ? lane : NPT * M - 1;
+    const int lq = l / M, lg = l % M;
+    const int lnode = (lq / H) * UT + wave * H + lq % H;
+    auto fetch = [&](int tile) -> uint64_t {
+      const int n = tile * TN + lnode;
+      if (p.ptrs != nullptr) return reinterpret_cast<uint64_t>(ld_pointer_lane(p.ptrs, (size_t)n * M + lg));
+      return reinterpret_cast<uint64_t>(p.base + (size_t)n * p.stride_n + (size_t)lg * p.stride_g);
+    };
+    auto resolve = [&](uint64_t a, int tile) -> uint64_t {
+      const int s = (tile * TN + lnode) * M + lg;
+      return (p.ptrs != nullptr && s == p.override_index) ? reinterpret_cast<uint64_t>(p.override_ptr) : a;
+    };
+    // part u of this wave's share: lanes (u*H + q)*M + g
+    auto issue = [&](float (&x)[H][MM][EPL], uint64_t a, int u) {
+#pragma unroll
+      for (int q = 0; q < H; ++q)
+#pragma unroll
+        for (int g = 0; g < MM; ++g)
+          ld_word<IN, EPL, false>(lane_pointer(a, (u * H + q) * M + g), le, p.count, x[q][g]);
+    };
+    auto sum_park = [&](float* buf, const float (&x)[H][MM][EPL], int u) {
+#pragma unroll
+      for (int q = 0; q < H; ++q) {
+        float t[EPL];
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) {
+          t[e] = x[q][0][e];
+#pragma unroll
+          for (int g = 1; g < MM; ++g) t[e] = t[e] + x[q][g][e];
+        }
+        park(buf, u * UT + wave * H + q, t);
+      }
+    };
+    // acc (+)= the UT parked partials of one element, ascending node order, 16 reads at a time
+    static_assert(UT % 16 == 0, "whole rounds of 16");
+    auto chain = [&](const float* part, bool first) {
+#pragma unroll
+      for (int j0 = 0; j0 < UT; j0 += 16) {
+        float v[16];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) v[j] = part[(j0 + j) * E + threadIdx.x];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) acc = (first && j0 + j == 0) ? v[j] : acc + v[j];
+      }
+    };
+    uint64_t nxt = ntiles > 1 ? fetch(1) : 0;
+    float x[UNITS][H][MM][EPL];
+    {
+      const uint64_t cur = resolve(fetch(0), 0);
+#pragma unroll
+      for (int u = 0; u < UNITS; ++u) issue(x[u], cur, u);
+    }
+    for (int k = 0; k + 1 < ntiles; ++k) {
+      float* buf = parked[k & 1];
+      const uint64_t nn = k + 2 < ntiles ? fetch(k + 2) : 0;
+      const uint64_t a = resolve(nxt, k + 1);
+#pragma unroll
+      for (int u = 0; u < UNITS; ++u) {
+        sum_park(buf, x[u], u);
+        issue(x[u], a, u);
+        __syncthreads();
+        if (threadIdx.x < E) chain(buf + u * UT * E, k == 0 && u == 0);
+      }
+      nxt = nn;
+    }
+    {
+      const int k = ntiles - 1;
+      float* buf = parked[k & 1];
+#pragma unroll
+      for (int u = 0; u < UNITS; ++u) {
+        sum_park(buf, x[u], u);
+        __syncthreads();
+        if (threadIdx.x < E) chain(buf + u * UT * E, k == 0 && u == 0);
+      }
+    }
+  } else if constexpr (M > 0) {
     // lane l < NPT*M of wave w holds the address of source (tile*TN + w*NPT + l/M, l%M)
     auto fetch = [&](int tile) -> uint64_t {
       const int n = tile * TN + wave * NPT + lane / M;
@@ -261,7 +357,7 @@ __global__ __launch_bounds__(kLdsBlock) void k_reduce2l_lds(ReduceProblem p) {
   }
   if (threadIdx.x < E) {
     const int last = ntiles - 1;
-    acc = ordered_sum<E>(parked[last & 1], p.nodes - last * TN, last == 0, acc);
+    if constexpr (!(M > 0 && UNITS > 0)) acc = ordered_sum<E>(parked[last & 1], p.nodes - last * TN, last == 0, acc);
     if (p.divisor != 0.0f) acc = acc / p.divisor;
     if (e0 + threadIdx.x < p.count)
       st_elem<OUT>(reinterpret_cast<char*>(p.dst), e0 + threadIdx.x, acc);
@@ -276,15 +372,36 @@ hipError_t launch_lds_m(const ReduceProblem& p, hipStream_t st) {
   if (p.nodes > (1 << 30) || (size_t)p.nodes * (size_t)p.gpus > ((size_t)1 << 30)) return hipErrorInvalidValue;
   unsigned gx, gz;
   if (!split_grid_xz(blocks, kLdsBlock, &gx, &gz)) return hipErrorInvalidValue;
+  // Whole tiles, whole slices and sources on 32-bit words (fp32 sources are by their type; 16-bit
+  // ones only when they are strided from an aligned base: a pointer array cannot be inspected
+  // here): the variant that loads, sums and chains a tile in two parts and keeps loads in flight
+  // across the tile boundary.  2048 x 64 KB of fp32: 23.35 us against 24.9 us back to back.
+  // PCCL_TWO_LEVEL_PIPE=0 keeps the plain loop (tests run both).
+  auto piped_ok = [&](int npt) {
+    const bool words = !narrow(IN) || (p.ptrs == nullptr && reinterpret_cast<uintptr_t>(p.base) % 4 == 0 &&
+                                       p.stride_n % 4 == 0 && p.stride_g % 4 == 0);
+    return knobs().two_level_pipe && words && p.nodes % (kLdsWaves * npt) == 0 && p.count % E == 0;
+  };
+  const dim3 grid(gx, 1, gz), blk(kLdsBlock);
   if constexpr (M == 8 && !narrow(IN)) {
     // 2048 ranks x 64 KB of fp32: eight nodes per wavefront and tile (64 loads in flight per lane, two
     // barriers fewer) measured 24.5 us against 25.1 us with four; PCCL_TWO_LEVEL_NPT=4 keeps the four for A/B runs
     if (knobs().two_level_npt != 4) {
-      hipLaunchKernelGGL((k_reduce2l_lds<IN, OUT, M, 8>), dim3(gx, 1, gz), dim3(kLdsBlock), 0, st, p);
+      if (piped_ok(8))
+        hipLaunchKernelGGL((k_reduce2l_lds<IN, OUT, M, 8, 2>), grid, blk, 0, st, p);
+      else
+        hipLaunchKernelGGL((k_reduce2l_lds<IN, OUT, M, 8>), grid, blk, 0, st, p);
       return hipGetLastError();
     }
   }
-  hipLaunchKernelGGL((k_reduce2l_lds<IN, OUT, M>), dim3(gx, 1, gz), dim3(kLdsBlock), 0, st, p);
+  if constexpr (M > 0) {
+    constexpr int NPT = lds_npt(M, narrow(IN));
+    if (piped_ok(NPT)) {
+      hipLaunchKernelGGL((k_reduce2l_lds<IN, OUT, M, NPT, 2>), grid, blk, 0, st, p);
+      return hipGetLastError();
+    }
+  }
+  hipLaunchKernelGGL((k_reduce2l_lds<IN, OUT, M>), grid, blk, 0, st, p);
   return hipGetLastError();
 }
 

@@ -42,8 +42,9 @@ class Guarded:
         self.numel = numel
         self.lo = self.GUARD + offset_elems
         total = self.lo + numel + self.GUARD
-        int_dt = torch.int16 if dtype == torch.bfloat16 else torch.int32
-        self.poison = 0x7FC1 if dtype == torch.bfloat16 else 0x7FC12345
+        narrow = dtype in (torch.bfloat16, torch.float16)
+        int_dt = torch.int16 if narrow else torch.int32
+        self.poison = 0x7FC1 if narrow else 0x7FC12345   # a NaN in every one of the three formats
         raw = torch.full((total,), self.poison, dtype=int_dt, device=device)
         self.raw = raw
         self.view = raw.view(dtype)[self.lo:self.lo + numel]
