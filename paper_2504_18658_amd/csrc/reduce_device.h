@@ -283,6 +283,27 @@ __device__ __forceinline__ uint64_t lds_lane_src(const ReduceProblem& p, int n, 
   return reinterpret_cast<uint64_t>(p.base + (size_t)n * p.stride_n + (size_t)g * p.stride_g);
 }
 
+// The same in two steps for loops that fetch the addresses of the NEXT tile while this tile's
+// loads are in flight.  Loads return in order, so a branch around the fetch or any use of its
+// result right behind it makes the wave wait for every load ahead of the fetch.  lane_src_fetch
+// therefore always loads (lanes without a source read slot 0 of the table; no entry read this
+// way is ever dereferenced) and lane_src_resolve applies "no source" and the caller's own-slot
+// override where the addresses are first used, a tile later.
+__device__ __forceinline__ uint64_t lane_src_fetch(const ReduceProblem& p, int n, int g, int gpus,
+                                                   bool valid) {
+  if (p.ptrs != nullptr) {
+    const size_t s = valid ? (size_t)n * gpus + g : 0;
+    return reinterpret_cast<uint64_t>(ld_pointer_lane(p.ptrs, s));
+  }
+  return reinterpret_cast<uint64_t>(p.base + (size_t)n * p.stride_n + (size_t)g * p.stride_g);
+}
+__device__ __forceinline__ uint64_t lane_src_resolve(const ReduceProblem& p, uint64_t a, int n, int g,
+                                                     int gpus, bool valid) {
+  const bool own = p.ptrs != nullptr && (int)((size_t)n * gpus + g) == p.override_index;
+  const uint64_t r = own ? reinterpret_cast<uint64_t>(p.override_ptr) : a;
+  return valid ? r : 0;
+}
+
 // Lane `l`'s 64-bit value as a wave-uniform pointer.
 __device__ __forceinline__ const char* lane_pointer(uint64_t v, int l) {
   const uint32_t lo = __builtin_amdgcn_readlane((int)(uint32_t)v, l);
@@ -341,7 +362,11 @@ __device__ __forceinline__ void flat_lds_slice(const ReduceProblem& p, size_t sl
   // lane l < 8 of wave w holds the address of source tile*TN + w*8 + l
   auto fetch = [&](int tile) -> uint64_t {
     const int n = tile * TN + wave * kFlatNpt + lane;
-    return lds_lane_src(p, n, 0, 1, lane < kFlatNpt && n < nsrc);
+    return lane_src_fetch(p, n, 0, 1, lane < kFlatNpt && n < nsrc);
+  };
+  auto resolve = [&](uint64_t a, int tile) -> uint64_t {
+    const int n = tile * TN + wave * kFlatNpt + lane;
+    return lane_src_resolve(p, a, n, 0, 1, lane < kFlatNpt && n < nsrc);
   };
   // acc (+)= the tn parked words of this lane, ascending source order
   float acc[EPL];
@@ -369,9 +394,9 @@ __device__ __forceinline__ void flat_lds_slice(const ReduceProblem& p, size_t sl
     }
   };
 
-  uint64_t cur = fetch(0);
+  uint64_t cur = resolve(fetch(0), 0);
   for (int k = 0; k < ntiles; ++k) {
-    const uint64_t nxt = k + 1 < ntiles ? fetch(k + 1) : 0;
+    const uint64_t nxt = k + 1 < ntiles ? fetch(k + 1) : 0;  // resolved at the bottom of the loop
     const int nvalid = min(kFlatNpt, max(0, nsrc - (k * TN + wave * kFlatNpt)));  // wave-uniform
     uint32_t raw[kFlatNpt];
     if (nvalid == kFlatNpt && slice_full && !__any((int)(cur & 3))) {
@@ -442,7 +467,7 @@ __device__ __forceinline__ void flat_lds_slice(const ReduceProblem& p, size_t sl
 #pragma unroll
     for (int q = 0; q < kFlatNpt; ++q)
       if (q < nvalid) buf[(wave * kFlatNpt + q) * 64 + lane] = raw[q];
-    cur = nxt;
+    cur = resolve(nxt, k + 1);
     __syncthreads();
   }
   if (wave == 0) {

@@ -286,12 +286,16 @@ __global__ __launch_bounds__(kLdsBlock) void k_reduce2l_lds(ReduceProblem p) {
     // lane l < NPT*M of wave w holds the address of source (tile*TN + w*NPT + l/M, l%M)
     auto fetch = [&](int tile) -> uint64_t {
       const int n = tile * TN + wave * NPT + lane / M;
-      return lds_lane_src(p, n, lane % M, M, lane < NPT * M && n < p.nodes);
+      return lane_src_fetch(p, n, lane % M, M, lane < NPT * M && n < p.nodes);
     };
-    uint64_t cur = fetch(0);
+    auto resolve = [&](uint64_t a, int tile) -> uint64_t {
+      const int n = tile * TN + wave * NPT + lane / M;
+      return lane_src_resolve(p, a, n, lane % M, M, lane < NPT * M && n < p.nodes);
+    };
+    uint64_t cur = resolve(fetch(0), 0);
     for (int k = 0; k < ntiles; ++k) {
       float* buf = parked[k & 1];
-      const uint64_t nxt = k + 1 < ntiles ? fetch(k + 1) : 0;
+      const uint64_t nxt = k + 1 < ntiles ? fetch(k + 1) : 0;  // resolved at the bottom of the loop
       const int nvalid = min(NPT, max(0, p.nodes - (k * TN + wave * NPT)));  // wave-uniform
       float x[NPT][MM][EPL];
       const bool plain = nvalid == NPT && slice_full && !__any((int)(cur & 3));
@@ -325,7 +329,7 @@ __global__ __launch_bounds__(kLdsBlock) void k_reduce2l_lds(ReduceProblem p) {
           }
           park(buf, wave * NPT + q, t);
         }
-      cur = nxt;
+      cur = resolve(nxt, k + 1);
       __syncthreads();
     }
   } else {
