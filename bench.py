@@ -159,6 +159,29 @@ def back_to_back(fn_list, launches=24, warm=4):
     return a.elapsed_time(b) * 1e3 / launches
 
 
+def graph_replay_us(fn_list, rounds, replays=20):
+    """Microseconds per call when `rounds` passes over fn_list are captured in one HIP graph and the
+    graph is replayed (a launch-bound call issued from Python is bound by the host, not by the GPU)."""
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        for fn in fn_list:
+            fn()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        for _ in range(rounds):
+            for fn in fn_list:
+                fn()
+    for _ in range(3):
+        g.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(replays):
+        g.replay()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / (replays * rounds * len(fn_list)) * 1e6
+
+
 def other_workloads(dev):
     """The remaining configurations, each timed on its own (10 trials, rotating buffer sets)."""
     res = {}
@@ -176,9 +199,10 @@ def other_workloads(dev):
     w = W.cfg1()
     sets = [(torch.empty(w.chunk, dtype=w.dtype, device=dev),
              W.draw(w, w.gpus * w.chunk, dev, seed_offset=k).view(w.gpus, w.chunk)) for k in range(8)]
-    entry("cfg1_flat_reduce_p8_f32_512KB", (w.gpus + 1) * w.chunk * 4,
-          *time_calls([lambda s=s: pccl.pccl_local_reduce(s[0], s[1]) for s in sets]))
-    del sets
+    fns = [lambda s=s: pccl.pccl_local_reduce(s[0], s[1]) for s in sets]
+    entry("cfg1_flat_reduce_p8_f32_512KB", (w.gpus + 1) * w.chunk * 4, *time_calls(fns),
+          graph_replay_us=round(graph_replay_us(fns, 4), 2))
+    del sets, fns
     # cfg2: all-gather reassembly, 4 x 8, 64 MB bf16
     w = W.cfg2()
     n = w.ranks * w.chunk
