@@ -368,8 +368,9 @@ def fused_leg(dev, steps, warmup, nsets=4, my_node=5, my_gpu=3):
     rank-order 256 MB messages through the node stride (pccl_reduce_scatter_local_unpacked with no shard:
     no pccl_hier_pack pass, 512 MB less traffic), then pccl_phase2_reassemble_local sums the inter-node
     phase straight into the rank's own chunk of the all-gather result while the other chunks are shuffled
-    in (no separate phase-2 launch, no copy of the shard).  Timed next to the three-launch form
-    (pccl_reduce_scatter_local_unpacked + pccl_allgather_reassemble)."""
+    in (no separate phase-2 launch, no copy of the shard).  Timed next to the other two-launch form, the
+    whole share in one launch and a plain reassemble (pccl_reduce_scatter_local_unpacked with received
+    chunks + pccl_allgather_reassemble), which moves the shard once more."""
     w = W.cfg3()
     n = w.ranks * w.chunk
     sets = []
@@ -395,7 +396,7 @@ def fused_leg(dev, steps, warmup, nsets=4, my_node=5, my_gpu=3):
         phase1(s)
         tail(s)
 
-    def run_three_launches(s):
+    def run_share_then_reassemble(s):
         pccl.pccl_reduce_scatter_local_unpacked(s["shard"], s["partial"], msgs=s["msgs"], d_inter=s["d_inter"],
                                                 nodes=w.nodes, gpus_per_node=w.gpus, my_node=my_node, my_gpu=my_gpu)
         pccl.pccl_allgather_reassemble(s["out"], src=s["gathered"], nodes=w.nodes, gpus_per_node=w.gpus)
@@ -410,13 +411,17 @@ def fused_leg(dev, steps, warmup, nsets=4, my_node=5, my_gpu=3):
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) * 1e3 / steps
 
-    ms, ms3 = wall(run), wall(run_three_launches)
+    ms, ms3 = wall(run), wall(run_share_then_reassemble)
     e = w.esize
     p1_bytes = (w.gpus + 1) * w.nodes * w.chunk * e
     tail_bytes = (w.nodes + 1) * w.chunk * e + 2 * (n - w.chunk) * e     # the own chunk is summed, not copied
     nbytes = p1_bytes + tail_bytes
     p1_us = back_to_back([lambda s=s: phase1(s) for s in sets])
     tail_us = back_to_back([lambda s=s: tail(s) for s in sets])
+    share_us = back_to_back([lambda s=s: pccl.pccl_reduce_scatter_local_unpacked(
+        s["shard"], s["partial"], msgs=s["msgs"], d_inter=s["d_inter"], nodes=w.nodes, gpus_per_node=w.gpus,
+        my_node=my_node, my_gpu=my_gpu) for s in sets])
+    share_bytes = p1_bytes + (w.nodes + 1) * w.chunk * e
     return dict(what="pccl_reduce_scatter_local_unpacked (phase 1 only, no pccl_hier_pack pass) + "
                      "pccl_phase2_reassemble_local (inter-node phase and all-gather shuffle in one launch)",
                 launches_per_step=2, ms_per_step=round(ms, 4), algorithmic_bytes_per_step=nbytes,
@@ -424,7 +429,9 @@ def fused_leg(dev, steps, warmup, nsets=4, my_node=5, my_gpu=3):
                 phase1_from_rank_order_messages_us=round(p1_us, 2),
                 phase1_from_rank_order_messages_GBps=round(p1_bytes / (p1_us * 1e-6) / 1e9, 1),
                 phase2_reassemble_us=round(tail_us, 2), phase2_reassemble_GBps=round(tail_bytes / (tail_us * 1e-6) / 1e9, 1),
-                three_launch_form_ms_per_step=round(ms3, 4))
+                whole_share_from_rank_order_messages_us=round(share_us, 2),
+                whole_share_from_rank_order_messages_GBps=round(share_bytes / (share_us * 1e-6) / 1e9, 1),
+                share_then_reassemble_ms_per_step=round(ms3, 4))
 
 
 def size_sweep(dev, sizes_mb=(64, 128, 256)):

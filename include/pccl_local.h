@@ -188,7 +188,7 @@ pccl_status_t pccl_reduce_scatter_local(void* shard, void* partial, const void* 
  * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc -- and so have
  * no `partial` buffer to hand over: the phase-1 result is kept in a workspace inside the
  * library, a static device array of PCCL_STATIC_SCRATCH_BYTES bytes (one copy on every GPU the
- * library runs on, held until the process ends).  Everything else -- arguments, the two
+ * library runs on, held until the process ends).  Everything else -- arguments, the
  * kernels, the order of the sums, the bits of `shard` -- is as in pccl_reduce_scatter_local.
  * The call allocates and frees nothing and runs no checked-mode queries, whatever
  * PCCL_CHECK_POINTERS says; its first use on a device asks the runtime for the workspace's
@@ -216,7 +216,8 @@ pccl_status_t pccl_reduce_scatter_local_static(void* shard, const void* intra_ba
  * bound for local id my_gpu on every node, read through the node stride.  Everything else
  * (partial, shard, d_inter, my_node, order of the sums) is as in pccl_reduce_scatter_local,
  * and the results are bit-identical to packing every message first (shard == NULL: phase 1
- * only, as there).
+ * only, as there).  One kernel when d_inter is given and the messages are strided (d_msgs ==
+ * NULL), under the conditions stated there; else one per phase.
  * Errors: as there; my_gpu outside [0, gpus_per_node); nodes > 65535. */
 pccl_status_t pccl_reduce_scatter_local_unpacked(void* shard, void* partial, const void* msgs_base,
                                                  size_t msg_stride_bytes,

@@ -70,10 +70,13 @@ struct FusedShape {
 // One two-level reduce-scatter share with received inter-node chunks, for the one-launch form:
 // pieces g at intra_base + g*intra_stride, each [nodes][chunk_count] of the message dtype;
 // partial [nodes][chunk_count]; inter[n] for n != my_node from the device pointer array.
+// own_src (the rows form only): source 0's chunk of the own node, the other sources intra_stride
+// apart; in the contiguous form it is intra_base + my_node * chunk bytes.
 struct ShareProblem {
   void* shard;
   void* partial;
   const char* intra_base;
+  const char* own_src;
   const void* const* d_inter;
   size_t intra_stride;
   size_t chunk_count;
@@ -100,6 +103,10 @@ hipError_t launch_reduce_two_level_lds(const ReduceProblem& p, int in_dt, int ou
 // (the caller then launches phase by phase), other errors as above.
 constexpr int kShareFusedMaxNodes = 16;
 hipError_t launch_share_fused(const ShareProblem& s, int dt, bool any_shape, hipStream_t st);
+// The same for a share read straight from rank-order messages: `rows` is the phase-1 problem as
+// launch_reduce takes it (rows = nodes, strided sources only; s.own_src = row my_node's source 0).
+hipError_t launch_share_rows_fused(const ShareProblem& s, const ReduceProblem& rows, int dt, bool any_shape,
+                                   hipStream_t st);
 // True when the LDS-staged kernel is the better choice for this shape.
 bool prefer_lds_two_level(const ReduceProblem& p, int in_dt);
 // A flat sum written as p.nodes sources (p.gpus == 1, one row, no partial kept) through the

@@ -268,6 +268,7 @@ pccl_status_t launch_share(void* shard, void* partial, const void* intra_base, s
     sp.shard = shard;
     sp.partial = partial;
     sp.intra_base = reinterpret_cast<const char*>(intra_base);
+    sp.own_src = sp.intra_base + (size_t)my_node * z.chunk_bytes;
     sp.d_inter = d_inter;
     sp.intra_stride = gpus_per_node > 1 ? intra_stride_bytes : 0;
     sp.chunk_count = chunk_count;
@@ -545,6 +546,24 @@ pccl_status_t pccl_reduce_scatter_local_unpacked(void* shard, void* partial, con
     p1.ptrs = d_msgs;
     p1.src_offset = (size_t)my_gpu * chunk_bytes;
     p1.row_pad = 1;  // the messages' addresses are on the device
+  }
+  // With the other nodes' chunks at hand and strided messages, one launch does both phases: the
+  // blocks of row my_node go on to add the received chunks (as in pccl_reduce_scatter_local).
+  if (d_inter != nullptr && shard != nullptr && d_msgs == nullptr && pccl::knobs().share_launches != 2) {
+    pccl::ShareProblem sp;
+    sp.shard = shard;
+    sp.partial = partial;
+    sp.intra_base = p1.base;
+    sp.own_src = p1.base + (size_t)my_node * node_bytes;
+    sp.d_inter = d_inter;
+    sp.intra_stride = p1.stride_g;
+    sp.chunk_count = chunk_count;
+    sp.nodes = nodes;
+    sp.gpus = gpus_per_node;
+    sp.my_node = my_node;
+    sp.divisor = divisor;
+    const hipError_t f = pccl::launch_share_rows_fused(sp, p1, dt, pccl::knobs().share_launches == 1, st);
+    if (f != hipErrorNotSupported) return f == hipErrorInvalidValue ? PCCL_ERR_INVALID : from_hip(f);
   }
   const hipError_t e = pccl::launch_reduce(p1, dt, dt, st);
   if (e != hipSuccess) return e == hipErrorInvalidValue ? PCCL_ERR_INVALID : PCCL_ERR_HIP;

@@ -23,29 +23,37 @@ namespace pccl {
 
 namespace {
 
+// Tile `tile` of row `row` of a launch over strided rows (the share straight from rank-order
+// messages): rows start at rotated tiles, and a row that may start off a cache line is shifted
+// so that wavefront loads start on line boundaries.
 template <int IN, int OUT, int M, bool FAST, int BLOCK>
-__global__ __launch_bounds__(BLOCK) void k_reduce(ReduceProblem p) {
-  size_t tile = linear_block_xz();
+__device__ __forceinline__ void reduce_row_tile(ReduceProblem p, size_t tile, size_t row) {
+  constexpr size_t VE = (size_t)words_for(M) * (narrow(IN) ? 2 : 1);
+  const size_t nvec = p.count / VE;
+  size_t ntiles = (nvec + BLOCK - 1) / BLOCK;
+  if (ntiles == 0) ntiles = 1;       // a lone ragged tail
+  ntiles += p.row_pad;               // room for the line shift below
+  if (tile >= ntiles) return;        // the x*z rectangle is rounded up
   size_t shift = 0, head = 0;
-  if (gridDim.y > 1) {
-    constexpr size_t VE = (size_t)words_for(M) * (narrow(IN) ? 2 : 1);
-    const size_t nvec = p.count / VE;
-    size_t ntiles = (nvec + BLOCK - 1) / BLOCK;
-    if (ntiles == 0) ntiles = 1;       // a lone ragged tail
-    ntiles += p.row_pad;               // room for the line shift below
-    if (tile >= ntiles) return;        // the x*z rectangle is rounded up
-    const size_t row = blockIdx.y;
-    tile = (tile + row * kRowSkewTiles) % ntiles;
-    p.base += row * p.row_stride_src;
-    p.src_offset += row * p.row_stride_src;
-    p.dst = reinterpret_cast<char*>(p.dst) + row * p.row_stride_dst;
-    if (p.row_pad) {
-      const char* row_start = src_ptr<FAST>(p, 0, 0);
-      head = word_head<IN>(row_start);
-      shift = line_shift<4 * words_for(M)>(row_start + 2 * head);
-    }
+  tile = (tile + row * kRowSkewTiles) % ntiles;
+  p.base += row * p.row_stride_src;
+  p.src_offset += row * p.row_stride_src;
+  p.dst = reinterpret_cast<char*>(p.dst) + row * p.row_stride_dst;
+  if (p.row_pad) {
+    const char* row_start = src_ptr<FAST>(p, 0, 0);
+    head = word_head<IN>(row_start);
+    shift = line_shift<4 * words_for(M)>(row_start + 2 * head);
   }
   reduce_tile<IN, OUT, M, words_for(M), FAST, BLOCK>(p, tile, shift, head);
+}
+
+template <int IN, int OUT, int M, bool FAST, int BLOCK>
+__global__ __launch_bounds__(BLOCK) void k_reduce(ReduceProblem p) {
+  const size_t tile = linear_block_xz();
+  if (gridDim.y > 1)
+    reduce_row_tile<IN, OUT, M, FAST, BLOCK>(p, tile, blockIdx.y);
+  else
+    reduce_tile<IN, OUT, M, words_for(M), FAST, BLOCK>(p, tile, 0, 0);
 }
 
 // strided sources with every base, stride, row and output 16-byte aligned
@@ -488,7 +496,7 @@ __device__ __forceinline__ void own_row_tile(const ShareProblem& s, size_t tile)
   constexpr int NMAX = kShareFusedMaxNodes;
   const size_t count = s.chunk_count;
   const size_t row_off = (size_t)s.my_node * count * ES;
-  const char* own = s.intra_base + row_off;
+  const char* own = s.own_src;
   char* prow = reinterpret_cast<char*>(s.partial) + row_off;
   char* shard = reinterpret_cast<char*>(s.shard);
   const size_t nvec = count / VE;
@@ -657,6 +665,52 @@ hipError_t launch_share_dt(const ShareProblem& s, hipStream_t st) {
     case 4: return launch_share_m<DT, 4>(s, st);
     case 8: return launch_share_m<DT, 8>(s, st);
     case 16: return launch_share_m<DT, 16>(s, st);
+    default: return hipErrorNotSupported;
+  }
+}
+
+// The same over the rows of rank-order messages: plane y = 0 holds the own row's tiles (phase 1
+// and phase 2; first in dispatch order), plane y > 0 row y - 1, or y past the own row.
+template <int DT, int M, bool FAST, bool MANY>
+__global__ __launch_bounds__(kBlockSmall) void k_share_rows_fused(ShareProblem s, ReduceProblem rows) {
+  const size_t tile = linear_block_xz();
+  if (blockIdx.y == 0) {
+    own_row_tile<DT, M, FAST, kBlockSmall, MANY>(s, tile);  // tiles past the row's last find nothing to do
+    return;
+  }
+  const size_t row = (int)blockIdx.y - 1 < s.my_node ? blockIdx.y - 1 : blockIdx.y;
+  reduce_row_tile<DT, DT, M, FAST, kBlockSmall>(rows, tile, row);
+}
+
+template <int DT, int M>
+hipError_t launch_share_rows_m(const ShareProblem& s, const ReduceProblem& rows, hipStream_t st) {
+  const size_t es = narrow(DT) ? 2 : 4;
+  const size_t tiles = tiles_for(rows.count, M, narrow(DT), kBlockSmall) + rows.row_pad;
+  unsigned gx, gz;
+  if (rows.rows < 1 || rows.rows > 65535 || !split_grid_xz(tiles, kBlockSmall, &gx, &gz)) return hipErrorInvalidValue;
+  const bool fast = fast_eligible(rows, narrow(DT)) && is16(s.shard) && is16(s.own_src) && s.intra_stride % 16 == 0 &&
+                    (s.chunk_count * es) % 16 == 0;
+  const bool many = s.nodes > kShareFusedMaxNodes;
+  const dim3 grid(gx, (unsigned)rows.rows, gz), blk(kBlockSmall);
+  if (fast && !many)
+    hipLaunchKernelGGL((k_share_rows_fused<DT, M, true, false>), grid, blk, 0, st, s, rows);
+  else if (fast)
+    hipLaunchKernelGGL((k_share_rows_fused<DT, M, true, true>), grid, blk, 0, st, s, rows);
+  else if (!many)
+    hipLaunchKernelGGL((k_share_rows_fused<DT, M, false, false>), grid, blk, 0, st, s, rows);
+  else
+    hipLaunchKernelGGL((k_share_rows_fused<DT, M, false, true>), grid, blk, 0, st, s, rows);
+  return hipGetLastError();
+}
+
+template <int DT>
+hipError_t launch_share_rows_dt(const ShareProblem& s, const ReduceProblem& rows, hipStream_t st) {
+  switch (pick_m(s.gpus)) {
+    case 1: return launch_share_rows_m<DT, 1>(s, rows, st);
+    case 2: return launch_share_rows_m<DT, 2>(s, rows, st);
+    case 4: return launch_share_rows_m<DT, 4>(s, rows, st);
+    case 8: return launch_share_rows_m<DT, 8>(s, rows, st);
+    case 16: return launch_share_rows_m<DT, 16>(s, rows, st);
     default: return hipErrorNotSupported;
   }
 }
@@ -883,6 +937,20 @@ hipError_t launch_reduce_flat_lds(const ReduceProblem& p, int in_dt, int out_dt,
   PCCL_DISPATCH_IO(launch_flat_lds_io, in_dt, out_dt, p, st);
 }
 
+// Beyond kShareFusedMaxNodes nodes: is phase 1 long enough to cover the own row's walk?
+bool share_fused_pays(const ShareProblem& s, int dt);
+
+hipError_t launch_share_rows_fused(const ShareProblem& s, const ReduceProblem& rows, int dt, bool any_shape,
+                                   hipStream_t st) {
+  if (s.d_inter == nullptr || s.chunk_count == 0 || rows.ptrs != nullptr || rows.partial != nullptr)
+    return hipErrorNotSupported;
+  if (!any_shape && !share_fused_pays(s, dt)) return hipErrorNotSupported;
+  if (dt == kF32) return launch_share_rows_dt<kF32>(s, rows, st);
+  if (dt == kBF16) return launch_share_rows_dt<kBF16>(s, rows, st);
+  if (dt == kF16) return launch_share_rows_dt<kF16>(s, rows, st);
+  return hipErrorInvalidValue;
+}
+
 hipError_t launch_share_fused(const ShareProblem& s, int dt, bool any_shape, hipStream_t st) {
   if (s.d_inter == nullptr || s.chunk_count == 0) return hipErrorNotSupported;
   // Beyond kShareFusedMaxNodes nodes a block of the own row walks the received chunks in rounds, each
@@ -890,16 +958,19 @@ hipError_t launch_share_fused(const ShareProblem& s, int dt, bool any_shape, hip
   // cover that chain.  Measured, bf16, 8 per node, one launch against two: 256 MB at 32-256 nodes
   // 52-53 against 57-59 us; 64 MB at 64 nodes 16.9 against 17.7, at 128 nodes 21.3 against 18.5;
   // 16 MB at 64 nodes 10.3 against 8.3.
-  if (s.nodes > kShareFusedMaxNodes && !any_shape) {
-    const size_t rounds = ((size_t)s.nodes + kShareFusedMaxNodes - 1) / kShareFusedMaxNodes;
-    const size_t es = (dt == kF32) ? 4 : 2;
-    const size_t phase1_in = (size_t)s.gpus * s.nodes * s.chunk_count * es;
-    if (phase1_in < rounds * ((size_t)10 << 20)) return hipErrorNotSupported;
-  }
+  if (!any_shape && !share_fused_pays(s, dt)) return hipErrorNotSupported;
   if (dt == kF32) return launch_share_dt<kF32>(s, st);
   if (dt == kBF16) return launch_share_dt<kBF16>(s, st);
   if (dt == kF16) return launch_share_dt<kF16>(s, st);
   return hipErrorInvalidValue;
+}
+
+bool share_fused_pays(const ShareProblem& s, int dt) {
+  if (s.nodes <= kShareFusedMaxNodes) return true;
+  const size_t rounds = ((size_t)s.nodes + kShareFusedMaxNodes - 1) / kShareFusedMaxNodes;
+  const size_t es = (dt == kF32) ? 4 : 2;
+  const size_t phase1_in = (size_t)s.gpus * s.nodes * s.chunk_count * es;
+  return phase1_in >= rounds * ((size_t)10 << 20);
 }
 
 bool prefer_flat_lds(const ReduceProblem& p, int in_dt) {
