@@ -109,6 +109,9 @@ hipError_t launch_share_rows_fused(const ShareProblem& s, const ReduceProblem& r
                                    hipStream_t st);
 // True when the LDS-staged kernel is the better choice for this shape.
 bool prefer_lds_two_level(const ReduceProblem& p, int in_dt);
+// True when a flat sum of many short sources (p.gpus == 1, p.nodes sources) is better sent through
+// the two-level LDS kernel than through the flat LDS kernel.
+bool prefer_two_level_for_flat(const ReduceProblem& p, int in_dt);
 // A flat sum written as p.nodes sources (p.gpus == 1, one row, no partial kept) through the
 // LDS-staged flat kernel: every load of an element slice in flight at once.
 hipError_t launch_reduce_flat_lds(const ReduceProblem& p, int in_dt, int out_dt, hipStream_t st);

@@ -166,9 +166,10 @@ hipError_t launch_flat(const ReduceProblem& p, int in_dt, int out_dt, hipStream_
   q.stride_g = 0;
   if (p.rows == 1 && p.partial == nullptr) {
     const int forced = pccl::knobs().flat_kernel;  // 1 streaming, 2 two-level LDS, 3 flat LDS: pinned for tests
-    if (forced == 3 || (forced == 0 && pccl::prefer_flat_lds(q, in_dt)))
-      return pccl::launch_reduce_flat_lds(q, in_dt, out_dt, st);
-    if (forced == 2) return pccl::launch_reduce_two_level_lds(q, in_dt, out_dt, st);
+    const bool lds = forced == 0 && pccl::prefer_flat_lds(q, in_dt);
+    if (forced == 2 || (lds && pccl::prefer_two_level_for_flat(q, in_dt)))
+      return pccl::launch_reduce_two_level_lds(q, in_dt, out_dt, st);
+    if (forced == 3 || lds) return pccl::launch_reduce_flat_lds(q, in_dt, out_dt, st);
   }
   return pccl::launch_reduce(p, in_dt, out_dt, st);
 }

@@ -170,9 +170,10 @@ __device__ __forceinline__ float ordered_sum(const float* parked, int tn, bool f
   return acc;
 }
 
-// UNITS > 0 (chosen by the host): every tile is whole (nodes a multiple of TN), every slice is
-// whole (count a multiple of E) and every source starts on a 32-bit word, so no load needs a
-// check; a wave's share of a tile is then loaded, summed and chained in UNITS parts (below).
+// UNITS > 0 (chosen by the host): every source starts on a 32-bit word, so a whole tile of a whole
+// element slice needs no check on any load; a wave's share of such a tile is then loaded, summed
+// and chained in UNITS parts (below).  The nodes past the last whole tile, and the block of a
+// ragged last slice, take the plain loop.
 template <int IN, int OUT, int M, int NPT = lds_npt(M, narrow(IN)), int UNITS = 0>
 __global__ __launch_bounds__(kLdsBlock) void k_reduce2l_lds(ReduceProblem p) {
   constexpr int EPL = narrow(IN) ? 2 : 1;
@@ -199,135 +200,49 @@ __global__ __launch_bounds__(kLdsBlock) void k_reduce2l_lds(ReduceProblem p) {
   };
 
   float acc = 0.0f;
+  int k0 = 0;  // tiles [0, k0) are done, their ordered sums included
   if constexpr (M > 0 && UNITS > 0) {
-    // A wave's NPT nodes of a tile are loaded and summed in UNITS parts, and the loads of the NEXT
-    // tile's part are issued as soon as the registers of this tile's are free -- ahead of the
-    // barrier -- so a wave always has nearly a whole tile of loads in flight and the memory
-    // pipeline of the CU does not drain at a tile boundary (one 1024-thread block per CU: nothing
-    // else would fill such a gap).  Part u of all waves together is nodes [u*UT, (u+1)*UT) of the
-    // tile, so the ordered sum runs one part behind the loads and only the last part's is
-    // exposed.  Addresses are fetched two tiles ahead, so that the fetch is older than the loads
-    // it would otherwise wait behind (loads return in order).
-    static_assert(NPT % UNITS == 0, "whole parts");
-    constexpr int H = NPT / UNITS;  // nodes of a wave in one part
-    constexpr int UT = TN / UNITS;  // nodes of the tile in one part
-    // Lane l < NPT*M holds source (node, l % M), node = part (q / H), place wave*H + q % H in it,
-    // q = l / M.  No branch around the load and no use of its result here (either would make the
-    // wave wait for every load ahead of it): lanes past NPT*M repeat the last source, and the
-    // caller's own-slot override is applied by `resolve` when the addresses are used, a tile later.
-    const int l = lane < NPT * M ? lane : NPT * M - 1;
-    const int lq = l / M, lg = l % M;
-    const int lnode = (lq / H) * UT + wave * H + lq % H;
-    auto fetch = [&](int tile) -> uint64_t {
-      const int n = tile * TN + lnode;
-      if (p.ptrs != nullptr) return reinterpret_cast<uint64_t>(ld_pointer_lane(p.ptrs, (size_t)n * M + lg));
-      return reinterpret_cast<uint64_t>(p.base + (size_t)n * p.stride_n + (size_t)lg * p.stride_g);
-    };
-    auto resolve = [&](uint64_t a, int tile) -> uint64_t {
-      const int s = (tile * TN + lnode) * M + lg;
-      return (p.ptrs != nullptr && s == p.override_index) ? reinterpret_cast<uint64_t>(p.override_ptr) : a;
-    };
-    // part u of this wave's share: lanes (u*H + q)*M + g
-    auto issue = [&](float (&x)[H][MM][EPL], uint64_t a, int u) {
+    const int ntf = slice_full ? p.nodes / TN : 0;  // whole tiles; block-uniform
+    k0 = ntf;
+    if (ntf > 0) {
+      // A wave's NPT nodes of a tile are loaded and summed in UNITS parts, and the loads of the NEXT
+      // tile's part are issued as soon as the registers of this tile's are free -- ahead of the
+      // barrier -- so a wave always has nearly a whole tile of loads in flight and the memory
+      // pipeline of the CU does not drain at a tile boundary (one 1024-thread block per CU: nothing
+      // else would fill such a gap).  Part u of all waves together is nodes [u*UT, (u+1)*UT) of the
+      // tile, so the ordered sum runs one part behind the loads and only the last part's is
+      // exposed.  Addresses are fetched two tiles ahead, so that the fetch is older than the loads
+      // it would otherwise wait behind (loads return in order).
+      static_assert(NPT % UNITS == 0, "whole parts");
+      constexpr int H = NPT / UNITS;  // nodes of a wave in one part
+      constexpr int UT = TN / UNITS;  // nodes of the tile in one part
+      // Lane l < NPT*M holds source (node, l % M), node = part (q / H), place wave*H + q % H in it,
+      // q = l / M.  No branch around the load and no use of its result here (either would make the
+      // wave wait for every load ahead of it): lanes past NPT*M repeat the last source, and the
+      // caller's own-slot override is applied by `resolve` when the addresses are used, a tile later.
+      const int l = lane < NPT * M ? lane : NPT * M - 1;
+      const int lq = l / M, lg = l % M;
+      const int lnode = (lq / H) * UT + wave * H + lq % H;
+      auto fetch = [&](int tile) -> uint64_t {
+        const int n = tile * TN + lnode;
+        if (p.ptrs != nullptr) return reinterpret_cast<uint64_t>(ld_pointer_lane(p.ptrs, (size_t)n * M + lg));
+        return reinterpret_cast<uint64_t>(p.base + (size_t)n * p.stride_n + (size_t)lg * p.stride_g);
+      };
+      auto resolve = [&](uint64_t a, int tile) -> uint64_t {
+        const int s = (tile * TN + lnode) * M + lg;
+        return (p.ptrs != nullptr && s == p.override_index) ? reinterpret_cast<uint64_t>(p.override_ptr) : a;
+      };
+      // part u of this wave's share: lanes (u*H + q)*M + g
+      auto issue = [&](float (&x)[H][MM][EPL], uint64_t a, int u) {
 #pragma unroll
-      for (int q = 0; q < H; ++q)
-#pragma unroll
-        for (int g = 0; g < MM; ++g)
-          ld_word<IN, EPL, false>(lane_pointer(a, (u * H + q) * M + g), le, p.count, x[q][g]);
-    };
-    auto sum_park = [&](float* buf, const float (&x)[H][MM][EPL], int u) {
-#pragma unroll
-      for (int q = 0; q < H; ++q) {
-        float t[EPL];
-#pragma unroll
-        for (int e = 0; e < EPL; ++e) {
-          t[e] = x[q][0][e];
-#pragma unroll
-          for (int g = 1; g < MM; ++g) t[e] = t[e] + x[q][g][e];
-        }
-        park(buf, u * UT + wave * H + q, t);
-      }
-    };
-    // acc (+)= the UT parked partials of one element, ascending node order, 16 reads at a time
-    static_assert(UT % 16 == 0, "whole rounds of 16");
-    auto chain = [&](const float* part, bool first) {
-#pragma unroll
-      for (int j0 = 0; j0 < UT; j0 += 16) {
-        float v[16];
-#pragma unroll
-        for (int j = 0; j < 16; ++j) v[j] = part[(j0 + j) * E + threadIdx.x];
-#pragma unroll
-        for (int j = 0; j < 16; ++j) acc = (first && j0 + j == 0) ? v[j] : acc + v[j];
-      }
-    };
-    uint64_t nxt = ntiles > 1 ? fetch(1) : 0;
-    float x[UNITS][H][MM][EPL];
-    {
-      const uint64_t cur = resolve(fetch(0), 0);
-#pragma unroll
-      for (int u = 0; u < UNITS; ++u) issue(x[u], cur, u);
-    }
-    for (int k = 0; k + 1 < ntiles; ++k) {
-      float* buf = parked[k & 1];
-      const uint64_t nn = k + 2 < ntiles ? fetch(k + 2) : 0;
-      const uint64_t a = resolve(nxt, k + 1);
-#pragma unroll
-      for (int u = 0; u < UNITS; ++u) {
-        sum_park(buf, x[u], u);
-        issue(x[u], a, u);
-        __syncthreads();
-        if (threadIdx.x < E) chain(buf + u * UT * E, k == 0 && u == 0);
-      }
-      nxt = nn;
-    }
-    {
-      const int k = ntiles - 1;
-      float* buf = parked[k & 1];
-#pragma unroll
-      for (int u = 0; u < UNITS; ++u) {
-        sum_park(buf, x[u], u);
-        __syncthreads();
-        if (threadIdx.x < E) chain(buf + u * UT * E, k == 0 && u == 0);
-      }
-    }
-  } else if constexpr (M > 0) {
-    // lane l < NPT*M of wave w holds the address of source (tile*TN + w*NPT + l/M, l%M)
-    auto fetch = [&](int tile) -> uint64_t {
-      const int n = tile * TN + wave * NPT + lane / M;
-      return lane_src_fetch(p, n, lane % M, M, lane < NPT * M && n < p.nodes);
-    };
-    auto resolve = [&](uint64_t a, int tile) -> uint64_t {
-      const int n = tile * TN + wave * NPT + lane / M;
-      return lane_src_resolve(p, a, n, lane % M, M, lane < NPT * M && n < p.nodes);
-    };
-    uint64_t cur = resolve(fetch(0), 0);
-    for (int k = 0; k < ntiles; ++k) {
-      float* buf = parked[k & 1];
-      const uint64_t nxt = k + 1 < ntiles ? fetch(k + 1) : 0;  // resolved at the bottom of the loop
-      const int nvalid = min(NPT, max(0, p.nodes - (k * TN + wave * NPT)));  // wave-uniform
-      float x[NPT][MM][EPL];
-      const bool plain = nvalid == NPT && slice_full && !__any((int)(cur & 3));
-      if (plain) {
-        // the whole trip without a check: NPT*M loads issue back to back
-#pragma unroll
-        for (int q = 0; q < NPT; ++q)
+        for (int q = 0; q < H; ++q)
 #pragma unroll
           for (int g = 0; g < MM; ++g)
-            ld_word<IN, EPL, false>(lane_pointer(cur, q * M + g), le, p.count, x[q][g]);
-      } else {
+            ld_word<IN, EPL, false>(lane_pointer(a, (u * H + q) * M + g), le, p.count, x[q][g]);
+      };
+      auto sum_park = [&](float* buf, const float (&x)[H][MM][EPL], int u) {
 #pragma unroll
-        for (int q = 0; q < NPT; ++q)
-          if (q < nvalid) {
-#pragma unroll
-            for (int g = 0; g < MM; ++g)
-              ld_word<IN, EPL, true>(lane_pointer(cur, q * M + g), le, p.count, x[q][g]);
-          }
-      }
-      // ordered sum of the previous tile while this tile's loads are in flight
-      if (threadIdx.x < E && k > 0) acc = ordered_sum<E>(parked[(k - 1) & 1], TN, k == 1, acc);
-#pragma unroll
-      for (int q = 0; q < NPT; ++q)
-        if (q < nvalid) {
+        for (int q = 0; q < H; ++q) {
           float t[EPL];
 #pragma unroll
           for (int e = 0; e < EPL; ++e) {
@@ -335,10 +250,104 @@ __global__ __launch_bounds__(kLdsBlock) void k_reduce2l_lds(ReduceProblem p) {
 #pragma unroll
             for (int g = 1; g < MM; ++g) t[e] = t[e] + x[q][g][e];
           }
-          park(buf, wave * NPT + q, t);
+          park(buf, u * UT + wave * H + q, t);
         }
-      cur = resolve(nxt, k + 1);
-      __syncthreads();
+      };
+      // acc (+)= the UT parked partials of one element, ascending node order, 16 reads at a time
+      static_assert(UT % 16 == 0, "whole rounds of 16");
+      auto chain = [&](const float* part, bool first) {
+#pragma unroll
+        for (int j0 = 0; j0 < UT; j0 += 16) {
+          float v[16];
+#pragma unroll
+          for (int j = 0; j < 16; ++j) v[j] = part[(j0 + j) * E + threadIdx.x];
+#pragma unroll
+          for (int j = 0; j < 16; ++j) acc = (first && j0 + j == 0) ? v[j] : acc + v[j];
+        }
+      };
+      uint64_t nxt = ntf > 1 ? fetch(1) : 0;
+      float x[UNITS][H][MM][EPL];
+      {
+        const uint64_t cur = resolve(fetch(0), 0);
+#pragma unroll
+        for (int u = 0; u < UNITS; ++u) issue(x[u], cur, u);
+      }
+      for (int k = 0; k + 1 < ntf; ++k) {
+        float* buf = parked[k & 1];
+        const uint64_t nn = k + 2 < ntf ? fetch(k + 2) : 0;
+        const uint64_t a = resolve(nxt, k + 1);
+#pragma unroll
+        for (int u = 0; u < UNITS; ++u) {
+          sum_park(buf, x[u], u);
+          issue(x[u], a, u);
+          __syncthreads();
+          if (threadIdx.x < E) chain(buf + u * UT * E, k == 0 && u == 0);
+        }
+        nxt = nn;
+      }
+      {
+        const int k = ntf - 1;
+        float* buf = parked[k & 1];
+#pragma unroll
+        for (int u = 0; u < UNITS; ++u) {
+          sum_park(buf, x[u], u);
+          __syncthreads();
+          if (threadIdx.x < E) chain(buf + u * UT * E, k == 0 && u == 0);
+        }
+      }
+    }
+  }
+  if constexpr (M > 0) {
+    if (k0 < ntiles) {
+      // lane l < NPT*M of wave w holds the address of source (tile*TN + w*NPT + l/M, l%M)
+      auto fetch = [&](int tile) -> uint64_t {
+        const int n = tile * TN + wave * NPT + lane / M;
+        return lane_src_fetch(p, n, lane % M, M, lane < NPT * M && n < p.nodes);
+      };
+      auto resolve = [&](uint64_t a, int tile) -> uint64_t {
+        const int n = tile * TN + wave * NPT + lane / M;
+        return lane_src_resolve(p, a, n, lane % M, M, lane < NPT * M && n < p.nodes);
+      };
+      uint64_t cur = resolve(fetch(k0), k0);
+      for (int k = k0; k < ntiles; ++k) {
+        float* buf = parked[k & 1];
+        const uint64_t nxt = k + 1 < ntiles ? fetch(k + 1) : 0;  // resolved at the bottom of the loop
+        const int nvalid = min(NPT, max(0, p.nodes - (k * TN + wave * NPT)));  // wave-uniform
+        float x[NPT][MM][EPL];
+        const bool plain = nvalid == NPT && slice_full && !__any((int)(cur & 3));
+        if (plain) {
+          // the whole trip without a check: NPT*M loads issue back to back
+#pragma unroll
+          for (int q = 0; q < NPT; ++q)
+#pragma unroll
+            for (int g = 0; g < MM; ++g)
+              ld_word<IN, EPL, false>(lane_pointer(cur, q * M + g), le, p.count, x[q][g]);
+        } else {
+#pragma unroll
+          for (int q = 0; q < NPT; ++q)
+            if (q < nvalid) {
+#pragma unroll
+              for (int g = 0; g < MM; ++g)
+                ld_word<IN, EPL, true>(lane_pointer(cur, q * M + g), le, p.count, x[q][g]);
+            }
+        }
+        // ordered sum of the previous tile while this tile's loads are in flight
+        if (threadIdx.x < E && k > k0) acc = ordered_sum<E>(parked[(k - 1) & 1], TN, k == 1, acc);
+#pragma unroll
+        for (int q = 0; q < NPT; ++q)
+          if (q < nvalid) {
+            float t[EPL];
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) {
+              t[e] = x[q][0][e];
+#pragma unroll
+              for (int g = 1; g < MM; ++g) t[e] = t[e] + x[q][g][e];
+            }
+            park(buf, wave * NPT + q, t);
+          }
+        cur = resolve(nxt, k + 1);
+        __syncthreads();
+      }
     }
   } else {
     // any number of sources per node: one node per wave and tile, sources in batches of 8
@@ -369,7 +378,7 @@ __global__ __launch_bounds__(kLdsBlock) void k_reduce2l_lds(ReduceProblem p) {
   }
   if (threadIdx.x < E) {
     const int last = ntiles - 1;
-    if constexpr (!(M > 0 && UNITS > 0)) acc = ordered_sum<E>(parked[last & 1], p.nodes - last * TN, last == 0, acc);
+    if (k0 < ntiles) acc = ordered_sum<E>(parked[last & 1], p.nodes - last * TN, last == 0, acc);
     if (p.divisor != 0.0f) acc = acc / p.divisor;
     if (e0 + threadIdx.x < p.count)
       st_elem<OUT>(reinterpret_cast<char*>(p.dst), e0 + threadIdx.x, acc);
@@ -384,15 +393,15 @@ hipError_t launch_lds_m(const ReduceProblem& p, hipStream_t st) {
   if (p.nodes > (1 << 30) || (size_t)p.nodes * (size_t)p.gpus > ((size_t)1 << 30)) return hipErrorInvalidValue;
   unsigned gx, gz;
   if (!split_grid_xz(blocks, kLdsBlock, &gx, &gz)) return hipErrorInvalidValue;
-  // Whole tiles, whole slices and sources on 32-bit words (fp32 sources are by their type; 16-bit
-  // ones only when they are strided from an aligned base: a pointer array cannot be inspected
-  // here): the variant that loads, sums and chains a tile in two parts and keeps loads in flight
-  // across the tile boundary.  2048 x 64 KB of fp32: 23.35 us against 24.9 us back to back.
+  // Sources on 32-bit words (fp32 sources are by their type; 16-bit ones only when they are strided
+  // from an aligned base: a pointer array cannot be inspected here) and at least one whole tile of
+  // nodes: the variant that loads, sums and chains a whole tile in two parts and keeps loads in
+  // flight across tile boundaries.  2048 x 64 KB of fp32: 23.35 us against 24.9 us back to back.
   // PCCL_TWO_LEVEL_PIPE=0 keeps the plain loop (tests run both).
   auto piped_ok = [&](int npt) {
     const bool words = !narrow(IN) || (p.ptrs == nullptr && reinterpret_cast<uintptr_t>(p.base) % 4 == 0 &&
                                        p.stride_n % 4 == 0 && p.stride_g % 4 == 0);
-    return knobs().two_level_pipe && words && p.nodes % (kLdsWaves * npt) == 0 && p.count % E == 0;
+    return knobs().two_level_pipe && words && p.nodes >= kLdsWaves * npt && p.count >= (size_t)E;
   };
   const dim3 grid(gx, 1, gz), blk(kLdsBlock);
   if constexpr (M == 8 && !narrow(IN)) {
@@ -982,6 +991,23 @@ bool prefer_flat_lds(const ReduceProblem& p, int in_dt) {
   if (p.gpus != 1 || p.nodes <= 16) return false;
   if (src_bytes >= ((size_t)16 << 20)) return false;
   return !(src_bytes >= ((size_t)4 << 20) && p.nodes < 32);
+}
+
+bool prefer_two_level_for_flat(const ReduceProblem& p, int in_dt) {
+  // A flat sum is a two-level sum with one source per node, and on many SHORT sources the
+  // two-level LDS kernel's in-flight variant beats the flat LDS kernel, which drains its loads at
+  // every tile of 128 sources.  Measured, fp32 through a pointer array, flat LDS against this:
+  // 2048 / 1024 / 128 x 64 KB 33.7 / 18.6 / 4.7 against 22.1 / 12.4 / 4.0 us, 512 x 128 KB 16.3
+  // against 12.8, 256 x 256 KB 13.9 against 13.2; 128 x 256 KB 8.3 against 8.9 and longer
+  // sources within a few per cent either way; ragged shapes the same (2040 x 64 KB 33.6 against
+  // 24.0, 300 x 100 KB 10.4 against 9.3).  16-bit sources stay with the flat kernel, which parks
+  // two elements per 32-bit word where this one parks two floats (strided bf16: 2048 x 64 KB
+  // 36.8 against 36.2 us, 256 x 256 KB 13.2 against 16.4).
+  // (p as launch_flat hands it on: nodes = sources.)
+  if (narrow(in_dt) || p.gpus != 1 || !knobs().two_level_pipe) return false;
+  const size_t src_bytes = p.count * 4;
+  if (p.nodes < kLdsWaves * lds_npt(1, false)) return false;
+  return src_bytes <= ((size_t)128 << 10) || (src_bytes <= ((size_t)256 << 10) && p.nodes >= 256);
 }
 
 bool prefer_lds_two_level(const ReduceProblem& p, int in_dt) {

@@ -1,6 +1,7 @@
-"""The LDS-staged two-level reduction on shapes made of whole tiles and whole element slices, where
-the kernel keeps loads in flight across tile boundaries and chains half a tile behind them
-(PCCL_TWO_LEVEL_PIPE=0 keeps the plain loop): both forms against the oracle, bit for bit."""
+"""The LDS-staged two-level reduction where its whole tiles of whole element slices keep loads in
+flight across tile boundaries and chain half a tile behind them (the nodes past the last whole
+tile and a ragged last slice take the plain loop; PCCL_TWO_LEVEL_PIPE=0 keeps the plain loop
+throughout): both forms against the oracle, bit for bit."""
 import pytest
 import torch
 
@@ -33,13 +34,16 @@ def _sources(nsrc, count, dtype, seed):
     return arena, dev, cpu
 
 
-# nodes = whole tiles of 16 wavefronts x (nodes per wavefront: 8 for up to 8 fp32 sources per node,
-# 2 for 16), count = whole slices of 64 fp32
+# a tile = 16 wavefronts x (nodes per wavefront: 8 for up to 8 fp32 sources per node, 2 for 16), a slice =
+# 64 fp32: first shapes made of whole tiles and slices only, then the ragged ones
 @pytest.mark.parametrize("out_dt", [F32, BF16])
 @pytest.mark.parametrize("nodes,gpus,count,npt4", [
     (128, 1, 192, False), (256, 2, 128, False), (128, 4, 64, False), (256, 8, 256, False), (384, 8, 64, False),
-    (128, 8, 4096, False), (64, 8, 128, True), (192, 8, 64, True), (32, 16, 64, False), (96, 16, 128, False)])
-def test_two_level_ptrs_whole_tiles(pipe, monkeypatch, out_dt, nodes, gpus, count, npt4):
+    (128, 8, 4096, False), (64, 8, 128, True), (192, 8, 64, True), (32, 16, 64, False), (96, 16, 128, False),
+    # whole tiles followed by a partial one, a ragged last slice, fewer nodes than a tile, fewer elements than a slice
+    (133, 8, 64 * 3 + 7, False), (255, 2, 100, False), (257, 4, 64, False), (127, 8, 128, False), (300, 1, 5, False),
+    (70, 8, 200, True), (40, 16, 130, False)])
+def test_two_level_ptrs_shapes(pipe, monkeypatch, out_dt, nodes, gpus, count, npt4):
     print("case", pipe, out_dt, nodes, gpus, count, npt4, flush=True)
     monkeypatch.setenv("PCCL_FORCE_TWO_LEVEL_KERNEL", "lds")
     if npt4:
@@ -72,7 +76,8 @@ def test_two_level_ptrs_average(pipe, monkeypatch):
 # ones on 32-bit words qualify as well (tiles of 64 sources, slices of 128 elements)
 @pytest.mark.parametrize("in_dt,out_dt,nsrc,count,pad", [
     (F32, F32, 128, 128, 0), (F32, BF16, 256, 64, 64), (BF16, BF16, 64, 256, 0), (BF16, F32, 128, 128, 128),
-    (F16, F16, 192, 128, 0), (BF16, BF16, 64, 128, 1)])   # pad 1: rows start in mid-word, so the plain loop runs
+    (F16, F16, 192, 128, 0), (BF16, BF16, 64, 128, 1),   # pad 1: rows start in mid-word, so the plain loop runs
+    (F32, F32, 300, 77, 3), (BF16, BF16, 150, 300, 2)])
 def test_flat_strided_through_two_level_kernel(pipe, monkeypatch, in_dt, out_dt, nsrc, count, pad):
     print("case", pipe, in_dt, out_dt, nsrc, count, pad, flush=True)
     monkeypatch.setenv("PCCL_FORCE_FLAT_KERNEL", "two-level")
@@ -110,3 +115,18 @@ def test_phase2_own_slot_through_two_level_kernel(pipe, monkeypatch, my_node):
     assert same_bits(to_np(partial.view), want_p.reshape(-1))
     shard.check()
     partial.check()
+
+
+@pytest.mark.parametrize("nsrc,count", [(128, 16384), (2048, 1024), (300, 25600), (1000, 999), (256, 65536), (127, 4096)])
+def test_flat_ptrs_many_short_fp32_sources(pipe, nsrc, count):
+    """The kernel chooser sends flat sums of many short fp32 sources through this kernel (one source
+    per node): whatever it picks, the bits are the flat order's."""
+    print("case", pipe, nsrc, count, flush=True)
+    pccl.diag_reload_env()
+    arena, dev, cpu = _sources(nsrc, count, F32, seed=nsrc + count)
+    dst = Guarded(count, F32)
+    pccl.pccl_local_reduce_ptrs(dst.view, pccl.device_pointer_array(dev), count, F32)
+    torch.cuda.synchronize()
+    want = oracle.flat_reduce(cpu, oracle.F32)
+    assert same_bits(to_np(dst.view), want), first_diff(to_np(dst.view), want)
+    dst.check()
