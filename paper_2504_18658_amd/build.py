@@ -57,18 +57,87 @@ def is_stale():
     return built_id() != source_id()
 
 
+RESOURCES = os.path.join(HERE, "libpccl_local.resources.json")
+
+
+def _parse_resource_remarks(text):
+    """{kernel: {"vgpr", "scratch_bytes", "vgpr_spill", "sgpr_spill", "occupancy"}} from the compiler's
+    -Rpass-analysis=kernel-resource-usage remarks."""
+    import re
+    keys = {"VGPRs": "vgpr", "ScratchSize [bytes/lane]": "scratch_bytes", "VGPRs Spill": "vgpr_spill",
+            "SGPRs Spill": "sgpr_spill", "Occupancy [waves/SIMD]": "occupancy"}
+    res, cur = {}, None
+    for line in text.splitlines():
+        m = re.search(r"remark:\s+Function Name: (\S+)", line)
+        if m:
+            cur = res.setdefault(m.group(1), {})
+            continue
+        m = re.search(r"remark:\s+([A-Za-z][^:]*): (\d+) \[-Rpass-analysis", line)
+        if m and cur is not None and m.group(1) in keys:
+            cur[keys[m.group(1)]] = int(m.group(2))
+    return res
+
+
 def build(force=True, verbose=False):
-    """Compile every HIP source into one shared library.  Returns its path."""
+    """Compile every HIP source into one shared library.  Returns its path.
+
+    The compiler's per-kernel resource report is kept next to the library (RESOURCES), and a kernel
+    that spills vector registers to memory fails the build: every kernel here is bandwidth-bound, and a spill (a tile
+    body that no longer fits the 128 registers of a 1024-thread block, say) halves its speed without
+    changing a single result."""
     if not force and not is_stale():
         return LIB
+    import json
+    import sys
     tmp = LIB + ".tmp.%d" % os.getpid()
-    cmd = [hipcc(), *HIPCC_FLAGS, '-DPCCL_BUILD_ID="%s"' % source_id(),
+    sid = source_id()
+    cmd = [hipcc(), *HIPCC_FLAGS, "-Rpass-analysis=kernel-resource-usage", '-DPCCL_BUILD_ID="%s"' % sid,
            *[os.path.join(CSRC, s) for s in SOURCES], "-o", tmp]
     if verbose:
         print(" ".join(cmd), flush=True)
-    subprocess.check_call(cmd)
+    proc = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.PIPE)
+    err = proc.stderr.decode("utf-8", "replace")
+    quiet = []   # everything but the remarks (each is the remark line, the source line and a caret line)
+    lines = err.splitlines()
+    i = 0
+    while i < len(lines):
+        if "[-Rpass-analysis=kernel-resource-usage]" in lines[i]:
+            i += 1
+            while i < len(lines) and (lines[i].lstrip().startswith("|") or " | " in lines[i][:12]):
+                i += 1
+            continue
+        quiet.append(lines[i])
+        i += 1
+    if quiet:
+        sys.stderr.write("\n".join(quiet) + "\n")
+    if proc.returncode != 0:
+        if os.path.exists(tmp):
+            os.remove(tmp)
+        raise subprocess.CalledProcessError(proc.returncode, cmd)
+    res = _parse_resource_remarks(err)
+    # (scalar registers spilled into lanes of a vector register cost next to nothing and are not meant)
+    spilled = {k: v for k, v in res.items() if v.get("vgpr_spill", 0)}
+    if spilled:
+        os.remove(tmp)
+        raise RuntimeError("kernels that spill registers: %s" % ", ".join(
+            "%s (%d VGPRs, %d spilled)" % (k, v.get("vgpr", -1), v.get("vgpr_spill", 0)) for k, v in spilled.items()))
+    with open(RESOURCES + ".tmp", "w") as f:
+        json.dump({"build_id": sid, "kernels": res}, f, indent=0, sort_keys=True)
+    os.replace(RESOURCES + ".tmp", RESOURCES)
     os.replace(tmp, LIB)
     return LIB
+
+
+def resources():
+    """The resource report of the library on disk ({kernel: {...}}), or None when the report is missing
+    or belongs to another build."""
+    import json
+    try:
+        with open(RESOURCES) as f:
+            data = json.load(f)
+    except (OSError, ValueError):
+        return None
+    return data["kernels"] if data.get("build_id") == built_id() else None
 
 
 if __name__ == "__main__":

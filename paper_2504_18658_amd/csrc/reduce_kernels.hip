@@ -232,23 +232,34 @@ __global__ __launch_bounds__(kLdsBlock) void k_reduce2l_lds(ReduceProblem p) {
         const int s = (tile * TN + lnode) * M + lg;
         return (p.ptrs != nullptr && s == p.override_index) ? reinterpret_cast<uint64_t>(p.override_ptr) : a;
       };
-      // part u of this wave's share: lanes (u*H + q)*M + g
-      auto issue = [&](float (&x)[H][MM][EPL], uint64_t a, int u) {
+      // part u of this wave's share: lanes (u*H + q)*M + g.  The registers hold the raw words (two
+      // 16-bit elements each), unpacked when summed.
+      const size_t lane_byte = le * (narrow(IN) ? 2 : 4);
+      auto issue = [&](uint32_t (&x)[H][MM], uint64_t a, int u) {
 #pragma unroll
         for (int q = 0; q < H; ++q)
 #pragma unroll
-          for (int g = 0; g < MM; ++g)
-            ld_word<IN, EPL, false>(lane_pointer(a, (u * H + q) * M + g), le, p.count, x[q][g]);
+          for (int g = 0; g < MM; ++g) x[q][g] = ld_stream<uint32_t>(lane_pointer(a, (u * H + q) * M + g) + lane_byte);
       };
-      auto sum_park = [&](float* buf, const float (&x)[H][MM][EPL], int u) {
+      auto word = [&](uint32_t w, float* v) {
+        if constexpr (narrow(IN)) {
+          v[0] = lo16<IN>(w);
+          v[1] = hi16<IN>(w);
+        } else {
+          v[0] = __uint_as_float(w);
+        }
+      };
+      auto sum_park = [&](float* buf, const uint32_t (&x)[H][MM], int u) {
 #pragma unroll
         for (int q = 0; q < H; ++q) {
           float t[EPL];
+          word(x[q][0], t);
 #pragma unroll
-          for (int e = 0; e < EPL; ++e) {
-            t[e] = x[q][0][e];
+          for (int g = 1; g < MM; ++g) {
+            float v[EPL];
+            word(x[q][g], v);
 #pragma unroll
-            for (int g = 1; g < MM; ++g) t[e] = t[e] + x[q][g][e];
+            for (int e = 0; e < EPL; ++e) t[e] = t[e] + v[e];
           }
           park(buf, u * UT + wave * H + q, t);
         }
@@ -266,7 +277,7 @@ __global__ __launch_bounds__(kLdsBlock) void k_reduce2l_lds(ReduceProblem p) {
         }
       };
       uint64_t nxt = ntf > 1 ? fetch(1) : 0;
-      float x[UNITS][H][MM][EPL];
+      uint32_t x[UNITS][H][MM];
       {
         const uint64_t cur = resolve(fetch(0), 0);
 #pragma unroll
@@ -396,7 +407,7 @@ hipError_t launch_lds_m(const ReduceProblem& p, hipStream_t st) {
   // Sources on 32-bit words (fp32 sources are by their type; 16-bit ones only when they are strided
   // from an aligned base: a pointer array cannot be inspected here) and at least one whole tile of
   // nodes: the variant that loads, sums and chains a whole tile in two parts and keeps loads in
-  // flight across tile boundaries.  2048 x 64 KB of fp32: 23.35 us against 24.9 us back to back.
+  // flight across tile boundaries.  2048 x 64 KB of fp32: 23.25 us against 24.9 us back to back.
   // PCCL_TWO_LEVEL_PIPE=0 keeps the plain loop (tests run both).
   auto piped_ok = [&](int npt) {
     const bool words = !narrow(IN) || (p.ptrs == nullptr && reinterpret_cast<uintptr_t>(p.base) % 4 == 0 &&
@@ -404,21 +415,19 @@ hipError_t launch_lds_m(const ReduceProblem& p, hipStream_t st) {
     return knobs().two_level_pipe && words && p.nodes >= kLdsWaves * npt && p.count >= (size_t)E;
   };
   const dim3 grid(gx, 1, gz), blk(kLdsBlock);
-  if constexpr (M == 8 && !narrow(IN)) {
-    // 2048 ranks x 64 KB of fp32: eight nodes per wavefront and tile (64 loads in flight per lane, two
-    // barriers fewer) measured 24.5 us against 25.1 us with four; PCCL_TWO_LEVEL_NPT=4 keeps the four for A/B runs
-    if (knobs().two_level_npt != 4) {
-      if (piped_ok(8))
-        hipLaunchKernelGGL((k_reduce2l_lds<IN, OUT, M, 8, 2>), grid, blk, 0, st, p);
-      else
-        hipLaunchKernelGGL((k_reduce2l_lds<IN, OUT, M, 8>), grid, blk, 0, st, p);
-      return hipGetLastError();
-    }
-  }
   if constexpr (M > 0) {
     constexpr int NPT = lds_npt(M, narrow(IN));
     if (piped_ok(NPT)) {
       hipLaunchKernelGGL((k_reduce2l_lds<IN, OUT, M, NPT, 2>), grid, blk, 0, st, p);
+      return hipGetLastError();
+    }
+  }
+  if constexpr (M == 8 && !narrow(IN)) {
+    // the plain loop on 2048 ranks x 64 KB of fp32: eight nodes per wavefront and tile (64 loads in flight per
+    // lane, two barriers fewer) measured 24.5 us against 25.1 us with four; PCCL_TWO_LEVEL_NPT=4 keeps the four.
+    // (The in-flight variant above stays at four: 23.25 us, and with eight it does not fit the register file.)
+    if (knobs().two_level_npt != 4) {
+      hipLaunchKernelGGL((k_reduce2l_lds<IN, OUT, M, 8>), grid, blk, 0, st, p);
       return hipGetLastError();
     }
   }
