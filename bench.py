@@ -470,7 +470,8 @@ def size_sweep(dev, sizes_mb=(64, 128, 256)):
 def scale_sweep(dev):
     """Message size x node count (8 GPUs per node), the two axes of the paper's heat maps
     (Section IV-B, Section V-A: 16 MB - 1 GB, up to 2048 GCDs), through the four calls of an
-    all-reduce share: bf16, back-to-back launches over rotating buffer sets."""
+    all-reduce share (the other nodes' chunks received in buffers of their own): bf16, back-to-back
+    launches over rotating buffer sets."""
     gpus, dt = 8, torch.bfloat16
     out = []
     for mb in (16, 64, 256, 1024):
@@ -481,7 +482,8 @@ def scale_sweep(dev):
         for k in range(nsets):
             msgs = W.uniform_pm1(gpus * n, 800 + k, dev, dt).view(gpus, n)
             sets.append(dict(msgs=msgs, packed=torch.empty(n, dtype=dt, device=dev), out=torch.empty(n, dtype=dt, device=dev),
-                             partial=torch.empty(n // gpus, dtype=dt, device=dev), shard=torch.empty(n // (4 * gpus), dtype=dt, device=dev)))
+                             partial=torch.empty(n // gpus, dtype=dt, device=dev), shard=torch.empty(n // (4 * gpus), dtype=dt, device=dev),
+                             inter=W.uniform_pm1(n // gpus, 900 + k, dev, dt)))   # the chunks received from the other nodes
         for nodes in (4, 16, 64, 256):
             c = n // (nodes * gpus)
             share_bytes = (gpus + 1) * nodes * c * 2 + (nodes + 1) * c * 2
@@ -491,14 +493,18 @@ def scale_sweep(dev):
                 row[name + "_us"] = round(t[3] * 1e3, 2)
                 row[name + "_GBps"] = round(nbytes / (t[3] * 1e-3) / 1e9, 1)
 
+            for s in sets:
+                s["d_inter"] = pccl.device_pointer_array([s["inter"][j * c:(j + 1) * c] for j in range(nodes)])
             put("hier_pack", 2 * m, time_calls(
                 [lambda s=s: pccl.pccl_hier_pack(s["packed"], s["msgs"][0], nodes, gpus) for s in sets], trials=4 * nsets))
             put("reduce_scatter_local", share_bytes, time_calls(
-                [lambda s=s: pccl.pccl_reduce_scatter_local(s["shard"][:c], s["partial"], s["msgs"][0].view(gpus, nodes, c))
+                [lambda s=s: pccl.pccl_reduce_scatter_local(s["shard"][:c], s["partial"], s["msgs"][0].view(gpus, nodes, c),
+                                                            d_inter=s["d_inter"], my_node=nodes // 3)
                  for s in sets], trials=4 * nsets))
             put("reduce_scatter_local_unpacked", share_bytes, time_calls(
                 [lambda s=s: pccl.pccl_reduce_scatter_local_unpacked(s["shard"][:c], s["partial"], msgs=s["msgs"], nodes=nodes,
-                                                                     gpus_per_node=gpus, my_gpu=3) for s in sets], trials=4 * nsets))
+                                                                     gpus_per_node=gpus, my_gpu=3, d_inter=s["d_inter"],
+                                                                     my_node=nodes // 3) for s in sets], trials=4 * nsets))
             put("allgather_reassemble", 2 * m, time_calls(
                 [lambda s=s: pccl.pccl_allgather_reassemble(s["out"], src=s["msgs"][1], nodes=nodes, gpus_per_node=gpus)
                  for s in sets], trials=4 * nsets))
