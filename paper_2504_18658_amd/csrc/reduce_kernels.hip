@@ -170,10 +170,10 @@ __device__ __forceinline__ float ordered_sum(const float* parked, int tn, bool f
   return acc;
 }
 
-// UNITS > 0 (chosen by the host): every source starts on a 32-bit word, so a whole tile of a whole
-// element slice needs no check on any load; a wave's share of such a tile is then loaded, summed
-// and chained in UNITS parts (below).  The nodes past the last whole tile, and the block of a
-// ragged last slice, take the plain loop.
+// UNITS > 0 (chosen by the host): a whole tile of a whole element slice whose sources all start on
+// 32-bit words needs no check on any load; a wave's share of such a tile is loaded, summed and
+// chained in UNITS parts (below).  The nodes past the last whole tile, the block of a ragged last
+// slice, and everything from the first tile with a 16-bit source in mid-word on take the plain loop.
 template <int IN, int OUT, int M, int NPT = lds_npt(M, narrow(IN)), int UNITS = 0>
 __global__ __launch_bounds__(kLdsBlock) void k_reduce2l_lds(ReduceProblem p) {
   constexpr int EPL = narrow(IN) ? 2 : 1;
@@ -203,7 +203,6 @@ __global__ __launch_bounds__(kLdsBlock) void k_reduce2l_lds(ReduceProblem p) {
   int k0 = 0;  // tiles [0, k0) are done, their ordered sums included
   if constexpr (M > 0 && UNITS > 0) {
     const int ntf = slice_full ? p.nodes / TN : 0;  // whole tiles; block-uniform
-    k0 = ntf;
     if (ntf > 0) {
       // A wave's NPT nodes of a tile are loaded and summed in UNITS parts, and the loads of the NEXT
       // tile's part are issued as soon as the registers of this tile's are free -- ahead of the
@@ -276,36 +275,48 @@ __global__ __launch_bounds__(kLdsBlock) void k_reduce2l_lds(ReduceProblem p) {
           for (int j = 0; j < 16; ++j) acc = (first && j0 + j == 0) ? v[j] : acc + v[j];
         }
       };
+      // 16-bit sources may start in the middle of a 32-bit word, which only their addresses tell:
+      // the block votes on every tile's addresses before that tile's loads are issued (they arrive
+      // a tile ahead), and the first tile with such a source ends this loop: the plain loop takes
+      // it and the rest.  The vote is block-uniform, so every wavefront leaves at the same tile.
+      constexpr bool kVote = narrow(IN);
       uint64_t nxt = ntf > 1 ? fetch(1) : 0;
       uint32_t x[UNITS][H][MM];
-      {
-        const uint64_t cur = resolve(fetch(0), 0);
+      int npipe = ntf;  // whole tiles this loop takes
+      const uint64_t cur = resolve(fetch(0), 0);
+      if (kVote && __syncthreads_or((int)__any((int)(cur & 3)))) npipe = 0;
+      if (npipe > 0) {
 #pragma unroll
         for (int u = 0; u < UNITS; ++u) issue(x[u], cur, u);
-      }
-      for (int k = 0; k + 1 < ntf; ++k) {
-        float* buf = parked[k & 1];
-        const uint64_t nn = k + 2 < ntf ? fetch(k + 2) : 0;
-        const uint64_t a = resolve(nxt, k + 1);
+        for (int k = 0; k + 1 < npipe; ++k) {
+          float* buf = parked[k & 1];
+          const uint64_t nn = k + 2 < ntf ? fetch(k + 2) : 0;
+          const uint64_t a = resolve(nxt, k + 1);
+          if (kVote && __syncthreads_or((int)__any((int)(a & 3)))) {
+            npipe = k + 1;  // tile k, whose loads are in flight, is the last one here
+            break;
+          }
 #pragma unroll
-        for (int u = 0; u < UNITS; ++u) {
-          sum_park(buf, x[u], u);
-          issue(x[u], a, u);
-          __syncthreads();
-          if (threadIdx.x < E) chain(buf + u * UT * E, k == 0 && u == 0);
+          for (int u = 0; u < UNITS; ++u) {
+            sum_park(buf, x[u], u);
+            issue(x[u], a, u);
+            __syncthreads();
+            if (threadIdx.x < E) chain(buf + u * UT * E, k == 0 && u == 0);
+          }
+          nxt = nn;
         }
-        nxt = nn;
-      }
-      {
-        const int k = ntf - 1;
-        float* buf = parked[k & 1];
+        {
+          const int k = npipe - 1;
+          float* buf = parked[k & 1];
 #pragma unroll
-        for (int u = 0; u < UNITS; ++u) {
-          sum_park(buf, x[u], u);
-          __syncthreads();
-          if (threadIdx.x < E) chain(buf + u * UT * E, k == 0 && u == 0);
+          for (int u = 0; u < UNITS; ++u) {
+            sum_park(buf, x[u], u);
+            __syncthreads();
+            if (threadIdx.x < E) chain(buf + u * UT * E, k == 0 && u == 0);
+          }
         }
       }
+      k0 = npipe;
     }
   }
   if constexpr (M > 0) {
@@ -404,15 +415,12 @@ hipError_t launch_lds_m(const ReduceProblem& p, hipStream_t st) {
   if (p.nodes > (1 << 30) || (size_t)p.nodes * (size_t)p.gpus > ((size_t)1 << 30)) return hipErrorInvalidValue;
   unsigned gx, gz;
   if (!split_grid_xz(blocks, kLdsBlock, &gx, &gz)) return hipErrorInvalidValue;
-  // Sources on 32-bit words (fp32 sources are by their type; 16-bit ones only when they are strided
-  // from an aligned base: a pointer array cannot be inspected here) and at least one whole tile of
-  // nodes: the variant that loads, sums and chains a whole tile in two parts and keeps loads in
-  // flight across tile boundaries.  2048 x 64 KB of fp32: 23.25 us against 24.9 us back to back.
-  // PCCL_TWO_LEVEL_PIPE=0 keeps the plain loop (tests run both).
+  // At least one whole tile of nodes and one whole slice: the variant that loads, sums and chains a
+  // whole tile in two parts and keeps loads in flight across tile boundaries (16-bit sources that
+  // start in mid-word make it hand over to the plain loop, tile by tile).  2048 x 64 KB of fp32:
+  // 23.25 us against 24.9 us back to back.  PCCL_TWO_LEVEL_PIPE=0 keeps the plain loop (tests run both).
   auto piped_ok = [&](int npt) {
-    const bool words = !narrow(IN) || (p.ptrs == nullptr && reinterpret_cast<uintptr_t>(p.base) % 4 == 0 &&
-                                       p.stride_n % 4 == 0 && p.stride_g % 4 == 0);
-    return knobs().two_level_pipe && words && p.nodes >= kLdsWaves * npt && p.count >= (size_t)E;
+    return knobs().two_level_pipe && p.nodes >= kLdsWaves * npt && p.count >= (size_t)E;
   };
   const dim3 grid(gx, 1, gz), blk(kLdsBlock);
   if constexpr (M > 0) {

@@ -130,3 +130,46 @@ def test_flat_ptrs_many_short_fp32_sources(pipe, nsrc, count):
     want = oracle.flat_reduce(cpu, oracle.F32)
     assert same_bits(to_np(dst.view), want), first_diff(to_np(dst.view), want)
     dst.check()
+
+
+def _sources_some_mid_word(nsrc, count, dtype, seed, odd):
+    """As _sources, but the sources whose index is in `odd` start one 16-bit element into their slot:
+    in the middle of a 32-bit word."""
+    slot = count + 2
+    host = W.normal(nsrc * slot, seed, 1.0, "cpu", dtype)
+    arena = host.to(DEV)
+    order = W.shuffled_slot_order(nsrc, seed)
+    lo = [order[s] * slot + (1 if s in odd else 0) for s in range(nsrc)]
+    return arena, [arena[a:a + count] for a in lo], [to_np(host[a:a + count]) for a in lo]
+
+
+# tiles of 64 nodes for 16-bit sources: the block leaves the in-flight loop at the first tile that holds
+# a source in mid-word (tile 0: never enters it; none: never leaves it)
+@pytest.mark.parametrize("dtype", [BF16, F16])
+@pytest.mark.parametrize("odd", [(), (0,), (3,), (64 * 8 + 5,), (130 * 8,), (255 * 8 + 7,), (70 * 8, 200 * 8 + 1)])
+def test_two_level_ptrs_16_bit_sources_vote_on_alignment(pipe, monkeypatch, dtype, odd):
+    print("case", pipe, dtype, odd, flush=True)
+    monkeypatch.setenv("PCCL_FORCE_TWO_LEVEL_KERNEL", "lds")
+    pccl.diag_reload_env()
+    nodes, gpus, count = 256, 8, 256 + 128
+    arena, dev, cpu = _sources_some_mid_word(nodes * gpus, count, dtype, seed=len(odd) * 17 + 3, odd=set(odd))
+    dst = Guarded(count, dtype)
+    pccl.pccl_local_reduce_ptrs_two_level(dst.view, pccl.device_pointer_array(dev), nodes, gpus, count, dtype)
+    torch.cuda.synchronize()
+    want = oracle.two_level_reduce(cpu, nodes, gpus, ODT[dtype])
+    assert same_bits(to_np(dst.view), want), first_diff(to_np(dst.view), want)
+    dst.check()
+
+
+@pytest.mark.parametrize("odd", [(), (1,), (130,), (255,)])
+def test_flat_ptrs_16_bit_through_two_level_kernel(pipe, monkeypatch, odd):
+    monkeypatch.setenv("PCCL_FORCE_FLAT_KERNEL", "two-level")
+    pccl.diag_reload_env()
+    nsrc, count = 256, 512
+    arena, dev, cpu = _sources_some_mid_word(nsrc, count, BF16, seed=41 + len(odd), odd=set(odd))
+    dst = Guarded(count, BF16)
+    pccl.pccl_local_reduce_ptrs(dst.view, pccl.device_pointer_array(dev), count, BF16)
+    torch.cuda.synchronize()
+    want = oracle.flat_reduce(cpu, oracle.BF16)
+    assert same_bits(to_np(dst.view), want), first_diff(to_np(dst.view), want)
+    dst.check()
