@@ -132,7 +132,9 @@ constexpr int kLdsBatch = 8;  // sources per batch when the per-node count is no
 constexpr int lds_npt(int m, bool in_narrow) {
   if (m <= 0) return 1;
   int npt = 32 / m;
-  const int cap = in_narrow ? 4 : 8;
+  // 16-bit sources park two floats per word loaded: four nodes keep two blocks on a CU (64 KB each),
+  // except for one source per node, where eight are what keeps enough loads in flight
+  const int cap = (in_narrow && m > 1) ? 4 : 8;
   if (npt > cap) npt = cap;
   return npt < 1 ? 1 : npt;
 }
@@ -1017,13 +1019,16 @@ bool prefer_two_level_for_flat(const ReduceProblem& p, int in_dt) {
   // 2048 / 1024 / 128 x 64 KB 33.7 / 18.6 / 4.7 against 22.1 / 12.4 / 4.0 us, 512 x 128 KB 16.3
   // against 12.8, 256 x 256 KB 13.9 against 13.2; 128 x 256 KB 8.3 against 8.9 and longer
   // sources within a few per cent either way; ragged shapes the same (2040 x 64 KB 33.6 against
-  // 24.0, 300 x 100 KB 10.4 against 9.3).  16-bit sources stay with the flat kernel, which parks
+  // 24.0, 300 x 100 KB 10.4 against 9.3).  16-bit sources mostly stay with the flat kernel, which parks
   // two elements per 32-bit word where this one parks two floats (strided bf16: 2048 x 64 KB
-  // 36.8 against 36.2 us, 256 x 256 KB 13.2 against 16.4).
+  // 36.8 against 36.2 us, 256 x 256 KB 13.2 against 16.4) -- except up to 64 KB per source, where
+  // this one wins (bf16 through a pointer array: 2048 / 1024 / 128 x 64 KB 39.7 / 21.7 / 5.3 against
+  // 30.6 / 16.5 / 4.7 us, 256 x 32 KB 7.1 against 5.7; 512 x 128 KB 17.5 against 18.0).
   // (p as launch_flat hands it on: nodes = sources.)
-  if (narrow(in_dt) || p.gpus != 1 || !knobs().two_level_pipe) return false;
+  if (p.gpus != 1 || !knobs().two_level_pipe) return false;
+  if (p.nodes < kLdsWaves * lds_npt(1, narrow(in_dt))) return false;
+  if (narrow(in_dt)) return p.count * 2 <= ((size_t)64 << 10);
   const size_t src_bytes = p.count * 4;
-  if (p.nodes < kLdsWaves * lds_npt(1, false)) return false;
   return src_bytes <= ((size_t)128 << 10) || (src_bytes <= ((size_t)256 << 10) && p.nodes >= 256);
 }
 

@@ -117,17 +117,20 @@ def test_phase2_own_slot_through_two_level_kernel(pipe, monkeypatch, my_node):
     partial.check()
 
 
-@pytest.mark.parametrize("nsrc,count", [(128, 16384), (2048, 1024), (300, 25600), (1000, 999), (256, 65536), (127, 4096)])
-def test_flat_ptrs_many_short_fp32_sources(pipe, nsrc, count):
-    """The kernel chooser sends flat sums of many short fp32 sources through this kernel (one source
-    per node): whatever it picks, the bits are the flat order's."""
-    print("case", pipe, nsrc, count, flush=True)
+@pytest.mark.parametrize("dtype,nsrc,count,odd", [
+    (F32, 128, 16384, ()), (F32, 2048, 1024, ()), (F32, 300, 25600, ()), (F32, 1000, 999, ()), (F32, 256, 65536, ()),
+    (F32, 127, 4096, ()), (BF16, 128, 32768, ()), (BF16, 2048, 1024, ()), (BF16, 300, 2000, (290,)), (F16, 256, 16384, (7, 200)),
+    (BF16, 127, 4096, ()), (BF16, 512, 65536, ())])
+def test_flat_ptrs_many_short_sources(pipe, dtype, nsrc, count, odd):
+    """The kernel chooser sends flat sums of many short sources through this kernel (one source per
+    node): whatever it picks, the bits are the flat order's."""
+    print("case", pipe, dtype, nsrc, count, odd, flush=True)
     pccl.diag_reload_env()
-    arena, dev, cpu = _sources(nsrc, count, F32, seed=nsrc + count)
-    dst = Guarded(count, F32)
-    pccl.pccl_local_reduce_ptrs(dst.view, pccl.device_pointer_array(dev), count, F32)
+    arena, dev, cpu = _sources_some_mid_word(nsrc, count, dtype, seed=nsrc + count, odd=set(odd))
+    dst = Guarded(count, dtype)
+    pccl.pccl_local_reduce_ptrs(dst.view, pccl.device_pointer_array(dev), count, dtype)
     torch.cuda.synchronize()
-    want = oracle.flat_reduce(cpu, oracle.F32)
+    want = oracle.flat_reduce(cpu, ODT[dtype])
     assert same_bits(to_np(dst.view), want), first_diff(to_np(dst.view), want)
     dst.check()
 
