@@ -158,6 +158,34 @@ def test_one_launch_share_beyond_4gib():
         assert same_bits(to_np(partial.view(nodes, c)[:, sl]), want_p)
 
 
+def test_one_launch_share_from_rank_order_messages_beyond_4gib():
+    """pccl_reduce_scatter_local_unpacked with received chunks (both phases in one launch over the rows
+    of rank-order messages): 2 x 2 ranks with 2 GiB + 16 B chunks, so rows, messages and the own row's
+    offsets pass 2^32 bytes."""
+    nodes, gpus, my_node, my_gpu = 2, 2, 1, 1
+    c = (1 << 30) + 8                                      # bf16 elements per chunk
+    msgs = _rand(gpus * nodes * gpus * c, BF16, 43).view(gpus, nodes, gpus, c)   # [message][node][gpu][chunk]
+    inter = _rand(nodes * c, BF16, 44).view(nodes, c)
+    d_inter = pccl.device_pointer_array([inter[n] for n in range(nodes)])
+    shard = torch.empty(c, dtype=BF16, device=DEV)
+    partial = torch.empty(nodes * c, dtype=BF16, device=DEV)
+    pccl.pccl_reduce_scatter_local_unpacked(shard, partial, msgs=msgs.view(gpus, nodes * gpus * c), d_inter=d_inter,
+                                            nodes=nodes, gpus_per_node=gpus, my_node=my_node, my_gpu=my_gpu)
+    _sync()
+    pieces = msgs[:, :, my_gpu, :]                          # [message][node][chunk]
+    ref_partial = (pieces[0].float() + pieces[1].float()).to(BF16)
+    assert torch.equal(partial.view(torch.int16), ref_partial.view(torch.int16).reshape(-1))
+    ref_shard = (inter[0].float() + ref_partial[1].float()).to(BF16)
+    assert torch.equal(shard.view(torch.int16), ref_shard.view(torch.int16))
+    del ref_partial, ref_shard
+    for lo in (0, c // 2, c - 4096):
+        sl = slice(lo, lo + 4096)
+        want_s, want_p = oracle.reduce_scatter_local(to_np(pieces[:, :, sl]), my_node=my_node,
+                                                     inter=[to_np(inter[n, sl]) for n in range(nodes)])
+        assert same_bits(to_np(shard[sl]), want_s)
+        assert same_bits(to_np(partial.view(nodes, c)[:, sl]), want_p)
+
+
 def test_fused_tail_chunks_beyond_4gib():
     """pccl_phase2_reassemble_local with 4 GiB + 48 B chunks: tile indices, chunk offsets and the own
     chunk's reduction all beyond 2^32 bytes."""
