@@ -38,3 +38,26 @@ def test_thousand_thread_blocks_fit_the_register_file():
     lds = {k: v for k, v in rep.items() if "k_reduce2l_lds" in k or "k_flat_lds" in k}
     assert lds
     assert max(v["vgpr"] for v in lds.values()) <= 128
+
+
+def test_remark_parser_reads_the_compilers_format():
+    text = """
+step_kernels.hip:67:1: remark: Function Name: _Z3fooPf [-Rpass-analysis=kernel-resource-usage]
+   67 | __global__ void foo(float* p) {
+      | ^
+step_kernels.hip:67:1: remark:     TotalSGPRs: 22 [-Rpass-analysis=kernel-resource-usage]
+step_kernels.hip:67:1: remark:     VGPRs: 11 [-Rpass-analysis=kernel-resource-usage]
+step_kernels.hip:67:1: remark:     AGPRs: 0 [-Rpass-analysis=kernel-resource-usage]
+step_kernels.hip:67:1: remark:     ScratchSize [bytes/lane]: 160 [-Rpass-analysis=kernel-resource-usage]
+step_kernels.hip:67:1: remark:     Dynamic Stack: False [-Rpass-analysis=kernel-resource-usage]
+step_kernels.hip:67:1: remark:     Occupancy [waves/SIMD]: 4 [-Rpass-analysis=kernel-resource-usage]
+step_kernels.hip:67:1: remark:     SGPRs Spill: 3 [-Rpass-analysis=kernel-resource-usage]
+step_kernels.hip:67:1: remark:     VGPRs Spill: 40 [-Rpass-analysis=kernel-resource-usage]
+step_kernels.hip:90:1: remark: Function Name: _Z3barPf [-Rpass-analysis=kernel-resource-usage]
+step_kernels.hip:90:1: remark:     VGPRs: 7 [-Rpass-analysis=kernel-resource-usage]
+step_kernels.hip:90:1: remark:     ScratchSize [bytes/lane]: 0 [-Rpass-analysis=kernel-resource-usage]
+step_kernels.hip:90:1: remark:     VGPRs Spill: 0 [-Rpass-analysis=kernel-resource-usage]
+"""
+    rep = build._parse_resource_remarks(text)
+    assert rep["_Z3fooPf"] == {"vgpr": 11, "scratch_bytes": 160, "occupancy": 4, "sgpr_spill": 3, "vgpr_spill": 40}
+    assert rep["_Z3barPf"] == {"vgpr": 7, "scratch_bytes": 0, "vgpr_spill": 0}
